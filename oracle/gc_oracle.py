@@ -1,0 +1,228 @@
+"""fp64 CPU oracle for the Gradient Cache hot path (arXiv 2101.06983).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+HIP kernels are checked against.  Only tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py may import it; the product path never does.  It
+shares no code with the package under paper_2101_06983_amd/ and imports
+nothing from it.
+
+Everything is numpy float64.  Inputs that the GPU stores in bf16 or fp32 are
+widened exactly to float64 by the caller, so input quantisation is not part of
+the comparison.  The B x P score matrix is materialised on purpose: the method
+is exact (Sec. "Gradient Cache Technique", Step 3 and the Conclusion), so the
+oracle is the plain full-batch definition.
+
+Notation follows the paper: F = {f(s_i)} are the anchor (query) rows Q[B, d],
+G = {g(t_j)} the target (passage) rows P[P, d], r_i = pos_idx[i] the index of
+the related target of anchor i, tau the temperature.
+
+Every function is pinned by tests/test_oracle_pins.py against closed forms,
+invariants, central finite differences, brute-force enumeration and the
+torch.nn.functional.cross_entropy / autograd library routine; none is
+"parity unpinned".
+"""
+import numpy as np
+from scipy.special import erf
+
+__all__ = [
+    "loss_and_rep_grad", "ntxent", "mlp_forward", "mlp_backward",
+    "mlp_fullbatch_grad", "mlp_chunked_grad", "mlp_accumulation_grad",
+]
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False):
+    """Contrastive loss (Eq. 1) and its representation gradients (Eq. 4-7).
+
+    q: [B, d] anchors f(s_i); p: [P, d] targets g(t_j); pos_idx: [B] ints r_i.
+    Logits are s_ij = (scale / temp) * <q_i, p_j>  (Eq. 1 with the 1/tau kept;
+    `scale` is an extra multiplier on the dot product, 1 in the paper).
+    mask_self: s_ii = -inf (needs B == P), used by the NT-Xent variation.
+
+    Returns dict with
+      loss      Eq. 1, mean over the B anchors
+      lse       [B]  log sum_j exp(s_ij)
+      pos_logit [B]  s_{i, r_i}
+      argmax    [B]  smallest j attaining max_j s_ij
+      dq        [B, d]  dL/df(s_i), Eq. 5 (with the factor scale/temp)
+      dp        [P, d]  dL/dg(t_j), Eq. 6 with eps_j = sum of f(s_k) over every
+                        k that has r_k = j (Eq. 7; several anchors may share one
+                        positive, none gives eps_j = 0)
+    """
+    q = _f64(q)
+    p = _f64(p)
+    r = np.asarray(pos_idx, dtype=np.int64)
+    B, d = q.shape
+    P, d2 = p.shape
+    assert d == d2 and r.shape == (B,)
+    assert np.all((r >= 0) & (r < P))
+    alpha = float(scale) / float(temp)
+
+    # scores: s_ij = alpha * f(s_i)^T g(t_j)
+    s = alpha * (q @ p.T)
+    if mask_self:
+        assert B == P and P >= 2
+        s[np.arange(B), np.arange(B)] = -np.inf
+
+    # Eq. 4: p_ij = exp(s_ij) / sum_t exp(s_it), computed through the row max
+    m = s.max(axis=1)
+    e = np.exp(s - m[:, None])
+    lse = m + np.log(e.sum(axis=1))
+    argmax = np.argmax(s, axis=1)          # first occurrence = smallest index
+    pos_logit = s[np.arange(B), r]
+
+    # Eq. 1
+    loss = np.sum(lse - pos_logit) / B
+
+    # g_ij = p_ij - [j == r_i]
+    g = np.exp(s - lse[:, None])
+    g[np.arange(B), r] -= 1.0
+
+    # Eq. 5:  dL/df(s_i) = -(1/|S|) (g(t_{r_i}) - sum_j p_ij g(t_j))      (* alpha)
+    dq = (alpha / B) * (g @ p)
+    # Eq. 6:  dL/dg(t_j) = -(1/|S|) (eps_j - sum_i p_ij f(s_i))           (* alpha)
+    dp = (alpha / B) * (g.T @ q)
+    return dict(loss=float(loss), lse=lse, pos_logit=pos_logit,
+                argmax=argmax.astype(np.int64), dq=dq, dp=dp)
+
+
+def ntxent(z, temp):
+    """NT-Xent over 2N views (the loss variation named in Sec. Related Work /
+    Step 2's remark that other contrastive losses are supported).
+
+    z: [2N, d], rows already L2-normalised by the caller (normalisation is not
+    part of the path).  Views 2k and 2k+1 are a positive pair.  Each view is an
+    anchor against all other views (self-similarity removed); the loss is the
+    mean over all 2N anchors, which averages both directions of every pair.
+    Returns dict(loss, dz, lse) with dz = dL/dz: every row is both an anchor
+    and a target, so its gradient is the sum of Eq. 5 and Eq. 6.
+    """
+    z = _f64(z)
+    n = z.shape[0]
+    assert n % 2 == 0 and n >= 2
+    r = np.arange(n) ^ 1
+    out = loss_and_rep_grad(z, z, r, scale=1.0, temp=temp, mask_self=True)
+    return dict(loss=out["loss"], dz=out["dq"] + out["dp"], lse=out["lse"])
+
+
+# ---------------------------------------------------------------------------
+# Stand-in encoder: y = GELU(x W1 + b1) W2 + b2 (exact erf GELU), one parameter
+# set shared by f and g (Theta = Lambda), so Eq. 2 and Eq. 3 add up.
+# params = dict(W1 [din, dh], b1 [dh], W2 [dh, dout], b2 [dout])
+# ---------------------------------------------------------------------------
+def _gelu(h):
+    return 0.5 * h * (1.0 + erf(h / np.sqrt(2.0)))
+
+
+def _gelu_prime(h):
+    # d/dh [h Phi(h)] = Phi(h) + h phi(h)
+    return 0.5 * (1.0 + erf(h / np.sqrt(2.0))) + h * np.exp(-0.5 * h * h) / np.sqrt(2.0 * np.pi)
+
+
+def _params64(params):
+    return {k: _f64(params[k]) for k in ("W1", "b1", "W2", "b2")}
+
+
+def mlp_forward(x, params, keep=False):
+    """Encoder forward.  keep=False is the graph-less forward of Step 1."""
+    w = _params64(params)
+    x = _f64(x)
+    h = x @ w["W1"] + w["b1"]
+    a = _gelu(h)
+    y = a @ w["W2"] + w["b2"]
+    if keep:
+        return y, h, a
+    return y
+
+
+def mlp_backward(x, params, upstream):
+    """Parameter gradient of <f(x), upstream> for one (sub-)batch: the inner sum
+    of Eq. 8 / Eq. 9 with u_i (v_i) = rows of `upstream`."""
+    w = _params64(params)
+    x = _f64(x)
+    u = _f64(upstream)
+    _, h, a = mlp_forward(x, w, keep=True)
+    dW2 = a.T @ u
+    db2 = u.sum(axis=0)
+    da = u @ w["W2"].T
+    dh = da * _gelu_prime(h)
+    dW1 = x.T @ dh
+    db1 = dh.sum(axis=0)
+    return dict(W1=dW1, b1=db1, W2=dW2, b2=db2)
+
+
+def _add(acc, g):
+    for k in acc:
+        acc[k] = acc[k] + g[k]
+    return acc
+
+
+def _zeros_like_params(params):
+    return {k: np.zeros_like(_f64(params[k])) for k in ("W1", "b1", "W2", "b2")}
+
+
+def mlp_fullbatch_grad(xq, xp, pos_idx, params, scale=1.0, temp=1.0):
+    """Direct large-batch update (Eq. 2-3): encode everything, loss, backprop
+    all B + P rows at once."""
+    fq = mlp_forward(xq, params)
+    gp = mlp_forward(xp, params)
+    out = loss_and_rep_grad(fq, gp, pos_idx, scale, temp)
+    grads = _zeros_like_params(params)
+    _add(grads, mlp_backward(xq, params, out["dq"]))
+    _add(grads, mlp_backward(xp, params, out["dp"]))
+    return dict(loss=out["loss"], grads=grads, dq=out["dq"], dp=out["dp"], q=fq, p=gp)
+
+
+def _chunks(n, size):
+    return [(a, min(a + size, n)) for a in range(0, n, size)]
+
+
+def mlp_chunked_grad(xq, xp, pos_idx, params, chunk_q, chunk_p, scale=1.0, temp=1.0):
+    """Gradient Cache, Steps 1-3: graph-less forward per sub-batch, loss and
+    representation-gradient cache on the stored representations, then per
+    sub-batch re-encode and backprop of the cached rows (Eq. 8-9).  Sub-batches
+    are taken in index order; the last one may be short."""
+    xq = _f64(xq)
+    xp = _f64(xp)
+    # Step 1
+    fq = np.concatenate([mlp_forward(xq[a:b], params) for a, b in _chunks(len(xq), chunk_q)])
+    gp = np.concatenate([mlp_forward(xp[a:b], params) for a, b in _chunks(len(xp), chunk_p)])
+    # Step 2
+    out = loss_and_rep_grad(fq, gp, pos_idx, scale, temp)
+    u, v = out["dq"], out["dp"]          # the Representation Gradient Cache
+    # Step 3
+    grads = _zeros_like_params(params)
+    for a, b in _chunks(len(xq), chunk_q):
+        _add(grads, mlp_backward(xq[a:b], params, u[a:b]))
+    for a, b in _chunks(len(xp), chunk_p):
+        _add(grads, mlp_backward(xp[a:b], params, v[a:b]))
+    return dict(loss=out["loss"], grads=grads, dq=u, dp=v, q=fq, p=gp)
+
+
+def mlp_accumulation_grad(xq, xp, pos_idx, params, n_chunks, scale=1.0, temp=1.0):
+    """Plain gradient accumulation (the paper's "Accumulation" system): each of
+    n_chunks sub-batches sees only its own targets as negatives.  Used as a
+    negative control: it must NOT equal the full-batch gradient (Introduction;
+    the remark under Eq. 7).  Requires the layout r_i = (P/B) * i so that a
+    contiguous split keeps every positive inside its chunk."""
+    xq = _f64(xq)
+    xp = _f64(xp)
+    B, P = len(xq), len(xp)
+    assert B % n_chunks == 0 and P % B == 0
+    k = P // B
+    r = np.asarray(pos_idx)
+    assert np.array_equal(r, k * np.arange(B))
+    cb = B // n_chunks
+    grads = _zeros_like_params(params)
+    loss = 0.0
+    for c in range(n_chunks):
+        qs = slice(c * cb, (c + 1) * cb)
+        ps = slice(c * cb * k, (c + 1) * cb * k)
+        sub = mlp_fullbatch_grad(xq[qs], xp[ps], k * np.arange(cb), params, scale, temp)
+        loss += sub["loss"] / n_chunks
+        for key in grads:
+            grads[key] = grads[key] + sub["grads"][key] / n_chunks
+    return dict(loss=loss, grads=grads)
