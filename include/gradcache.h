@@ -1,0 +1,172 @@
+/*
+ * gradcache.h - C ABI of the MI355X (gfx950) Gradient Cache hot path.
+ *
+ * The library computes, for anchor representations Q[B,d] (the paper's
+ * f(s_i)), target representations P[P,d] (g(t_j)) and positive indices r_i,
+ * the full-batch in-batch-negative contrastive loss (Eq. 1) and its
+ * representation gradients dL/dQ, dL/dP (Eq. 4-7): the "Representation
+ * Gradient Cache" of Step 2.  It also runs the sub-batch steps around it for a
+ * stand-in two-layer MLP encoder: the graph-less forward (Step 1) and the
+ * per-sub-batch re-encode + backward of the cached rows (Step 3, Eq. 8-9).
+ * The B x P score matrix is never written to device memory.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers unless marked "host".  Matrices
+ *     are row-major and contiguous (leading dimension = number of columns).
+ *   - The caller owns every buffer, the workspace included; the library frees
+ *     nothing the caller passed.  Entry points that take no workspace argument
+ *     use a per-device buffer the library allocates with hipMalloc on first use
+ *     and grows on demand; two such calls that overlap in time on one device
+ *     race on it - use the *_ex forms with your own workspace for that.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  A
+ *     call only enqueues work and returns; outputs are valid once the stream
+ *     has been synchronised.  No call synchronises the device, except
+ *     gc_check_async_error.
+ *   - Return value: GC_OK or a negative gc_status.  All argument checks are
+ *     made on the host before the first HIP call, so a bad call enqueues
+ *     nothing.  pos_idx values cannot be checked on the host: a value outside
+ *     [0, P) makes the kernels set loss to NaN and raise the device error word
+ *     that gc_check_async_error reads.
+ *   - loss, dq, dp, dz, lse, argmax, y are overwritten; gc_mlp_grads buffers are
+ *     accumulated into (+=).
+ *   - Same inputs give bit-identical outputs from run to run (no atomics, fixed
+ *     reduction order).
+ */
+#ifndef GRADCACHE_H
+#define GRADCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GC_OK = 0,
+  GC_ERR_NULL = -1,        /* a required pointer is NULL */
+  GC_ERR_SHAPE = -2,       /* a size is <= 0 / too large, or scale/temp is not a positive finite number */
+  GC_ERR_UNSUPPORTED = -3, /* dtype, flag or shape combination not implemented */
+  GC_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or smaller than the *_workspace_bytes value */
+  GC_ERR_POS_IDX = -5,     /* reported by gc_check_async_error: some pos_idx[i] was outside [0, P) */
+  GC_ERR_HIP = -6          /* a HIP runtime call failed (launch, allocation) */
+} gc_status;
+
+typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
+
+/* flags of gc_loss_and_rep_grad_ex */
+#define GC_MASK_SELF 1u /* s_ii = -inf (needs B == P >= 2): an anchor is never its own target */
+
+/* Text for a gc_status value (host; static storage, never NULL). */
+const char* gc_strerror(int status);
+
+/* Bytes of workspace gc_loss_and_rep_grad_ex needs for this shape (host, pure).
+ * Holds per-row softmax statistics and the split partial sums of dq and dp:
+ * O((B + P) * d), never O(B * P) (Sec. "Gradient Cache Technique": the cache is
+ * (|S| d + |T| d) numbers).  Returns 0 for an invalid shape. */
+size_t gc_workspace_bytes(int B, int P, int d, gc_dtype dt);
+
+/*
+ * Loss and representation gradients (Step 2; Eq. 1, 4, 5, 6, 7).
+ *   q       [B,d]  anchors, bf16 (or float for _f32)
+ *   p       [P,d]  targets, same type
+ *   pos_idx [B]    int32, r_i in [0, P); several anchors may share one target
+ *   logits  s_ij = (scale / temp) * <q_i, p_j>
+ *   loss    [1]    float: (1/B) sum_i (logsumexp_j s_ij - s_{i,r_i})
+ *   dq      [B,d]  float: (scale/(temp B)) sum_j (softmax_j(s_i.) - [j = r_i]) p_j
+ *   dp      [P,d]  float: (scale/(temp B)) sum_i (softmax_j(s_i.) - [j = r_i]) q_i
+ * Any B, P >= 1 and d >= 1 are accepted (ragged sizes are masked); the MFMA
+ * kernels serve bf16 with d a multiple of 128 up to 768, other cases take a
+ * slower general kernel.  Errors: GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_HIP.
+ */
+int gc_loss_and_rep_grad_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                              float scale, float temp, float* loss, float* dq, float* dp, void* stream);
+int gc_loss_and_rep_grad_f32(const float* q, const float* p, const int32_t* pos_idx, int B, int P, int d,
+                             float scale, float temp, float* loss, float* dq, float* dp, void* stream);
+
+/*
+ * Extended form of the same computation.
+ *   dt         type of q and p
+ *   flags      0 or GC_MASK_SELF
+ *   loss, dq, dp, lse, argmax   each may be NULL (not produced).  lse[B] float is
+ *              logsumexp_j s_ij; argmax[B] int32 is the smallest j that attains
+ *              max_j s_ij in the kernel's fp32 scores.
+ *   workspace  device, 256-byte aligned, at least gc_workspace_bytes(B,P,d,dt)
+ */
+int gc_loss_and_rep_grad_ex(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                            float scale, float temp, unsigned flags, float* loss, float* dq, float* dp, float* lse,
+                            int32_t* argmax, void* workspace, size_t workspace_bytes, void* stream);
+
+/* After the stream has been synchronised by the caller: copies the device error
+ * word of `workspace` to the host (a blocking 4-byte copy) and returns GC_OK or
+ * GC_ERR_POS_IDX.  workspace == NULL checks the library's own per-device buffer. */
+int gc_check_async_error(const void* workspace);
+
+/*
+ * NT-Xent over n_views = 2N views (a loss variation in the sense of Step 2's
+ * remark; SimCLR is cited in Related Work): z[n_views,d] bf16, rows already
+ * L2-normalised; views 2k and 2k+1 are positives of each other; logits
+ * <z_i,z_j>/temp with the self-similarity removed; loss = mean over all n_views
+ * anchors; dz[n_views,d] float = gradient w.r.t. z (anchor part + target part).
+ * workspace: gc_ntxent_workspace_bytes(n_views, d).
+ */
+size_t gc_ntxent_workspace_bytes(int n_views, int d);
+int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, float* loss, float* dz,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stand-in encoder  y = GELU(x W1 + b1) W2 + b2  (exact erf GELU), bf16 storage,
+ * fp32 accumulation.  W1[din,dh], b1[dh], W2[dh,dout], b2[dout], all device bf16.
+ * din, dh, dout must be multiples of 64.
+ */
+typedef struct {
+  const void* W1;
+  const void* b1;
+  const void* W2;
+  const void* b2;
+  int din, dh, dout;
+} gc_mlp_params;
+
+/* fp32 parameter-gradient accumulators, same shapes as the parameters (device). */
+typedef struct {
+  float* dW1;
+  float* db1;
+  float* dW2;
+  float* db2;
+} gc_mlp_grads;
+
+/* Step 1 for one sub-batch: y[rows,dout] bf16 = encoder(x[rows,din]); no
+ * activations are kept.  workspace: gc_mlp_workspace_bytes(rows, w). */
+size_t gc_mlp_workspace_bytes(int rows, const gc_mlp_params* w);
+int gc_mlp_forward_nograd_bf16(const void* x, int rows, const gc_mlp_params* w, void* y, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/* Step 3 for one sub-batch (the inner sum of Eq. 8 / Eq. 9): re-encodes
+ * x_chunk[rows,din] keeping the activations, then back-propagates
+ * cached_grad_rows[rows,dout] (float: the sub-batch's rows of dq or dp) and adds
+ * the parameter gradients into acc.  workspace: gc_mlp_workspace_bytes(rows, w). */
+int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp_params* w,
+                                     const float* cached_grad_rows, const gc_mlp_grads* acc, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
+/*
+ * One whole Gradient Cache step on one GPU (Steps 1-3) with the shared stand-in
+ * encoder: sub-batches of chunk_q anchors / chunk_p targets in index order (the
+ * last one may be short); graph-less forward of every sub-batch, loss and
+ * representation-gradient cache, then per-sub-batch surrogate backward.
+ *   x_q [B,din], x_p [P,din] bf16; pos_idx [B] int32
+ *   loss [1] float (overwritten); grads accumulated (+=): zero them before the call
+ *   q_rep [B,dout], p_rep [P,dout] bf16 and dq [B,dout], dp [P,dout] float:
+ *     optional outputs (NULL = kept in the workspace only)
+ * workspace: gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, w).
+ */
+size_t gc_step_mlp_workspace_bytes(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w);
+int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32_t* pos_idx, int chunk_q,
+                     int chunk_p, const gc_mlp_params* w, float scale, float temp, float* loss,
+                     const gc_mlp_grads* grads, void* q_rep, void* p_rep, float* dq, float* dp, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRADCACHE_H */

@@ -1,0 +1,282 @@
+"""ctypes binding of libgradcache.so: same names as include/gradcache.h.
+
+Argument marshalling only: torch supplies device buffers and the current HIP
+stream, every step of the path runs inside the library's kernels.  There is no
+fallback: if the library has not been built, or a call fails, an error is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgradcache.so")
+
+GC_OK = 0
+GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_POS_IDX, GC_ERR_HIP = -1, -2, -3, -4, -5, -6
+GC_F32, GC_BF16 = 0, 1
+GC_MASK_SELF = 1
+
+EXPORTS = [
+    "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",
+    "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
+    "gc_ntxent_loss_and_grad_bf16", "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
+    "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
+]
+
+
+class GradCacheError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+class gc_mlp_params(ctypes.Structure):
+    _fields_ = [("W1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+                ("din", ctypes.c_int), ("dh", ctypes.c_int), ("dout", ctypes.c_int)]
+
+
+class gc_mlp_grads(ctypes.Structure):
+    _fields_ = [("dW1", ctypes.c_void_p), ("db1", ctypes.c_void_p), ("dW2", ctypes.c_void_p), ("db2", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Loads the built library (raises if it is missing: build it with
+    `python -m paper_2101_06983_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libgradcache.so is not built (%s); run python -m paper_2101_06983_amd.build" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.gc_strerror.restype = ctypes.c_char_p
+    lib.gc_strerror.argtypes = [ci]
+    lib.gc_workspace_bytes.restype = sz
+    lib.gc_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    for name in ("gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [vp, vp, vp, ci, ci, ci, cf, cf, vp, vp, vp, vp]
+    lib.gc_loss_and_rep_grad_ex.restype = ci
+    lib.gc_loss_and_rep_grad_ex.argtypes = [ci, vp, vp, vp, ci, ci, ci, cf, cf, ctypes.c_uint, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.gc_check_async_error.restype = ci
+    lib.gc_check_async_error.argtypes = [vp]
+    lib.gc_ntxent_workspace_bytes.restype = sz
+    lib.gc_ntxent_workspace_bytes.argtypes = [ci, ci]
+    lib.gc_ntxent_loss_and_grad_bf16.restype = ci
+    lib.gc_ntxent_loss_and_grad_bf16.argtypes = [vp, ci, ci, cf, vp, vp, vp, sz, vp]
+    pp, pg = ctypes.POINTER(gc_mlp_params), ctypes.POINTER(gc_mlp_grads)
+    lib.gc_mlp_workspace_bytes.restype = sz
+    lib.gc_mlp_workspace_bytes.argtypes = [ci, pp]
+    lib.gc_mlp_forward_nograd_bf16.restype = ci
+    lib.gc_mlp_forward_nograd_bf16.argtypes = [vp, ci, pp, vp, vp, sz, vp]
+    lib.gc_chunk_surrogate_backward_bf16.restype = ci
+    lib.gc_chunk_surrogate_backward_bf16.argtypes = [vp, ci, pp, vp, pg, vp, sz, vp]
+    lib.gc_step_mlp_workspace_bytes.restype = sz
+    lib.gc_step_mlp_workspace_bytes.argtypes = [ci, ci, ci, ci, pp]
+    lib.gc_step_mlp_bf16.restype = ci
+    lib.gc_step_mlp_bf16.argtypes = [vp, ci, vp, ci, vp, ci, ci, pp, cf, cf, vp, pg, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def strerror(status):
+    return load().gc_strerror(int(status)).decode()
+
+
+def _check(rc, where):
+    if rc != GC_OK:
+        raise GradCacheError(rc, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_contig(t, dtype, what):
+    if t.dtype != dtype or not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous %s device tensor" % (what, dtype))
+    return t
+
+
+def alloc_workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256) + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_ptr(ws):
+    base = ws.data_ptr()
+    aligned = (base + 255) // 256 * 256
+    return ctypes.c_void_p(aligned), ws.numel() - (aligned - base)
+
+
+def gc_workspace_bytes(B, P, d, dt):
+    return load().gc_workspace_bytes(B, P, d, dt)
+
+
+def _simple(fn_name, dtype, q, p, pos_idx, scale, temp, stream):
+    lib = load()
+    _dev_contig(q, dtype, "q"); _dev_contig(p, dtype, "p"); _dev_contig(pos_idx, torch.int32, "pos_idx")
+    B, d = q.shape
+    P = p.shape[0]
+    loss = torch.empty(1, dtype=torch.float32, device=q.device)
+    dq = torch.empty(B, d, dtype=torch.float32, device=q.device)
+    dp = torch.empty(P, d, dtype=torch.float32, device=q.device)
+    rc = getattr(lib, fn_name)(_ptr(q), _ptr(p), _ptr(pos_idx), B, P, d, scale, temp, _ptr(loss), _ptr(dq), _ptr(dp),
+                               _stream(stream))
+    _check(rc, fn_name)
+    return loss, dq, dp
+
+
+def gc_loss_and_rep_grad_bf16(q, p, pos_idx, scale=1.0, temp=1.0, stream=None):
+    return _simple("gc_loss_and_rep_grad_bf16", torch.bfloat16, q, p, pos_idx, scale, temp, stream)
+
+
+def gc_loss_and_rep_grad_f32(q, p, pos_idx, scale=1.0, temp=1.0, stream=None):
+    return _simple("gc_loss_and_rep_grad_f32", torch.float32, q, p, pos_idx, scale, temp, stream)
+
+
+def gc_loss_and_rep_grad_ex(q, p, pos_idx, scale=1.0, temp=1.0, flags=0, want=("loss", "dq", "dp", "lse", "argmax"),
+                            workspace=None, out=None, stream=None):
+    """Returns a dict of the requested outputs (+ 'workspace').  `out` may hold
+    preallocated output tensors to write into."""
+    lib = load()
+    if q.dtype == torch.bfloat16:
+        dt = GC_BF16
+    elif q.dtype == torch.float32:
+        dt = GC_F32
+    else:
+        raise ValueError("q must be bf16 or fp32")
+    _dev_contig(q, q.dtype, "q"); _dev_contig(p, q.dtype, "p"); _dev_contig(pos_idx, torch.int32, "pos_idx")
+    B, d = q.shape
+    P = p.shape[0]
+    dev = q.device
+    out = dict(out or {})
+    shapes = dict(loss=((1,), torch.float32), dq=((B, d), torch.float32), dp=((P, d), torch.float32),
+                  lse=((B,), torch.float32), argmax=((B,), torch.int32))
+    for k in want:
+        if k not in out:
+            out[k] = torch.empty(shapes[k][0], dtype=shapes[k][1], device=dev)
+    need = lib.gc_workspace_bytes(B, P, d, dt)
+    if workspace is None:
+        workspace = alloc_workspace(need, dev)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_loss_and_rep_grad_ex(dt, _ptr(q), _ptr(p), _ptr(pos_idx), B, P, d, scale, temp, flags,
+                                     _ptr(out.get("loss")), _ptr(out.get("dq")), _ptr(out.get("dp")),
+                                     _ptr(out.get("lse")), _ptr(out.get("argmax")), wp, wn, _stream(stream))
+    _check(rc, "gc_loss_and_rep_grad_ex")
+    out["workspace"] = workspace
+    return out
+
+
+def gc_check_async_error(workspace=None):
+    lib = load()
+    if workspace is None:
+        return lib.gc_check_async_error(None)
+    return lib.gc_check_async_error(_ws_ptr(workspace)[0])
+
+
+def gc_ntxent_loss_and_grad_bf16(z, temp, workspace=None, stream=None):
+    lib = load()
+    _dev_contig(z, torch.bfloat16, "z")
+    n, d = z.shape
+    loss = torch.empty(1, dtype=torch.float32, device=z.device)
+    dz = torch.empty(n, d, dtype=torch.float32, device=z.device)
+    if workspace is None:
+        workspace = alloc_workspace(lib.gc_ntxent_workspace_bytes(n, d), z.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_ntxent_loss_and_grad_bf16(_ptr(z), n, d, temp, _ptr(loss), _ptr(dz), wp, wn, _stream(stream))
+    _check(rc, "gc_ntxent_loss_and_grad_bf16")
+    return loss, dz
+
+
+# ----------------------------------------------------------------------------- stand-in encoder
+def make_mlp_params(params):
+    """params: dict W1 [din,dh], b1, W2 [dh,dout], b2 of contiguous bf16 device tensors."""
+    for k in ("W1", "b1", "W2", "b2"):
+        _dev_contig(params[k], torch.bfloat16, k)
+    din, dh = params["W1"].shape
+    dout = params["W2"].shape[1]
+    return gc_mlp_params(params["W1"].data_ptr(), params["b1"].data_ptr(), params["W2"].data_ptr(),
+                         params["b2"].data_ptr(), din, dh, dout)
+
+
+def make_mlp_grads(grads):
+    for k in ("W1", "b1", "W2", "b2"):
+        _dev_contig(grads[k], torch.float32, "grad " + k)
+    return gc_mlp_grads(grads["W1"].data_ptr(), grads["b1"].data_ptr(), grads["W2"].data_ptr(), grads["b2"].data_ptr())
+
+
+def zero_mlp_grads(params):
+    return {k: torch.zeros(params[k].shape, dtype=torch.float32, device=params[k].device) for k in ("W1", "b1", "W2", "b2")}
+
+
+def gc_mlp_forward_nograd_bf16(x, params, workspace=None, stream=None):
+    lib = load()
+    _dev_contig(x, torch.bfloat16, "x")
+    w = make_mlp_params(params)
+    rows = x.shape[0]
+    y = torch.empty(rows, w.dout, dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = alloc_workspace(lib.gc_mlp_workspace_bytes(rows, ctypes.byref(w)), x.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_mlp_forward_nograd_bf16(_ptr(x), rows, ctypes.byref(w), _ptr(y), wp, wn, _stream(stream))
+    _check(rc, "gc_mlp_forward_nograd_bf16")
+    return y
+
+
+def gc_chunk_surrogate_backward_bf16(x_chunk, params, cached_grad_rows, grads, workspace=None, stream=None):
+    lib = load()
+    _dev_contig(x_chunk, torch.bfloat16, "x_chunk")
+    _dev_contig(cached_grad_rows, torch.float32, "cached_grad_rows")
+    w = make_mlp_params(params)
+    g = make_mlp_grads(grads)
+    rows = x_chunk.shape[0]
+    if cached_grad_rows.shape != (rows, w.dout):
+        raise ValueError("cached_grad_rows must be [rows, dout]")
+    if workspace is None:
+        workspace = alloc_workspace(lib.gc_mlp_workspace_bytes(rows, ctypes.byref(w)), x_chunk.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_chunk_surrogate_backward_bf16(_ptr(x_chunk), rows, ctypes.byref(w), _ptr(cached_grad_rows),
+                                              ctypes.byref(g), wp, wn, _stream(stream))
+    _check(rc, "gc_chunk_surrogate_backward_bf16")
+    return grads
+
+
+def gc_step_mlp_bf16(x_q, x_p, pos_idx, chunk_q, chunk_p, params, scale=1.0, temp=1.0, grads=None, keep=False,
+                     workspace=None, stream=None):
+    """One Gradient Cache step.  Returns dict(loss, grads[, q, p, dq, dp])."""
+    lib = load()
+    _dev_contig(x_q, torch.bfloat16, "x_q"); _dev_contig(x_p, torch.bfloat16, "x_p")
+    _dev_contig(pos_idx, torch.int32, "pos_idx")
+    w = make_mlp_params(params)
+    if grads is None:
+        grads = zero_mlp_grads(params)
+    g = make_mlp_grads(grads)
+    B, P = x_q.shape[0], x_p.shape[0]
+    dev = x_q.device
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    out = dict(loss=loss, grads=grads)
+    if keep:
+        out["q"] = torch.empty(B, w.dout, dtype=torch.bfloat16, device=dev)
+        out["p"] = torch.empty(P, w.dout, dtype=torch.bfloat16, device=dev)
+        out["dq"] = torch.empty(B, w.dout, dtype=torch.float32, device=dev)
+        out["dp"] = torch.empty(P, w.dout, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = alloc_workspace(lib.gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, ctypes.byref(w)), dev)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_step_mlp_bf16(_ptr(x_q), B, _ptr(x_p), P, _ptr(pos_idx), chunk_q, chunk_p, ctypes.byref(w), scale, temp,
+                              _ptr(loss), ctypes.byref(g), _ptr(out.get("q")), _ptr(out.get("p")), _ptr(out.get("dq")),
+                              _ptr(out.get("dp")), wp, wn, _stream(stream))
+    _check(rc, "gc_step_mlp_bf16")
+    out["workspace"] = workspace
+    return out

@@ -1,0 +1,223 @@
+// C ABI of the library: argument checks, workspace planning and kernel sequencing.
+// Every check happens before the first HIP call of an entry point.
+#include <cmath>
+#include <cstring>
+#include <mutex>
+
+#include "gc_common.h"
+
+namespace gc {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
+  LossPlan pl{};
+  pl.use_mfma = (dt == GC_BF16 && d % 128 == 0 && d >= 128 && d <= 768) ? 1 : 0;
+  if (pl.use_mfma) {
+    const int n_ablk = ceil_div(B, 256), tiles = ceil_div(P, 256);
+    int splits = ceil_div(kNumCU, n_ablk);
+    if (splits > tiles) splits = tiles;
+    if (splits < 1) splits = 1;
+    pl.stat_cols_per_split = ceil_div(tiles, splits) * 256;
+    pl.stat_splits = ceil_div(P, pl.stat_cols_per_split);
+    // gradient pass: one workgroup per CU, equal streamed length for both roles
+    const long long obQ = ceil_div(B, 64), obP = ceil_div(P, 64);
+    const long long W = obQ * P + obP * B;
+    long long L = (W + kNumCU - 1) / kNumCU;
+    if (L < 256) L = 256;
+    L = (L + 31) / 32 * 32;
+    auto split_of = [&](int n, int& ns, int& len) {
+      ns = (int)((n + L - 1) / L);
+      if (ns > 16) ns = 16;
+      if (ns < 1) ns = 1;
+      len = (ceil_div(n, ns) + 31) / 32 * 32;
+      ns = ceil_div(n, len);
+    };
+    split_of(P, pl.nsq, pl.q_stream_len);
+    split_of(B, pl.nsp, pl.p_stream_len);
+  } else {
+    const int blocks = ceil_div(B, 16), tiles = ceil_div(P, 16);
+    int splits = ceil_div(4 * kNumCU, blocks);
+    if (splits > 64) splits = 64;
+    if (splits > tiles) splits = tiles;
+    if (splits < 1) splits = 1;
+    pl.stat_cols_per_split = ceil_div(tiles, splits) * 16;
+    pl.stat_splits = ceil_div(P, pl.stat_cols_per_split);
+    pl.nsq = pl.nsp = 1;
+    pl.q_stream_len = P;
+    pl.p_stream_len = B;
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  pl.off_err = take(256);
+  pl.off_part_m = take((size_t)pl.stat_splits * B * 4);
+  pl.off_part_l = take((size_t)pl.stat_splits * B * 4);
+  pl.off_part_idx = take((size_t)pl.stat_splits * B * 4);
+  pl.off_pos = take((size_t)B * 4);
+  pl.off_lse2 = take((size_t)B * 4);
+  pl.off_rowloss = take((size_t)B * 4);
+  pl.off_dq_part = take((pl.nsq > 1 || ntxent) ? (size_t)pl.nsq * B * d * 4 : 0);
+  pl.off_dp_part = take((pl.nsp > 1 || ntxent) ? (size_t)pl.nsp * P * d * 4 : 0);
+  pl.off_pos_idx = take(ntxent ? (size_t)B * 4 : 0);
+  pl.total = off;
+  return pl;
+}
+
+static bool shape_ok(int B, int P, int d) {
+  if (B < 1 || P < 1 || d < 1) return false;
+  if ((long long)B * d > (1ll << 40) || (long long)P * d > (1ll << 40)) return false;
+  return true;
+}
+
+// per-device buffer behind the entry points that take no workspace
+static std::mutex g_ws_mutex;
+static void* g_ws_ptr[64];
+static size_t g_ws_bytes[64];
+
+static int own_workspace(size_t need, void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  if (g_ws_bytes[dev] < need) {
+    if (g_ws_ptr[dev]) (void)hipFree(g_ws_ptr[dev]);  // waits for work that still uses it
+    g_ws_ptr[dev] = nullptr;
+    g_ws_bytes[dev] = 0;
+    size_t sz = align_up(need + need / 4, 1 << 20);
+    if (hipMalloc(&g_ws_ptr[dev], sz) != hipSuccess) return GC_ERR_HIP;
+    g_ws_bytes[dev] = sz;
+  }
+  *out = g_ws_ptr[dev];
+  return GC_OK;
+}
+
+static int run_loss(const LossArgs& a, const LossPlan& pl) {
+  hipError_t e = pl.use_mfma ? launch_stats_mfma(a, pl) : launch_stats_generic(a, pl);
+  if (e != hipSuccess) return GC_ERR_HIP;
+  e = launch_stats_merge(a, pl);
+  if (e != hipSuccess) return GC_ERR_HIP;
+  if (a.dq || a.dp || a.dz) {
+    e = pl.use_mfma ? launch_grad_mfma(a, pl) : launch_grad_generic(a, pl);
+    if (e != hipSuccess) return GC_ERR_HIP;
+  }
+  return GC_OK;
+}
+
+static int check_loss_args(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                           float scale, float temp, unsigned flags) {
+  if (!q || !p || !pos_idx) return GC_ERR_NULL;
+  if (!shape_ok(B, P, d)) return GC_ERR_SHAPE;
+  if (!(scale > 0.f) || !(temp > 0.f) || !std::isfinite(scale) || !std::isfinite(temp)) return GC_ERR_SHAPE;
+  if (!std::isfinite(scale / temp) || !(scale / temp > 0.f)) return GC_ERR_SHAPE;
+  if (dt != GC_F32 && dt != GC_BF16) return GC_ERR_UNSUPPORTED;
+  if (flags & ~GC_MASK_SELF) return GC_ERR_UNSUPPORTED;
+  if ((flags & GC_MASK_SELF) && (B != P || P < 2)) return GC_ERR_SHAPE;
+  return GC_OK;
+}
+
+__global__ void pair_index_kernel(int32_t* r, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) r[i] = i ^ 1;
+}
+
+}  // namespace gc
+
+using namespace gc;
+
+extern "C" {
+
+const char* gc_strerror(int status) {
+  switch (status) {
+    case GC_OK: return "ok";
+    case GC_ERR_NULL: return "a required pointer is NULL";
+    case GC_ERR_SHAPE: return "invalid size, scale or temperature";
+    case GC_ERR_UNSUPPORTED: return "unsupported dtype, flag or shape";
+    case GC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GC_ERR_POS_IDX: return "pos_idx value outside [0, P)";
+    case GC_ERR_HIP: return "HIP runtime call failed";
+    default: return "unknown gc_status";
+  }
+}
+
+size_t gc_workspace_bytes(int B, int P, int d, gc_dtype dt) {
+  if (!shape_ok(B, P, d) || (dt != GC_F32 && dt != GC_BF16)) return 0;
+  return make_loss_plan(B, P, d, dt, false).total;
+}
+
+int gc_loss_and_rep_grad_ex(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                            float scale, float temp, unsigned flags, float* loss, float* dq, float* dp, float* lse,
+                            int32_t* argmax, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_loss_args(dt, q, p, pos_idx, B, P, d, scale, temp, flags);
+  if (rc != GC_OK) return rc;
+  const LossPlan pl = make_loss_plan(B, P, d, dt, false);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return GC_ERR_WORKSPACE;
+  LossArgs a{};
+  a.dt = dt; a.q = q; a.p = p; a.pos_idx = pos_idx; a.B = B; a.P = P; a.d = d;
+  a.alpha = scale / temp; a.flags = flags;
+  a.loss = loss; a.dq = dq; a.dp = dp; a.lse = lse; a.argmax = argmax; a.dz = nullptr;
+  a.ws = (char*)workspace; a.stream = (hipStream_t)stream;
+  return run_loss(a, pl);
+}
+
+static int simple_loss(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                       float scale, float temp, float* loss, float* dq, float* dp, void* stream) {
+  int rc = check_loss_args(dt, q, p, pos_idx, B, P, d, scale, temp, 0);
+  if (rc != GC_OK) return rc;
+  if (!loss || !dq || !dp) return GC_ERR_NULL;
+  const size_t need = make_loss_plan(B, P, d, dt, false).total;
+  void* ws = nullptr;
+  rc = own_workspace(need, &ws);
+  if (rc != GC_OK) return rc;
+  return gc_loss_and_rep_grad_ex(dt, q, p, pos_idx, B, P, d, scale, temp, 0, loss, dq, dp, nullptr, nullptr, ws, need,
+                                 stream);
+}
+
+int gc_loss_and_rep_grad_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d, float scale,
+                              float temp, float* loss, float* dq, float* dp, void* stream) {
+  return simple_loss(GC_BF16, q, p, pos_idx, B, P, d, scale, temp, loss, dq, dp, stream);
+}
+
+int gc_loss_and_rep_grad_f32(const float* q, const float* p, const int32_t* pos_idx, int B, int P, int d, float scale,
+                             float temp, float* loss, float* dq, float* dp, void* stream) {
+  return simple_loss(GC_F32, q, p, pos_idx, B, P, d, scale, temp, loss, dq, dp, stream);
+}
+
+int gc_check_async_error(const void* workspace) {
+  const void* ws = workspace;
+  if (!ws) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    ws = g_ws_ptr[dev];
+    if (!ws) return GC_OK;  // nothing has run yet
+  }
+  int word = 0;
+  if (hipMemcpy(&word, ws, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return GC_ERR_HIP;
+  return word ? GC_ERR_POS_IDX : GC_OK;
+}
+
+size_t gc_ntxent_workspace_bytes(int n_views, int d) {
+  if (n_views < 2 || (n_views & 1) || !shape_ok(n_views, n_views, d)) return 0;
+  return make_loss_plan(n_views, n_views, d, GC_BF16, true).total;
+}
+
+int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, float* loss, float* dz,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!z) return GC_ERR_NULL;
+  if (n_views < 2 || (n_views & 1) || !shape_ok(n_views, n_views, d)) return GC_ERR_SHAPE;
+  if (!(temp > 0.f) || !std::isfinite(temp) || !std::isfinite(1.f / temp)) return GC_ERR_SHAPE;
+  const LossPlan pl = make_loss_plan(n_views, n_views, d, GC_BF16, true);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return GC_ERR_WORKSPACE;
+  LossArgs a{};
+  a.dt = GC_BF16; a.q = z; a.p = z; a.B = n_views; a.P = n_views; a.d = d;
+  a.alpha = 1.f / temp; a.flags = GC_MASK_SELF;
+  a.loss = loss; a.dz = dz;
+  a.ws = (char*)workspace; a.stream = (hipStream_t)stream;
+  int32_t* r = (int32_t*)(a.ws + pl.off_pos_idx);
+  pair_index_kernel<<<(n_views + 255) / 256, 256, 0, a.stream>>>(r, n_views);
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  a.pos_idx = r;
+  return run_loss(a, pl);
+}
+
+}  // extern "C"

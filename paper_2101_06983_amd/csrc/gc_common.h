@@ -1,0 +1,83 @@
+// Shared host/device declarations of the gfx950 Gradient Cache library
+// (internal; the public C ABI is include/gradcache.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gradcache.h"
+
+namespace gc {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kNumCU = 256;  // MI355X; used only to size grids and workspace splits
+
+// fp32 -> bf16 bits, round to nearest even (inputs here are finite).
+__device__ __forceinline__ unsigned short f2bf(float f) {
+  unsigned u = __builtin_bit_cast(unsigned, f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ unsigned pack2bf(float lo, float hi) {
+  return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16);
+}
+__device__ __forceinline__ float bf2f(unsigned short b) { return __builtin_bit_cast(float, (unsigned)b << 16); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// ---------------------------------------------------------------------------
+// Workspace plan of gc_loss_and_rep_grad_ex: one host function decides the
+// splits and the byte offsets, so gc_workspace_bytes and the launch agree.
+// ---------------------------------------------------------------------------
+struct LossPlan {
+  int use_mfma;          // 1: bf16 MFMA kernels, 0: general fp32-FMA kernels
+  int stat_splits;       // column (target) ranges of the statistics pass
+  int stat_cols_per_split;
+  int nsq, nsp;          // stream splits of the dQ-role / dP-role workgroups of the gradient pass
+  int q_stream_len, p_stream_len;  // stream rows per split (multiple of the stream tile)
+  size_t off_err, off_part_m, off_part_l, off_part_idx, off_pos, off_lse2, off_rowloss, off_dq_part,
+      off_dp_part, off_pos_idx, total;
+};
+
+LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent);
+
+struct LossArgs {
+  gc_dtype dt;
+  const void* q;
+  const void* p;
+  const int32_t* pos_idx;
+  int B, P, d;
+  float alpha;       // scale / temp
+  unsigned flags;
+  float* loss;
+  float* dq;
+  float* dp;
+  float* lse;
+  int32_t* argmax;
+  float* dz;         // NT-Xent: dq + dp summed into one buffer (dq, dp then unused)
+  char* ws;
+  hipStream_t stream;
+};
+
+// kernel-launching halves (one per .hip file)
+hipError_t launch_stats_generic(const LossArgs& a, const LossPlan& pl);
+hipError_t launch_grad_generic(const LossArgs& a, const LossPlan& pl);
+hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl);
+hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl);
+hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl);
+hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
+                                 int nsrc, size_t n, hipStream_t stream);
+
+}  // namespace gc

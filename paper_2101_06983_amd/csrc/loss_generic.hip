@@ -1,0 +1,279 @@
+// General (any d, fp32 or bf16 storage) kernels of the loss / representation-
+// gradient path, fp32 FMA arithmetic.  They serve the fp32 entry point and the
+// shapes the MFMA kernels do not cover, and they hold the pieces both paths
+// share: the merge of split row statistics, the loss reduction and the
+// fixed-order sum of split gradient partials.
+//
+// Scores are kept in the base-2 domain: t_ij = s_ij * log2(e), so that
+// softmax_j = 2^(t_ij - lse2_i) with lse2_i = log2 sum_j 2^t_ij (Eq. 4).
+#include "gc_common.h"
+
+namespace gc {
+
+template <typename T>
+__device__ __forceinline__ float ldf(const T* p, size_t i);
+template <>
+__device__ __forceinline__ float ldf<float>(const float* p, size_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float ldf<unsigned short>(const unsigned short* p, size_t i) { return bf2f(p[i]); }
+
+constexpr int GT = 16;  // tile edge of the general kernels (16 x 16 scores per workgroup step)
+constexpr int GK = 32;  // k-chunk staged through LDS
+
+// One 16x16 tile of base-2 scores: thread (ty, tx) gets t for anchor row0+ty, target col0+tx.
+template <typename T>
+__device__ __forceinline__ float score_tile(const T* __restrict__ Q, const T* __restrict__ Pm, int B, int P, int d,
+                                            int row0, int col0, float alpha2, float (*Qs)[GK + 1], float (*Ps)[GK + 1]) {
+  const int tx = threadIdx.x % GT, ty = threadIdx.x / GT;
+  float acc = 0.f;
+  for (int k0 = 0; k0 < d; k0 += GK) {
+    // 256 threads stage 16 x 32 of each operand (2 elements per thread per operand)
+    for (int e = threadIdx.x; e < GT * GK; e += GT * GT) {
+      int r = e / GK, k = e % GK;
+      int qi = min(row0 + r, B - 1), pj = min(col0 + r, P - 1);
+      bool kin = (k0 + k) < d;
+      Qs[r][k] = kin ? ldf<T>(Q, (size_t)qi * d + k0 + k) : 0.f;
+      Ps[r][k] = kin ? ldf<T>(Pm, (size_t)pj * d + k0 + k) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < GK; k++) acc = fmaf(Qs[ty][k], Ps[tx][k], acc);
+    __syncthreads();
+  }
+  return acc * alpha2;
+}
+
+// Row statistics (Eq. 4's denominator, online over target tiles), one column split per blockIdx.y.
+template <typename T>
+__global__ void __launch_bounds__(256) stats_generic_kernel(const T* __restrict__ Q, const T* __restrict__ Pm,
+                                                           const int32_t* __restrict__ pos_idx, int B, int P, int d,
+                                                           float alpha2, int mask_self, int cols_per_split,
+                                                           float* __restrict__ part_m, float* __restrict__ part_l,
+                                                           int* __restrict__ part_idx, float* __restrict__ pos_t) {
+  __shared__ float Qs[GT][GK + 1], Ps[GT][GK + 1];
+  __shared__ float red_m[GT][GT], red_l[GT][GT];
+  __shared__ int red_i[GT][GT];
+  const int tx = threadIdx.x % GT, ty = threadIdx.x / GT;
+  const int row0 = blockIdx.x * GT;
+  const int split = blockIdx.y;
+  const int cbeg = split * cols_per_split, cend = min(P, cbeg + cols_per_split);
+  const int i = row0 + ty;
+  const int ri = (i < B) ? pos_idx[i] : -1;
+  float m = -INFINITY, l = 0.f;
+  int best = 0x7fffffff;
+  for (int col0 = cbeg; col0 < cend; col0 += GT) {
+    float t = score_tile<T>(Q, Pm, B, P, d, row0, col0, alpha2, Qs, Ps);
+    int j = col0 + tx;
+    bool valid = (j < cend) && !(mask_self && j == i);
+    if (valid) {
+      if (j == ri && i < B) pos_t[i] = t;
+      if (t > m) {  // strict: ties keep the smaller index (columns are visited in increasing order)
+        l = l * exp2f(m - t) + 1.f;
+        m = t;
+        best = j;
+      } else {
+        l += exp2f(t - m);
+      }
+    }
+  }
+  red_m[ty][tx] = m; red_l[ty][tx] = l; red_i[ty][tx] = best;
+  __syncthreads();
+  if (tx == 0 && i < B) {
+    float mm = -INFINITY; int bi = 0x7fffffff;
+    for (int x = 0; x < GT; x++) {
+      float v = red_m[ty][x];
+      if (v > mm || (v == mm && red_i[ty][x] < bi)) { mm = v; bi = red_i[ty][x]; }
+    }
+    float ll = 0.f;
+    if (mm > -INFINITY)
+      for (int x = 0; x < GT; x++) ll += red_l[ty][x] * exp2f(red_m[ty][x] - mm);
+    part_m[(size_t)split * B + i] = mm;
+    part_l[(size_t)split * B + i] = ll;
+    part_idx[(size_t)split * B + i] = bi;
+  }
+}
+
+// Merge of the split statistics of every anchor: lse2_i, row loss (Eq. 1's summand), argmax.
+__global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restrict__ part_m, const float* __restrict__ part_l,
+                                                         const int* __restrict__ part_idx, const float* __restrict__ pos_t,
+                                                         const int32_t* __restrict__ pos_idx, int B, int P, int nsplit,
+                                                         float* __restrict__ lse2, float* __restrict__ rowloss,
+                                                         float* __restrict__ lse_out, int32_t* __restrict__ argmax_out) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B) return;
+  float m = -INFINITY; int bi = 0x7fffffff;
+  for (int s = 0; s < nsplit; s++) {
+    float v = part_m[(size_t)s * B + i]; int x = part_idx[(size_t)s * B + i];
+    if (v > m || (v == m && x < bi)) { m = v; bi = x; }
+  }
+  float l = 0.f;
+  for (int s = 0; s < nsplit; s++) {
+    float v = part_m[(size_t)s * B + i];
+    if (v > -INFINITY) l += part_l[(size_t)s * B + i] * exp2f(v - m);
+  }
+  float l2 = m + log2f(l);
+  lse2[i] = l2;
+  int r = pos_idx[i];
+  bool ok = (r >= 0 && r < P);
+  rowloss[i] = ok ? (l2 - pos_t[i]) * kLn2 : NAN;
+  if (lse_out) lse_out[i] = l2 * kLn2;
+  if (argmax_out) argmax_out[i] = bi;
+}
+
+// loss = (1/B) sum_i rowloss_i in a fixed order (single workgroup); raises the error word when a
+// row was flagged (NaN marker) because its pos_idx was out of range.
+__global__ void __launch_bounds__(1024) loss_reduce_kernel(const float* __restrict__ rowloss, const int32_t* __restrict__ pos_idx,
+                                                          int B, int P, float* __restrict__ loss, int* __restrict__ err) {
+  __shared__ float red[1024];
+  __shared__ int bad[1024];
+  float s = 0.f; int b = 0;
+  for (int i = threadIdx.x; i < B; i += 1024) {
+    s += rowloss[i];
+    int r = pos_idx[i];
+    b |= (r < 0 || r >= P);
+  }
+  red[threadIdx.x] = s; bad[threadIdx.x] = b;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) { red[threadIdx.x] += red[threadIdx.x + w]; bad[threadIdx.x] |= bad[threadIdx.x + w]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (loss) *loss = bad[0] ? NAN : red[0] / (float)B;
+    *err = bad[0] ? 1 : 0;
+  }
+}
+
+// Gradient pass, general form.  owner = the matrix whose gradient rows this workgroup owns
+// (Q for Eq. 5, P for Eq. 6); the other matrix is streamed 16 rows at a time.  The owned
+// 16 x d block of the output is updated in place tile by tile (one owner per row: no atomics).
+template <typename T, bool OWNER_IS_Q>
+__global__ void __launch_bounds__(256) grad_generic_kernel(const T* __restrict__ Q, const T* __restrict__ Pm,
+                                                          const int32_t* __restrict__ pos_idx, const float* __restrict__ lse2,
+                                                          int B, int P, int d, float alpha2, float out_scale, int mask_self,
+                                                          float* __restrict__ out) {
+  __shared__ float Qs[GT][GK + 1], Ps[GT][GK + 1];
+  __shared__ float g[GT][GT + 1];  // g[owner row][stream row]
+  const int tx = threadIdx.x % GT, ty = threadIdx.x / GT;
+  const int own0 = blockIdx.x * GT;
+  const int n_own = OWNER_IS_Q ? B : P, n_str = OWNER_IS_Q ? P : B;
+  const T* S = OWNER_IS_Q ? Pm : Q;
+  bool first = true;
+  for (int str0 = 0; str0 < n_str; str0 += GT) {
+    const int row0 = OWNER_IS_Q ? own0 : str0;  // anchors on ty
+    const int col0 = OWNER_IS_Q ? str0 : own0;  // targets on tx
+    float t = score_tile<T>(Q, Pm, B, P, d, row0, col0, alpha2, Qs, Ps);
+    int i = row0 + ty, j = col0 + tx;
+    float gv = 0.f;
+    if (i < B && j < P && !(mask_self && i == j)) {
+      gv = exp2f(t - lse2[i]) - ((pos_idx[i] == j) ? 1.f : 0.f);
+    }
+    if (OWNER_IS_Q) g[ty][tx] = gv * out_scale; else g[tx][ty] = gv * out_scale;
+    __syncthreads();
+    for (int e = threadIdx.x; e < GT * d; e += 256) {
+      int r = e / d, c = e % d;
+      if (own0 + r < n_own) {
+        float acc = 0.f;
+        for (int b = 0; b < GT; b++) {
+          int sr = min(str0 + b, n_str - 1);  // g is 0 past the end
+          acc = fmaf(g[r][b], ldf<T>(S, (size_t)sr * d + c), acc);
+        }
+        size_t o = (size_t)(own0 + r) * d + c;
+        out[o] = first ? acc : out[o] + acc;
+      }
+    }
+    first = false;
+    __syncthreads();
+  }
+}
+
+// out[e] = sum over sources s, over parts k < counts[s] of srcs[s][k * strides[s] + e], fixed order.
+struct ReduceSrc {
+  const float* ptr[4];
+  int count[4];
+  size_t stride[4];
+  int nsrc;
+};
+__global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__ out, ReduceSrc rs, size_t n4) {
+  size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n4) return;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < rs.nsrc; s++)
+    for (int k = 0; k < rs.count[s]; k++) acc += ((const f32x4*)(rs.ptr[s] + (size_t)k * rs.stride[s]))[e];
+  ((f32x4*)out)[e] = acc;
+}
+__global__ void __launch_bounds__(256) partial_reduce_tail_kernel(float* __restrict__ out, ReduceSrc rs, size_t beg, size_t n) {
+  size_t e = beg + (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  float acc = 0.f;
+  for (int s = 0; s < rs.nsrc; s++)
+    for (int k = 0; k < rs.count[s]; k++) acc += rs.ptr[s][(size_t)k * rs.stride[s] + e];
+  out[e] = acc;
+}
+
+hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
+                                 int nsrc, size_t n, hipStream_t stream) {
+  ReduceSrc rs{};
+  rs.nsrc = nsrc;
+  for (int s = 0; s < nsrc; s++) { rs.ptr[s] = srcs[s]; rs.count[s] = counts[s]; rs.stride[s] = strides[s]; }
+  size_t n4 = n / 4;
+  if (n4) partial_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256)), 256, 0, stream>>>(out, rs, n4);
+  if (n4 * 4 < n) partial_reduce_tail_kernel<<<1, 256, 0, stream>>>(out, rs, n4 * 4, n);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t stats_generic_t(const LossArgs& a, const LossPlan& pl) {
+  char* ws = a.ws;
+  dim3 grid((a.B + GT - 1) / GT, pl.stat_splits);
+  stats_generic_kernel<T><<<grid, 256, 0, a.stream>>>((const T*)a.q, (const T*)a.p, a.pos_idx, a.B, a.P, a.d,
+                                                      a.alpha * kLog2e, (a.flags & GC_MASK_SELF) ? 1 : 0,
+                                                      pl.stat_cols_per_split, (float*)(ws + pl.off_part_m),
+                                                      (float*)(ws + pl.off_part_l), (int*)(ws + pl.off_part_idx),
+                                                      (float*)(ws + pl.off_pos));
+  return hipGetLastError();
+}
+hipError_t launch_stats_generic(const LossArgs& a, const LossPlan& pl) {
+  return a.dt == GC_F32 ? stats_generic_t<float>(a, pl) : stats_generic_t<unsigned short>(a, pl);
+}
+
+hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
+  char* ws = a.ws;
+  stats_merge_kernel<<<(a.B + 255) / 256, 256, 0, a.stream>>>(
+      (const float*)(ws + pl.off_part_m), (const float*)(ws + pl.off_part_l), (const int*)(ws + pl.off_part_idx),
+      (const float*)(ws + pl.off_pos), a.pos_idx, a.B, a.P, pl.stat_splits, (float*)(ws + pl.off_lse2),
+      (float*)(ws + pl.off_rowloss), a.lse, a.argmax);
+  loss_reduce_kernel<<<1, 1024, 0, a.stream>>>((const float*)(ws + pl.off_rowloss), a.pos_idx, a.B, a.P, a.loss,
+                                               (int*)(ws + pl.off_err));
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t grad_generic_t(const LossArgs& a, const LossPlan& pl) {
+  char* ws = a.ws;
+  const float* lse2 = (const float*)(ws + pl.off_lse2);
+  const float alpha2 = a.alpha * kLog2e, osc = a.alpha / (float)a.B;
+  const int ms = (a.flags & GC_MASK_SELF) ? 1 : 0;
+  float* dq = a.dz ? (float*)(ws + pl.off_dq_part) : a.dq;
+  float* dp = a.dz ? (float*)(ws + pl.off_dp_part) : a.dp;
+  if (dq)
+    grad_generic_kernel<T, true><<<(a.B + GT - 1) / GT, 256, 0, a.stream>>>((const T*)a.q, (const T*)a.p, a.pos_idx, lse2,
+                                                                           a.B, a.P, a.d, alpha2, osc, ms, dq);
+  if (dp)
+    grad_generic_kernel<T, false><<<(a.P + GT - 1) / GT, 256, 0, a.stream>>>((const T*)a.q, (const T*)a.p, a.pos_idx, lse2,
+                                                                            a.B, a.P, a.d, alpha2, osc, ms, dp);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.dz) {
+    const float* srcs[2] = {dq, dp};
+    int counts[2] = {1, 1};
+    size_t strides[2] = {0, 0};
+    return launch_partial_reduce(a.dz, srcs, counts, strides, 2, (size_t)a.B * a.d, a.stream);
+  }
+  return hipSuccess;
+}
+hipError_t launch_grad_generic(const LossArgs& a, const LossPlan& pl) {
+  return a.dt == GC_F32 ? grad_generic_t<float>(a, pl) : grad_generic_t<unsigned short>(a, pl);
+}
+
+}  // namespace gc

@@ -1,0 +1,154 @@
+"""GPU parity of the loss / representation-gradient path against the fp64 oracle.
+Every call goes through the C ABI (ctypes binding)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2101_06983_amd import binding as gc
+from paper_2101_06983_amd import synth
+from parity import TOL_BF16, TOL_F32, check_argmax, oracle_loss, relerr, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_ex(q, p, r, scale=1.0, temp=1.0, flags=0):
+    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), scale, temp, flags)
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error(out["workspace"]) == gc.GC_OK
+    return out
+
+
+def compare(out, want, tol, q=None, p=None, alpha=1.0, gap_tol=1e-5):
+    assert abs(out["loss"].item() - want["loss"]) <= tol * abs(want["loss"]) + 1e-30
+    assert relerr(to_np(out["dq"]), want["dq"]) <= tol
+    assert relerr(to_np(out["dp"]), want["dp"]) <= tol
+    assert relerr(to_np(out["lse"]), want["lse"]) <= tol
+    amb = check_argmax(to_np(out["argmax"]), want, synth.widen(q), synth.widen(p), alpha, gap_tol)
+    assert amb <= max(1, len(want["argmax"]) // 1000)
+
+
+def test_config1_tiny_fp32():
+    q, p, r = synth.config1()
+    want = oracle_loss(q, p, r)
+    loss, dq, dp = gc.gc_loss_and_rep_grad_f32(q.to(DEV), p.to(DEV), r.to(DEV))
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error() == gc.GC_OK
+    assert abs(loss.item() - want["loss"]) <= TOL_F32 * want["loss"]
+    assert relerr(to_np(dq), want["dq"]) <= TOL_F32
+    assert relerr(to_np(dp), want["dp"]) <= TOL_F32
+    compare(run_ex(q, p, r), want, TOL_F32, q, p)
+
+
+@pytest.mark.parametrize("B,P,d,scale,temp", [(37, 53, 20, 1.0, 1.0), (1, 1, 7, 1.0, 1.0), (1, 40, 64, 2.0, 0.5),
+                                              (130, 70, 33, 1.0, 0.1), (16, 16, 128, 1.0, 1.0)])
+def test_fp32_general_shapes(B, P, d, scale, temp):
+    q, p, r = synth.dpr_batch(B, P, d, torch.float32, seed=1000 + B)
+    g = np.random.default_rng(B)
+    r = torch.from_numpy(g.integers(0, P, size=B).astype(np.int32))   # shared positives, unused targets
+    want = oracle_loss(q, p, r, scale, temp)
+    compare(run_ex(q, p, r, scale, temp), want, TOL_F32, q, p, scale / temp)
+
+
+def test_config2_dpr_shaped_bf16():
+    q, p, r = synth.config2()
+    want = oracle_loss(q, p, r)
+    assert 4.9 < want["loss"] < 5.2
+    loss, dq, dp = gc.gc_loss_and_rep_grad_bf16(q.to(DEV), p.to(DEV), r.to(DEV))
+    torch.cuda.synchronize()
+    assert abs(loss.item() - want["loss"]) <= TOL_BF16 * want["loss"]
+    assert relerr(to_np(dq), want["dq"]) <= TOL_BF16
+    assert relerr(to_np(dp), want["dp"]) <= TOL_BF16
+    compare(run_ex(q, p, r), want, TOL_BF16, q, p)
+
+
+@pytest.mark.parametrize("B,P,d,scale,temp", [
+    (100, 300, 128, 1.0, 1.0),     # ragged in both directions, several stream tiles
+    (65, 257, 256, 1.0, 0.5),      # one row past a tile edge
+    (1, 1, 128, 1.0, 1.0),         # closed form: loss 0, gradients 0
+    (1, 1000, 384, 3.0, 1.0),
+    (300, 31, 512, 1.0, 1.0),      # fewer targets than one stream tile
+    (257, 513, 768, 1.0, 0.25),
+    (64, 96, 96, 1.0, 1.0),        # d not a multiple of 128: general kernel on bf16 storage
+    (20, 50, 8, 1.0, 1.0),
+])
+def test_bf16_shapes_and_edges(B, P, d, scale, temp):
+    q, p, _ = synth.dpr_batch(B, P, d, torch.bfloat16, seed=2000 + B + P)
+    g = np.random.default_rng(B + P)
+    r = torch.from_numpy(g.integers(0, P, size=B).astype(np.int32))
+    want = oracle_loss(q, p, r, scale, temp)
+    out = run_ex(q, p, r, scale, temp)
+    if P == 1:
+        assert out["loss"].item() == 0.0
+        assert float(out["dq"].abs().max()) == 0.0 and float(out["dp"].abs().max()) == 0.0
+    compare(out, want, TOL_BF16, q, p, scale / temp)
+
+
+@pytest.mark.parametrize("n,d,dtype", [(96, 128, torch.bfloat16), (70, 24, torch.float32), (322, 256, torch.bfloat16)])
+def test_mask_self(n, d, dtype):
+    q, p, _ = synth.dpr_batch(n, n, d, dtype, seed=3000 + n)
+    r = torch.arange(n, dtype=torch.int32) ^ 1
+    want = oracle_loss(q, p, r, 1.0, 0.5, mask_self=True)
+    out = run_ex(q, p, r, 1.0, 0.5, flags=gc.GC_MASK_SELF)
+    compare(out, want, TOL_BF16 if dtype == torch.bfloat16 else TOL_F32, q, p, 2.0)
+
+
+def test_optional_outputs_and_reuse_of_workspace():
+    q, p, r = synth.config2()
+    qd, pd, rd = q.to(DEV), p.to(DEV), r.to(DEV)
+    full = gc.gc_loss_and_rep_grad_ex(qd, pd, rd)
+    only = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("loss",), workspace=full["workspace"])
+    torch.cuda.synchronize()
+    assert only["loss"].item() == full["loss"].item()
+    only_dp = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("dp",), workspace=full["workspace"])
+    torch.cuda.synchronize()
+    assert torch.equal(only_dp["dp"], full["dp"])
+
+
+def test_pos_idx_out_of_range_is_reported_not_faulted():
+    q, p, r = synth.config2()
+    r = r.clone()
+    r[5] = 256          # == P
+    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), want=("loss",))
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error(out["workspace"]) == gc.GC_ERR_POS_IDX
+    assert math.isnan(out["loss"].item())
+    r[5] = -3
+    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), want=("loss",), workspace=out["workspace"])
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error(out["workspace"]) == gc.GC_ERR_POS_IDX
+
+
+def test_config3_full_size_parity_invariants_and_reproducibility():
+    q, p, r = synth.config3()
+    want = oracle_loss(q, p, r)
+    assert abs(want["loss"] - (math.log(8192) + 1 / 1536)) < 0.01
+    out = run_ex(q, p, r)
+    compare(out, want, TOL_BF16, q, p, 1.0, gap_tol=2e-6)
+    dq, dp = to_np(out["dq"]), to_np(out["dp"])
+    q64, p64 = synth.widen(q), synth.widen(p)
+    # I1: rows of softmax - Y sum to zero  =>  sum_j dp_j = 0
+    assert np.abs(dp.sum(axis=0)).max() <= TOL_BF16 * np.abs(dp).max() * 8
+    # I2: sum_i <q_i, dq_i> = sum_j <p_j, dp_j>
+    eq, ep = np.sum(q64 * dq), np.sum(p64 * dp)
+    assert abs(eq - ep) <= 2e-3 * max(abs(eq), abs(ep), np.abs(dq).max())
+    # I5: bit-identical from run to run, and through the plain entry point
+    again = run_ex(q, p, r)
+    for k in ("loss", "dq", "dp", "lse", "argmax"):
+        assert torch.equal(out[k], again[k]), k
+    loss, dq2, dp2 = gc.gc_loss_and_rep_grad_bf16(q.to(DEV), p.to(DEV), r.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(dq2, out["dq"]) and torch.equal(dp2, out["dp"]) and loss.item() == out["loss"].item()
+
+
+def test_i4_permuting_targets_permutes_dp():
+    q, p, r = synth.dpr_batch(200, 500, 256, torch.bfloat16, seed=77)
+    a = run_ex(q, p, r)
+    perm = torch.from_numpy(np.random.default_rng(5).permutation(500))
+    inv = torch.argsort(perm)
+    b = run_ex(q, p[perm].contiguous(), inv[r.long()].to(torch.int32))
+    assert abs(a["loss"].item() - b["loss"].item()) <= 1e-5 * abs(a["loss"].item())
+    assert relerr(to_np(b["dq"]), to_np(a["dq"])) <= 1e-3
+    assert relerr(to_np(b["dp"]), to_np(a["dp"])[perm.numpy()]) <= 1e-3

@@ -1,0 +1,77 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2101_06983_amd import binding as gc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "gradcache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = gc.load()
+    names = header_functions()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(names) == sorted(gc.EXPORTS)
+
+
+def test_strerror_texts():
+    assert gc.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert gc.strerror(code) and "unknown" not in gc.strerror(code)
+    assert "unknown" in gc.strerror(-99)
+
+
+def test_workspace_bytes_is_linear_in_rows_not_quadratic():
+    # persistent state is O((B + P) d): the cache of Sec. "Gradient Cache Technique", never O(B P)
+    lib = gc.load()
+    w1 = lib.gc_workspace_bytes(4096, 8192, 768, gc.GC_BF16)
+    assert 0 < w1 < 8 * (4096 + 8192) * 768 * 4
+    assert w1 < 4096 * 8192 * 2 / 2       # far below a bf16 score matrix
+    w2 = lib.gc_workspace_bytes(8192, 16384, 768, gc.GC_BF16)
+    assert w2 < 3 * w1
+    assert lib.gc_workspace_bytes(0, 5, 8, gc.GC_F32) == 0
+    assert lib.gc_workspace_bytes(5, 5, 8, 7) == 0
+    assert lib.gc_ntxent_workspace_bytes(7, 128) == 0
+    assert lib.gc_ntxent_workspace_bytes(16384, 128) > 0
+
+
+def test_argument_errors_are_raised_on_the_host():
+    lib = gc.load()
+    vp = ctypes.c_void_p
+    fake = vp(256)  # never dereferenced: all checks below fail before any HIP call
+    f = lib.gc_loss_and_rep_grad_bf16
+    assert f(None, fake, fake, 8, 16, 128, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_NULL
+    assert f(fake, fake, None, 8, 16, 128, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_NULL
+    assert f(fake, fake, fake, 8, 16, 128, 1.0, 1.0, None, fake, fake, None) == gc.GC_ERR_NULL
+    assert f(fake, fake, fake, 0, 16, 128, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    assert f(fake, fake, fake, 8, -1, 128, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    assert f(fake, fake, fake, 8, 16, 0, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    assert f(fake, fake, fake, 8, 16, 128, 1.0, 0.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    assert f(fake, fake, fake, 8, 16, 128, float("nan"), 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    assert f(fake, fake, fake, 8, 16, 128, float("inf"), 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    ex = lib.gc_loss_and_rep_grad_ex
+    args = lambda **k: [k.get("dt", gc.GC_BF16), fake, fake, fake, k.get("B", 8), k.get("P", 16), 128, 1.0, 1.0,
+                        k.get("flags", 0), fake, fake, fake, None, None, k.get("ws", fake), k.get("wsb", 1 << 30), None]
+    assert ex(*args(dt=5)) == gc.GC_ERR_UNSUPPORTED
+    assert ex(*args(flags=2)) == gc.GC_ERR_UNSUPPORTED
+    assert ex(*args(flags=gc.GC_MASK_SELF)) == gc.GC_ERR_SHAPE          # B != P
+    assert ex(*args(ws=None)) == gc.GC_ERR_WORKSPACE
+    assert ex(*args(ws=vp(264))) == gc.GC_ERR_WORKSPACE                  # misaligned
+    assert ex(*args(wsb=16)) == gc.GC_ERR_WORKSPACE
+    nt = lib.gc_ntxent_loss_and_grad_bf16
+    assert nt(None, 16, 128, 0.1, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_NULL
+    assert nt(fake, 15, 128, 0.1, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
+    assert nt(fake, 16, 128, -1.0, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
+    assert nt(fake, 16, 128, 0.1, fake, fake, fake, 8, None) == gc.GC_ERR_WORKSPACE
