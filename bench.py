@@ -1,0 +1,125 @@
+#!/usr/bin/env python3
+"""Benchmark of the Gradient Cache hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+
+A step is one pass of the loss + representation-gradient path (statistics pass,
+merge, gradient pass, partial sums) over one synthetic batch of the headline
+workload: B=4096 queries, P=8192 passages, d=768, bf16 storage, fp32 accumulate.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+value      algorithmic TFLOP/s = 6*B*P*d / step time (three GEMMs: S, G*P, G^T*Q)
+roofline   for the dominant kernel (the gradient kernel): algorithmic flops of one
+           launch (4*B*P*d: the two gradient contractions) / its mean duration from
+           HIP events recorded by the library on the launch stream, against the
+           MI355X dense bf16 MFMA peak.  `executed_frac` counts the recomputed
+           score tiles as well (8*B*P*d flops per launch).
+cpu_baseline  the fp64 numpy oracle timed on the host cores on the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+# HBM bytes per gradient-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/grad_mfma_kernel_config3_pmc.txt); None until measured.
+TRAFFIC_BYTES = None
+
+
+def cpu_baseline(q, p, r, flops):
+    from oracle import gc_oracle as O
+    from paper_2101_06983_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    q64, p64, r64 = synth.widen(q), synth.widen(p), synth.widen(r)
+    reps, t_total = 0, 0.0
+    while reps < 3 and t_total < 30.0:
+        t0 = time.perf_counter()
+        O.loss_and_rep_grad(q64, p64, r64)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    sec = t_total / reps
+    return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "full workload batch (B=4096,P=8192,d=768), fp64 numpy oracle, mean of %d runs, %.2f s each" % (reps, sec)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the one-GPU hot path; --gpus must be 1 (no collectives are part of it)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    from paper_2101_06983_amd import binding as gc
+    from paper_2101_06983_amd import synth
+
+    dev = torch.device("cuda:0")
+    B, P, d = 4096, 8192, 768
+    q, p, r = synth.config3()
+    qd, pd, rd = q.to(dev), p.to(dev), r.to(dev)
+    out = {k: torch.empty(s, dtype=t, device=dev) for k, (s, t) in
+           dict(loss=((1,), torch.float32), dq=((B, d), torch.float32), dp=((P, d), torch.float32)).items()}
+    ws = gc.alloc_workspace(gc.gc_workspace_bytes(B, P, d, gc.GC_BF16), dev)
+    want = ("loss", "dq", "dp")
+
+    def step():
+        gc.gc_loss_and_rep_grad_ex(qd, pd, rd, 1.0, 1.0, 0, want, ws, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    gc.gc_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = gc.gc_profile_end()
+    assert gc.gc_check_async_error(ws) == gc.GC_OK
+
+    ms = (t1 - t0) * 1e3 / args.steps
+    flops_alg = 6.0 * B * P * d
+    value = flops_alg / (ms * 1e-3) / 1e12
+    k_alg = 4.0 * B * P * d          # G*P and G^T*Q
+    k_exe = 8.0 * B * P * d          # + the score tile recomputed in both walks
+    achieved = k_alg / (prof["ms_grad"] * 1e-3) / 1e12
+    rec = {
+        "metric": "loss+rep-grad TFLOP/s & ms/step at B=4096,P=8192,d=768 bf16; % MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config3 large-batch ICT-shaped: B=4096 queries, P=8192 passages, d=768, bf16 storage, "
+                               "fp32 accumulate, pos_idx[i]=2i, iid N(0,1/d)", "B": B, "P": P, "d": d,
+                   "loss": float(out["loss"].item())},
+        "roofline": {"bound": "mfma", "kernel": "grad_mfma_kernel<768>", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": TRAFFIC_BYTES,
+                     "executed_frac": round(k_exe / (prof["ms_grad"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "kernel_ms": {k: round(prof[k], 4) for k in ("ms_stats", "ms_merge", "ms_grad", "ms_reduce")},
+                     "whole_path_executed_frac": round(10.0 * B * P * d / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(q, p, r, flops_alg)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

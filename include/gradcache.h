@@ -103,6 +103,21 @@ int gc_loss_and_rep_grad_ex(gc_dtype dt, const void* q, const void* p, const int
 int gc_check_async_error(const void* workspace);
 
 /*
+ * Measurement aid for benchmarks (not part of the method; for callers that want per-phase
+ * device times without an external profiler).  gc_profile_begin(max_calls) makes
+ * every following loss call record HIP events on its stream at the phase
+ * boundaries (statistics pass | merge of split statistics and loss | gradient
+ * kernel | fixed-order sums of its split partials); gc_profile_end waits for the
+ * recorded events, writes the mean milliseconds per call of the four phases and the
+ * number of calls seen (each pointer may be NULL), and switches recording off.
+ * Host state is process-wide and not thread-safe.  Errors: GC_ERR_SHAPE
+ * (max_calls outside [1, 65536]), GC_ERR_UNSUPPORTED (begin twice / end without
+ * begin), GC_ERR_HIP.
+ */
+int gc_profile_begin(int max_calls);
+int gc_profile_end(float* ms_stats, float* ms_merge, float* ms_grad, float* ms_reduce, int* calls);
+
+/*
  * NT-Xent over n_views = 2N views (a loss variation in the sense of Step 2's
  * remark; SimCLR is cited in Related Work): z[n_views,d] bf16, rows already
  * L2-normalised; views 2k and 2k+1 are positives of each other; logits

@@ -22,6 +22,7 @@ EXPORTS = [
     "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
     "gc_ntxent_loss_and_grad_bf16", "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
     "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
+    "gc_profile_begin", "gc_profile_end",
 ]
 
 
@@ -80,6 +81,11 @@ def load():
     lib.gc_step_mlp_workspace_bytes.argtypes = [ci, ci, ci, ci, pp]
     lib.gc_step_mlp_bf16.restype = ci
     lib.gc_step_mlp_bf16.argtypes = [vp, ci, vp, ci, vp, ci, ci, pp, cf, cf, vp, pg, vp, vp, vp, vp, vp, sz, vp]
+    lib.gc_profile_begin.restype = ci
+    lib.gc_profile_begin.argtypes = [ci]
+    fp = ctypes.POINTER(ctypes.c_float)
+    lib.gc_profile_end.restype = ci
+    lib.gc_profile_end.argtypes = [fp, fp, fp, fp, ctypes.POINTER(ci)]
     _lib = lib
     return lib
 
@@ -183,6 +189,18 @@ def gc_check_async_error(workspace=None):
     if workspace is None:
         return lib.gc_check_async_error(None)
     return lib.gc_check_async_error(_ws_ptr(workspace)[0])
+
+
+def gc_profile_begin(max_calls):
+    _check(load().gc_profile_begin(int(max_calls)), "gc_profile_begin")
+
+
+def gc_profile_end():
+    """Returns dict(ms_stats, ms_merge, ms_grad, ms_reduce, calls): mean device milliseconds per call."""
+    a, b, c, d, n = ctypes.c_float(), ctypes.c_float(), ctypes.c_float(), ctypes.c_float(), ctypes.c_int()
+    _check(load().gc_profile_end(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d), ctypes.byref(n)),
+           "gc_profile_end")
+    return dict(ms_stats=a.value, ms_merge=b.value, ms_grad=c.value, ms_reduce=d.value, calls=n.value)
 
 
 def gc_ntxent_loss_and_grad_bf16(z, temp, workspace=None, stream=None):

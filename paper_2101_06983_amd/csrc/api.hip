@@ -91,15 +91,37 @@ static int own_workspace(size_t need, void** out) {
   return GC_OK;
 }
 
+// ---- measurement aid: HIP events around the phases of the loss path ------------------------------
+struct Profile {
+  bool on = false;
+  int max_calls = 0, calls = 0;
+  hipEvent_t* ev = nullptr;  // [max_calls][kMarks]
+};
+constexpr int kMarks = 5;  // start | after stats | after merge | after gradient kernel | after partial sums
+static Profile g_prof;
+
+static void prof_mark(int call, int mark, hipStream_t s) {
+  if (g_prof.on && call < g_prof.max_calls) (void)hipEventRecord(g_prof.ev[call * kMarks + mark], s);
+}
+void prof_mark_grad_kernel_done(hipStream_t s) { prof_mark(g_prof.calls, 3, s); }
+
 static int run_loss(const LossArgs& a, const LossPlan& pl) {
+  const int call = g_prof.calls;
+  prof_mark(call, 0, a.stream);
   hipError_t e = pl.use_mfma ? launch_stats_mfma(a, pl) : launch_stats_generic(a, pl);
   if (e != hipSuccess) return GC_ERR_HIP;
+  prof_mark(call, 1, a.stream);
   e = launch_stats_merge(a, pl);
   if (e != hipSuccess) return GC_ERR_HIP;
+  prof_mark(call, 2, a.stream);
   if (a.dq || a.dp || a.dz) {
-    e = pl.use_mfma ? launch_grad_mfma(a, pl) : launch_grad_generic(a, pl);
+    e = pl.use_mfma ? launch_grad_mfma(a, pl) : launch_grad_generic(a, pl);  // records mark 3 after its main kernel(s)
     if (e != hipSuccess) return GC_ERR_HIP;
+  } else {
+    prof_mark(call, 3, a.stream);
   }
+  prof_mark(call, 4, a.stream);
+  if (g_prof.on) g_prof.calls++;
   return GC_OK;
 }
 
@@ -194,6 +216,45 @@ int gc_check_async_error(const void* workspace) {
   int word = 0;
   if (hipMemcpy(&word, ws, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return GC_ERR_HIP;
   return word ? GC_ERR_POS_IDX : GC_OK;
+}
+
+int gc_profile_begin(int max_calls) {
+  if (max_calls < 1 || max_calls > (1 << 16)) return GC_ERR_SHAPE;
+  if (g_prof.ev) return GC_ERR_UNSUPPORTED;  // already open
+  g_prof.ev = new hipEvent_t[(size_t)max_calls * kMarks];
+  for (int i = 0; i < max_calls * kMarks; i++)
+    if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return GC_ERR_HIP;
+  g_prof.max_calls = max_calls;
+  g_prof.calls = 0;
+  g_prof.on = true;
+  return GC_OK;
+}
+
+int gc_profile_end(float* ms_stats, float* ms_merge, float* ms_grad, float* ms_reduce, int* calls) {
+  if (!g_prof.ev) return GC_ERR_UNSUPPORTED;
+  g_prof.on = false;
+  const int n = g_prof.calls < g_prof.max_calls ? g_prof.calls : g_prof.max_calls;
+  double acc[4] = {0, 0, 0, 0};
+  int rc = GC_OK;
+  for (int c = 0; c < n && rc == GC_OK; c++) {
+    if (hipEventSynchronize(g_prof.ev[c * kMarks + 4]) != hipSuccess) { rc = GC_ERR_HIP; break; }
+    for (int k = 0; k < 4; k++) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, g_prof.ev[c * kMarks + k], g_prof.ev[c * kMarks + k + 1]) != hipSuccess) rc = GC_ERR_HIP;
+      acc[k] += ms;
+    }
+  }
+  for (int i = 0; i < g_prof.max_calls * kMarks; i++) (void)hipEventDestroy(g_prof.ev[i]);
+  delete[] g_prof.ev;
+  g_prof.ev = nullptr;
+  if (rc != GC_OK) return rc;
+  if (ms_stats) *ms_stats = n ? (float)(acc[0] / n) : 0.f;
+  if (ms_merge) *ms_merge = n ? (float)(acc[1] / n) : 0.f;
+  if (ms_grad) *ms_grad = n ? (float)(acc[2] / n) : 0.f;
+  if (ms_reduce) *ms_reduce = n ? (float)(acc[3] / n) : 0.f;
+  if (calls) *calls = n;
+  g_prof.max_calls = g_prof.calls = 0;
+  return GC_OK;
 }
 
 size_t gc_ntxent_workspace_bytes(int n_views, int d) {

@@ -264,6 +264,7 @@ static hipError_t grad_generic_t(const LossArgs& a, const LossPlan& pl) {
                                                                             a.B, a.P, a.d, alpha2, osc, ms, dp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  prof_mark_grad_kernel_done(a.stream);
   if (a.dz) {
     const float* srcs[2] = {dq, dp};
     int counts[2] = {1, 1};

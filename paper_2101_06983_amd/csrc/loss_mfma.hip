@@ -479,7 +479,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   ga.dq_out = q_direct ? a.dq : (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
   ga.dp_out = p_direct ? a.dp : (float*)(ws + pl.off_dp_part); ga.dp_split_stride = np;
   const int nwg = ga.obQ * ga.nsq + ga.obP * ga.nsp;
-  if (nwg == 0) return hipSuccess;
+  if (nwg == 0) { prof_mark_grad_kernel_done(a.stream); return hipSuccess; }
   hipError_t e;
   switch (a.d) {
     case 128: e = grad_mfma_launch<128>(ga, nwg, a.stream); break;
@@ -491,6 +491,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
+  prof_mark_grad_kernel_done(a.stream);
   // fixed-order sums of the split partials
   if (a.dz) {
     const float* srcs[2] = {ga.dq_out, ga.dp_out};
