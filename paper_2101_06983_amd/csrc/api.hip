@@ -55,7 +55,9 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   pl.off_part_l = take((size_t)pl.stat_splits * B * 4);
   pl.off_part_idx = take((size_t)pl.stat_splits * B * 4);
   pl.off_pos = take((size_t)B * 4);
-  pl.off_lse2 = take((size_t)B * 4);
+  pl.b_pad = (B + 63) / 64 * 64;
+  pl.off_lse2 = take((size_t)pl.b_pad * 4);
+  pl.off_pos_pad = take((size_t)pl.b_pad * 4);
   pl.off_rowloss = take((size_t)B * 4);
   pl.off_dq_part = take((pl.nsq > 1 || ntxent) ? (size_t)pl.nsq * B * d * 4 : 0);
   pl.off_dp_part = take((pl.nsp > 1 || ntxent) ? (size_t)pl.nsp * P * d * 4 : 0);

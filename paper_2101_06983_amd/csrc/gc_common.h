@@ -47,7 +47,8 @@ struct LossPlan {
   int stat_cols_per_split;
   int nsq, nsp;          // stream splits of the dQ-role / dP-role workgroups of the gradient pass
   int q_stream_len, p_stream_len;  // stream rows per split (multiple of the stream tile)
-  size_t off_err, off_part_m, off_part_l, off_part_idx, off_pos, off_lse2, off_rowloss, off_dq_part,
+  int b_pad;             // B rounded up to 64: length of the padded lse2 / pos_pad arrays
+  size_t off_err, off_part_m, off_part_l, off_part_idx, off_pos, off_lse2, off_pos_pad, off_rowloss, off_dq_part,
       off_dp_part, off_pos_idx, total;
 };
 

@@ -94,13 +94,17 @@ __global__ void __launch_bounds__(256) stats_generic_kernel(const T* __restrict_
 }
 
 // Merge of the split statistics of every anchor: lse2_i, row loss (Eq. 1's summand), argmax.
+// lse2 and the copy of pos_idx are padded to b_pad rows with +inf / -1, so that the gradient pass
+// can read whole tiles without bounds checks (a padded row gives g = 0).
 __global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restrict__ part_m, const float* __restrict__ part_l,
                                                          const int* __restrict__ part_idx, const float* __restrict__ pos_t,
                                                          const int32_t* __restrict__ pos_idx, int B, int P, int nsplit,
-                                                         float* __restrict__ lse2, float* __restrict__ rowloss,
-                                                         float* __restrict__ lse_out, int32_t* __restrict__ argmax_out) {
+                                                         int b_pad, float* __restrict__ lse2, int32_t* __restrict__ pos_pad,
+                                                         float* __restrict__ rowloss, float* __restrict__ lse_out,
+                                                         int32_t* __restrict__ argmax_out) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B) return;
+  if (i >= b_pad) return;
+  if (i >= B) { lse2[i] = INFINITY; pos_pad[i] = -1; return; }
   float m = -INFINITY; int bi = 0x7fffffff;
   for (int s = 0; s < nsplit; s++) {
     float v = part_m[(size_t)s * B + i]; int x = part_idx[(size_t)s * B + i];
@@ -114,6 +118,7 @@ __global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restric
   float l2 = m + log2f(l);
   lse2[i] = l2;
   int r = pos_idx[i];
+  pos_pad[i] = r;
   bool ok = (r >= 0 && r < P);
   rowloss[i] = ok ? (l2 - pos_t[i]) * kLn2 : NAN;
   if (lse_out) lse_out[i] = l2 * kLn2;
@@ -239,10 +244,10 @@ hipError_t launch_stats_generic(const LossArgs& a, const LossPlan& pl) {
 
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
-  stats_merge_kernel<<<(a.B + 255) / 256, 256, 0, a.stream>>>(
+  stats_merge_kernel<<<(pl.b_pad + 255) / 256, 256, 0, a.stream>>>(
       (const float*)(ws + pl.off_part_m), (const float*)(ws + pl.off_part_l), (const int*)(ws + pl.off_part_idx),
-      (const float*)(ws + pl.off_pos), a.pos_idx, a.B, a.P, pl.stat_splits, (float*)(ws + pl.off_lse2),
-      (float*)(ws + pl.off_rowloss), a.lse, a.argmax);
+      (const float*)(ws + pl.off_pos), a.pos_idx, a.B, a.P, pl.stat_splits, pl.b_pad, (float*)(ws + pl.off_lse2),
+      (int32_t*)(ws + pl.off_pos_pad), (float*)(ws + pl.off_rowloss), a.lse, a.argmax);
   loss_reduce_kernel<<<1, 1024, 0, a.stream>>>((const float*)(ws + pl.off_rowloss), a.pos_idx, a.B, a.P, a.loss,
                                                (int*)(ws + pl.off_err));
   return hipGetLastError();

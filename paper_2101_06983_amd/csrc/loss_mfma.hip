@@ -258,10 +258,12 @@ struct GradCfg {
   static constexpr int DS = D / 4;        // columns per wave
   static constexpr int KS = DS / 16;      // MFMA k-steps of phase 1
   static constexpr int CT = DS / 32;      // 32-column output tiles of phase 2
-  static constexpr int LD = DS + 8;       // LDS row stride of the streamed slice (bf16 elements)
   static constexpr int C16 = DS / 8;      // 16-byte chunks per slice row
-  static constexpr int RS_WAVE = GR_T * LD;             // elements per wave slice
-  static constexpr int RS_BYTES = 4 * RS_WAVE * 2;      // one stage, all waves
+  static constexpr int SLOTS = C16 + 1;   // + one 16-byte pad chunk per row (bank skew)
+  static constexpr int LD = SLOTS * 8;    // LDS row stride of the streamed slice (bf16 elements)
+  static constexpr int NI = (GR_T * SLOTS + 63) / 64;   // direct-to-LDS load instructions per tile slice
+  static constexpr int RS_WAVE_BYTES = NI * 1024;       // one wave, one stage
+  static constexpr int RS_BYTES = 2 * 4 * RS_WAVE_BYTES;  // two stages, four waves
   static constexpr int X_BYTES = 4 * 4 * 2 * 64 * 16;   // [src][dst][quad][lane] float4
   static constexpr int G_BYTES = 4 * 64 * 16;           // [frag][lane] bf16x8
   static constexpr int SMEM = RS_BYTES + X_BYTES + G_BYTES;
@@ -270,8 +272,8 @@ struct GradCfg {
 struct GradArgs {
   const unsigned short* Q;
   const unsigned short* P;
-  const int32_t* pos_idx;
-  const float* lse2;
+  const int32_t* pos_pad;   // pos_idx copied and padded with -1 to a multiple of 64 rows
+  const float* lse2;        // log2-domain log-sum-exp per anchor, padded with +inf
   int B, Pn;
   float alpha2, out_scale;
   int mask_self;
@@ -280,6 +282,13 @@ struct GradArgs {
   float* dq_out; size_t dq_split_stride;  // split s writes dq_out + s * stride
   float* dp_out; size_t dp_split_stride;
 };
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + lane * 16 (wave-uniform
+// base in M0).  The compiler does not see the LDS write: the reader waits with wait_vmem0().
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void wait_vmem0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int D, bool OWNER_IS_Q>
 __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
@@ -292,7 +301,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   const int a0 = oblk * GR_OWN;
   const int sbeg = split * slen, send = min(Nr, sbeg + slen);
 
-  unsigned short* Rs = (unsigned short*)smem + w * C::RS_WAVE;
+  unsigned char* rs_wave = smem + w * (2 * C::RS_WAVE_BYTES);  // this wave's two stages
+  const unsigned rs_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)rs_wave);
   f32x4* X = (f32x4*)(smem + C::RS_BYTES);
   bf16x8* Gf = (bf16x8*)(smem + C::RS_BYTES + C::X_BYTES);
 
@@ -310,9 +320,27 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   const int a_q = a0 + 32 * nt_q + ln;  // owner row of every value this lane finishes
   float lse_a = 0.f; int r_a = -1;
   if (OWNER_IS_Q) {
-    lse_a = ga.lse2[min(a_q, No - 1)];
-    r_a = ga.pos_idx[min(a_q, No - 1)];
+    lse_a = ga.lse2[a_q];      // padded: +inf past the end, so g = 0 there
+    r_a = ga.pos_pad[a_q];
   }
+
+  // per-lane source offsets of the direct-to-LDS loads (slot q = it * 64 + lane -> row, chunk)
+  int src_off[C::NI];  // element offset inside the streamed tile: row * D + chunk * 8
+  int src_row[C::NI];
+#pragma unroll
+  for (int it = 0; it < C::NI; it++) {
+    const int q = it * 64 + lane;
+    const int row = min(q / C::SLOTS, GR_T - 1), c = min(q % C::SLOTS, C::C16 - 1);
+    src_row[it] = row;
+    src_off[it] = w * C::DS + c * 8;
+  }
+  auto prefetch = [&](int t0, int stage) {
+#pragma unroll
+    for (int it = 0; it < C::NI; it++) {
+      const int grow = min(t0 + src_row[it], Nr - 1);
+      dma16(R + (size_t)grow * D + src_off[it], rs_base + stage * C::RS_WAVE_BYTES + it * 1024);
+    }
+  };
 
   f32x16 acc[2][C::CT];
 #pragma unroll
@@ -322,16 +350,34 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[mt][ct][r] = 0.f;
 
-  for (int t0 = sbeg; t0 < send; t0 += GR_T) {
-    // ---- stage this wave's slice of the streamed tile --------------------------------------------
+  // softmax statistics of the streamed rows this lane finishes (dP role), fetched one tile ahead
+  const int brel = 16 * s_q + 4 * h;  // rows brel + {0..3} and brel + 8 + {0..3}
+  f32x4 nx_lse[2]; i32x4 nx_pos[2];
+  auto fetch_rowinfo = [&](int t0) {
+    if (!OWNER_IS_Q) {
 #pragma unroll
-    for (int it = 0; it < (GR_T * C::C16) / 64; it++) {
-      const int qd = it * 64 + lane, row = qd / C::C16, c16 = qd % C::C16;
-      const int grow = min(t0 + row, Nr - 1);
-      u32x4 v = *(const u32x4*)(R + (size_t)grow * D + w * C::DS + c16 * 8);
-      *(u32x4*)(Rs + row * C::LD + c16 * 8) = v;
+      for (int g = 0; g < 2; g++) {
+        nx_lse[g] = *(const f32x4*)(ga.lse2 + t0 + brel + 8 * g);
+        nx_pos[g] = *(const i32x4*)(ga.pos_pad + t0 + brel + 8 * g);
+      }
     }
-    __syncthreads();
+  };
+
+  fetch_rowinfo(sbeg);
+  prefetch(sbeg, 0);
+  int stage = 0;
+  for (int t0 = sbeg; t0 < send; t0 += GR_T, stage ^= 1) {
+    wait_vmem0();  // tile t0 (issued one step ago) has landed in this wave's LDS stage
+    f32x4 cur_lse[2]; i32x4 cur_pos[2];
+    if (!OWNER_IS_Q) {
+#pragma unroll
+      for (int g = 0; g < 2; g++) { cur_lse[g] = nx_lse[g]; cur_pos[g] = nx_pos[g]; }
+    }
+    if (t0 + GR_T < send) {
+      fetch_rowinfo(t0 + GR_T);
+      prefetch(t0 + GR_T, stage ^ 1);
+    }
+    const unsigned short* Rs = (const unsigned short*)(rs_wave + stage * C::RS_WAVE_BYTES);
     // ---- phase 1: partial S^T over this wave's k-slice ---------------------------------------------
     f32x16 sacc[2];
 #pragma unroll
@@ -364,16 +410,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     for (int src = 0; src < 4; src++) {  // fixed order: bit-identical whichever wave sums
 #pragma unroll
       for (int qd = 0; qd < 2; qd++) {
-        f32x4 own;  // this wave's own partial of its quarter (static register picks + selects)
-#pragma unroll
-        for (int x = 0; x < 4; x++) {
-          const float lo = s_q ? sacc[0][8 + 4 * qd + x] : sacc[0][4 * qd + x];
-          const float hi = s_q ? sacc[1][8 + 4 * qd + x] : sacc[1][4 * qd + x];
-          own[x] = nt_q ? hi : lo;
-        }
-        // reading the (unused) diagonal slot keeps the loop branch-free; it holds finite junk or zeros
         f32x4 v = X[((src * 4 + w) * 2 + qd) * 64 + lane];
-        v = (src == w) ? own : v;
 #pragma unroll
         for (int x = 0; x < 4; x++) sv[4 * qd + x] += v[x];
       }
@@ -384,13 +421,12 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       float gv[8];
 #pragma unroll
       for (int e = 0; e < 8; e++) {
-        const int b = t0 + 16 * s_q + 8 * (e >> 2) + 4 * h + (e & 3);  // streamed row
+        const int b = t0 + brel + 8 * (e >> 2) + (e & 3);  // streamed row
         float lse_i; int r_i, i, j;
         if (OWNER_IS_Q) {
           lse_i = lse_a; r_i = r_a; i = a_q; j = b;
         } else {
-          const int bc = min(b, Nr - 1);
-          lse_i = ga.lse2[bc]; r_i = ga.pos_idx[bc]; i = b; j = a_q;
+          lse_i = cur_lse[e >> 2][e & 3]; r_i = cur_pos[e >> 2][e & 3]; i = b; j = a_q;
         }
         float p = fast_exp2(sv[e] * ga.alpha2 - lse_i);
         float g = p - ((j == r_i) ? 1.f : 0.f);
@@ -425,7 +461,6 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         acc[1][ct] = mfma32(gf[1][s], bfr, acc[1][ct]);
       }
     }
-    __syncthreads();  // the slice buffer is rewritten by the next step
   }
 
   // ---- epilogue: scale by alpha / B and store the owned rows ---------------------------------------------------------
@@ -467,7 +502,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
   GradArgs ga{};
   ga.Q = (const unsigned short*)a.q; ga.P = (const unsigned short*)a.p;
-  ga.pos_idx = a.pos_idx; ga.lse2 = (const float*)(ws + pl.off_lse2);
+  ga.pos_pad = (const int32_t*)(ws + pl.off_pos_pad); ga.lse2 = (const float*)(ws + pl.off_lse2);
   ga.B = a.B; ga.Pn = a.P;
   ga.alpha2 = a.alpha * kLog2e; ga.out_scale = a.alpha / (float)a.B;
   ga.mask_self = (a.flags & GC_MASK_SELF) ? 1 : 0;
