@@ -12,6 +12,8 @@
 //   C/D:        lane l, register r holds D[m = 8 * (r / 4) + 4 * (l / 32) + r % 4][n = l % 32]
 // The reduction over targets is put on the M axis (registers) so that every lane owns one
 // anchor column and the softmax statistics need no cross-lane traffic inside a tile.
+#include <type_traits>
+
 #include "gc_common.h"
 
 namespace gc {
@@ -240,33 +242,49 @@ hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
 // ===========================================================================
 // Gradient pass.  Workgroup = 256 threads = 4 waves, one per SIMD (up to 512 registers a lane).
 // It owns 64 rows of the output (dQ rows: "owner" = Q, streamed = P; dP rows: owner = P,
-// streamed = Q) and walks the streamed matrix 32 rows at a time:
-//   phase 1  S^T tile [32 streamed x 64 owner] = R_tile * O^T.  The contraction over d is split
-//            four ways over the waves (wave w takes columns [w*D/4, (w+1)*D/4)), so that each
-//            wave keeps its slice of the owner rows in registers for the whole kernel and only
-//            ever touches its own D/4-column slice of every streamed tile.
-//   exchange the four partial tiles are summed through LDS (each wave reduces one quarter in a
-//            fixed order), turned into g = 2^(t - lse2) - [j = r_i] (Eq. 5 / Eq. 6 with eps_j of
-//            Eq. 7 folded in), rounded to bf16 and published as ready-made MFMA A fragments.
-//   phase 2  dO[64 x D/4 slice] += g[64 x 32] * R_tile[32 x D/4 slice]; the streamed slice is read
-//            back from the same LDS buffer with transposing loads (ds_read_b64_tr_b16).
+// streamed = Q) and walks the streamed matrix 16 rows at a time:
+//   phase 1  S^T tile [16 streamed x 64 owner] = R_tile * O^T (v_mfma_f32_16x16x32_bf16).  The
+//            contraction over d is split four ways over the waves (wave w takes columns
+//            [w*D/4, (w+1)*D/4)), so that each wave keeps its slice of the owner rows in
+//            registers for the whole kernel and only ever touches its own D/4-column slice of
+//            every streamed tile (a wave-private LDS ring of four stages, filled by direct
+//            global->LDS loads issued three tiles ahead).
+//   exchange the four partial tiles are summed through LDS (each wave finishes 16 owner rows, in
+//            a fixed order), turned into g = 2^(t - lse2) - [j = r_i] (Eq. 5 / Eq. 6 with eps_j
+//            of Eq. 7 folded in), rounded to bf16 and published as ready-made MFMA A fragments.
+//   phase 2  dO[64 x D/4 slice] += g[64 x 16] * R_tile[16 x D/4 slice] (v_mfma_f32_32x32x16_bf16);
+//            the streamed slice is read back from the same LDS stage with transposing loads
+//            (ds_read_b64_tr_b16).
+// The three steps of consecutive tiles are software-pipelined so that one workgroup barrier per
+// tile suffices: iteration u publishes the partials of tile u+1 and the fragments of tile u,
+// then runs phase 1 of tile u+2 and phase 2 of tile u while the exchanged data is in flight.
+//
+// 16x16x32 layouts: A lane l holds A[m = l % 16][k = 8 * (l / 16) + 0..7], B likewise with n,
+// D register r of lane l holds D[m = 4 * (l / 16) + r][n = l % 16].
+// ds_read_b64_tr_b16: in each group of 16 lanes, lane j supplies the address of 4 consecutive
+// 16-bit elements; lane i receives element (i % 4) of the addresses of lanes i / 4 + {0, 4, 8, 12}.
 // ===========================================================================
-constexpr int GR_OWN = 64, GR_T = 32;
+constexpr int GR_OWN = 64, GR_T = 16, GR_STAGES = 4;
 
 template <int D>
 struct GradCfg {
   static constexpr int DS = D / 4;        // columns per wave
-  static constexpr int KS = DS / 16;      // MFMA k-steps of phase 1
+  static constexpr int KS = DS / 32;      // MFMA k-steps of phase 1 (k = 32 each)
   static constexpr int CT = DS / 32;      // 32-column output tiles of phase 2
   static constexpr int C16 = DS / 8;      // 16-byte chunks per slice row
   static constexpr int SLOTS = C16 + 1;   // + one 16-byte pad chunk per row (bank skew)
   static constexpr int LD = SLOTS * 8;    // LDS row stride of the streamed slice (bf16 elements)
-  static constexpr int NI = (GR_T * SLOTS + 63) / 64;   // direct-to-LDS load instructions per tile slice
-  static constexpr int RS_WAVE_BYTES = NI * 1024;       // one wave, one stage
-  static constexpr int RS_BYTES = 2 * 4 * RS_WAVE_BYTES;  // two stages, four waves
-  static constexpr int X_BYTES = 4 * 4 * 2 * 64 * 16;   // [src][dst][quad][lane] float4
-  static constexpr int G_BYTES = 4 * 64 * 16;           // [frag][lane] bf16x8
+  static constexpr int TILE_SLOTS = GR_T * SLOTS;       // 16-byte slots holding tile data
+  static constexpr int NI = (TILE_SLOTS + 63) / 64;     // direct-to-LDS load instructions per tile slice
+  static constexpr int STAGE = NI * 1024;               // bytes: one wave, one stage
+  static constexpr int RS_BYTES = 4 * GR_STAGES * STAGE;
+  static constexpr int X_BYTES = 2 * 4 * 4 * 64 * 16;   // [parity][src][dst][lane] float4
+  static constexpr int G_BYTES = 2 * 2 * 64 * 16;       // [parity][m-tile][lane] bf16x8
   static constexpr int SMEM = RS_BYTES + X_BYTES + G_BYTES;
+  // the slots after the tile data in the last load instruction carry the row statistics of the
+  // streamed rows (dP role): 4 slots of lse2, 4 slots of pos_idx
+  static_assert(NI * 64 - TILE_SLOTS >= 8, "no room for the row statistics");
+  static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
 
 struct GradArgs {
@@ -283,62 +301,89 @@ struct GradArgs {
   float* dp_out; size_t dp_split_stride;
 };
 
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
 // 16 bytes per lane from global memory straight into LDS at lds_base + lane * 16 (wave-uniform
-// base in M0).  The compiler does not see the LDS write: the reader waits with wait_vmem0().
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+// base in M0).  The compiler does not see these loads: the reader waits with wait_vmem<N>().
+__device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void dma16v(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
-__device__ __forceinline__ void wait_vmem0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <int N>
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 template <int D, bool OWNER_IS_Q>
 __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
   using C = GradCfg<D>;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, ln = lane & 31;
+  const int l16 = lane & 15, g16 = lane >> 4;
   const unsigned short* O = OWNER_IS_Q ? ga.Q : ga.P;
   const unsigned short* R = OWNER_IS_Q ? ga.P : ga.Q;
   const int No = OWNER_IS_Q ? ga.B : ga.Pn, Nr = OWNER_IS_Q ? ga.Pn : ga.B;
   const int slen = OWNER_IS_Q ? ga.q_stream_len : ga.p_stream_len;
   const int a0 = oblk * GR_OWN;
   const int sbeg = split * slen, send = min(Nr, sbeg + slen);
+  const int nt = (send - sbeg + GR_T - 1) / GR_T;  // streamed tiles of this workgroup (>= 1)
 
-  unsigned char* rs_wave = smem + w * (2 * C::RS_WAVE_BYTES);  // this wave's two stages
+  unsigned char* rs_wave = smem + w * (GR_STAGES * C::STAGE);  // this wave's ring of stages
   const unsigned rs_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)rs_wave);
-  f32x4* X = (f32x4*)(smem + C::RS_BYTES);
-  bf16x8* Gf = (bf16x8*)(smem + C::RS_BYTES + C::X_BYTES);
+  unsigned char* Xb = smem + C::RS_BYTES;
+  unsigned char* Gb = smem + C::RS_BYTES + C::X_BYTES;
 
-  // owner slice, kept in registers as MFMA B fragments of phase 1
-  bf16x8 ofrag[2][C::KS];
+  // owner slice, kept in registers as MFMA B fragments of phase 1 (16 owner rows per fragment)
+  bf16x8 ofrag[4][C::KS];
 #pragma unroll
-  for (int nt = 0; nt < 2; nt++) {
-    const int row = min(a0 + 32 * nt + ln, No - 1);
+  for (int nq = 0; nq < 4; nq++) {
+    const int row = min(a0 + 16 * nq + l16, No - 1);
 #pragma unroll
     for (int ks = 0; ks < C::KS; ks++)
-      ofrag[nt][ks] = *(const bf16x8*)(O + (size_t)row * D + w * C::DS + 16 * ks + 8 * h);
+      ofrag[nq][ks] = *(const bf16x8*)(O + (size_t)row * D + w * C::DS + 32 * ks + 8 * g16);
   }
-  // the quarter of the score tile this wave finishes: owner column block nt_q, streamed rows 16*s_q + ...
-  const int nt_q = w >> 1, s_q = w & 1;
-  const int a_q = a0 + 32 * nt_q + ln;  // owner row of every value this lane finishes
+  // this wave finishes the scores of owner rows 16 w .. 16 w + 15; a lane holds streamed rows 4 * g16 + 0..3
+  const int a_q = a0 + 16 * w + l16;
   float lse_a = 0.f; int r_a = -1;
   if (OWNER_IS_Q) {
     lse_a = ga.lse2[a_q];      // padded: +inf past the end, so g = 0 there
     r_a = ga.pos_pad[a_q];
   }
 
-  // per-lane source offsets of the direct-to-LDS loads (slot q = it * 64 + lane -> row, chunk)
-  int src_off[C::NI];  // element offset inside the streamed tile: row * D + chunk * 8
-  int src_row[C::NI];
+  // per-lane byte offsets of the direct-to-LDS loads inside a streamed tile (slot q = it * 64 + lane
+  // -> row, chunk); a full tile needs no clamping, the ragged last tile recomputes them
+  unsigned src_off[C::NI];
 #pragma unroll
   for (int it = 0; it < C::NI; it++) {
     const int q = it * 64 + lane;
     const int row = min(q / C::SLOTS, GR_T - 1), c = min(q % C::SLOTS, C::C16 - 1);
-    src_row[it] = row;
-    src_off[it] = w * C::DS + c * 8;
+    src_off[it] = (unsigned)((row * D + w * C::DS + c * 8) * 2);
   }
-  auto prefetch = [&](int t0, int stage) {
+  const int q_last = (C::NI - 1) * 64 + lane;  // slot of this lane in the last load instruction
+  auto prefetch = [&](int u, bool known_full) {  // tile u -> stage u & 3
+    const int t0 = sbeg + u * GR_T;
+    const unsigned short* tile = R + (size_t)t0 * D;  // wave-uniform
+    const unsigned lds0 = rs_base + (u & (GR_STAGES - 1)) * C::STAGE;
+    const bool full = known_full || (t0 + GR_T <= Nr);
 #pragma unroll
     for (int it = 0; it < C::NI; it++) {
-      const int grow = min(t0 + src_row[it], Nr - 1);
-      dma16(R + (size_t)grow * D + src_off[it], rs_base + stage * C::RS_WAVE_BYTES + it * 1024);
+      unsigned off = src_off[it];
+      if (!full) {
+        const int q = it * 64 + lane;
+        const int row = min(min(q / C::SLOTS, GR_T - 1), Nr - 1 - t0), c = min(q % C::SLOTS, C::C16 - 1);
+        off = (unsigned)((row * D + w * C::DS + c * 8) * 2);
+      }
+      if (OWNER_IS_Q || it + 1 < C::NI) {
+        dma16(tile, off, lds0 + it * 1024);
+      } else {
+        // last instruction of the dP role: slots TILE_SLOTS..+3 fetch lse2[t0 .. t0+15], the next four pos_pad
+        const char* ptr = (const char*)tile + off;
+        const int e = q_last - C::TILE_SLOTS;
+        if (e >= 0 && e < 4) ptr = (const char*)(ga.lse2 + t0 + 4 * e);
+        if (e >= 4 && e < 8) ptr = (const char*)(ga.pos_pad + t0 + 4 * (e - 4));
+        dma16v(ptr, lds0 + it * 1024);
+      }
     }
   };
 
@@ -350,118 +395,114 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[mt][ct][r] = 0.f;
 
-  // softmax statistics of the streamed rows this lane finishes (dP role), fetched one tile ahead
-  const int brel = 16 * s_q + 4 * h;  // rows brel + {0..3} and brel + 8 + {0..3}
-  f32x4 nx_lse[2]; i32x4 nx_pos[2];
-  auto fetch_rowinfo = [&](int t0) {
-    if (!OWNER_IS_Q) {
+  f32x4 sacc[4];  // partial S^T of the tile most recently through phase 1: [owner 16-block]
+  auto phase1 = [&](int u) {
+    const unsigned short* Rs = (const unsigned short*)(rs_wave + (u & (GR_STAGES - 1)) * C::STAGE);
 #pragma unroll
-      for (int g = 0; g < 2; g++) {
-        nx_lse[g] = *(const f32x4*)(ga.lse2 + t0 + brel + 8 * g);
-        nx_pos[g] = *(const i32x4*)(ga.pos_pad + t0 + brel + 8 * g);
-      }
+    for (int nq = 0; nq < 4; nq++) sacc[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ks++) {
+      const bf16x8 af = *(const bf16x8*)(Rs + l16 * C::LD + 32 * ks + 8 * g16);
+#pragma unroll
+      for (int nq = 0; nq < 4; nq++) sacc[nq] = mfma16(af, ofrag[nq][ks], sacc[nq]);
+    }
+  };
+  auto phase2 = [&](int u, const bf16x8 (&gf)[2]) {
+    const unsigned short* Rs = (const unsigned short*)(rs_wave + (u & (GR_STAGES - 1)) * C::STAGE);
+    const int col = 16 * (g16 & 1) + 4 * (lane & 3);
+    const int row = 8 * h + (l16 >> 2);
+#pragma unroll
+    for (int ct = 0; ct < C::CT; ct++) {
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Rs + row * C::LD + 32 * ct + col));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Rs + (row + 4) * C::LD + 32 * ct + col));
+      s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      bf16x8 bfr = __builtin_bit_cast(bf16x8, bb);
+      acc[0][ct] = mfma32(gf[0], bfr, acc[0][ct]);
+      acc[1][ct] = mfma32(gf[1], bfr, acc[1][ct]);
     }
   };
 
-  fetch_rowinfo(sbeg);
-  prefetch(sbeg, 0);
-  int stage = 0;
-  for (int t0 = sbeg; t0 < send; t0 += GR_T, stage ^= 1) {
-    wait_vmem0();  // tile t0 (issued one step ago) has landed in this wave's LDS stage
-    f32x4 cur_lse[2]; i32x4 cur_pos[2];
-    if (!OWNER_IS_Q) {
+  bf16x4 gq = {0, 0, 0, 0};  // g of the tile whose scores were finished last (4 streamed rows of owner row a_q)
+
+  // One pipeline iteration (see the header comment).  STEADY: every stage is live and every tile full.
+  auto body = [&](int u, auto steady_tag) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const bool xw = STEADY || (u + 1 < nt);            // tile u+1: publish partials, finish scores
+    const bool gw = STEADY || (u >= 0);                // tile u: publish fragments, phase 2   (u < nt always)
+    const bool p1 = STEADY || (u + 2 < nt);            // tile u+2: phase 1
+    const bool pf = STEADY || (u >= 0 && u + 4 < nt);  // tile u+4: start its loads
+    const int par1 = (u + 1) & 1, par0 = u & 1;
+    if (xw) {
 #pragma unroll
-      for (int g = 0; g < 2; g++) { cur_lse[g] = nx_lse[g]; cur_pos[g] = nx_pos[g]; }
+      for (int dst = 0; dst < 4; dst++)
+        *(f32x4*)(Xb + (((par1 * 4 + w) * 4 + dst) * 64 + lane) * 16) = sacc[dst];
     }
-    if (t0 + GR_T < send) {
-      fetch_rowinfo(t0 + GR_T);
-      prefetch(t0 + GR_T, stage ^ 1);
-    }
-    const unsigned short* Rs = (const unsigned short*)(rs_wave + stage * C::RS_WAVE_BYTES);
-    // ---- phase 1: partial S^T over this wave's k-slice ---------------------------------------------
-    f32x16 sacc[2];
-#pragma unroll
-    for (int nt = 0; nt < 2; nt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) sacc[nt][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ks++) {
-      bf16x8 af = *(const bf16x8*)(Rs + ln * C::LD + 16 * ks + 8 * h);
-      sacc[0] = mfma32(af, ofrag[0][ks], sacc[0]);
-      sacc[1] = mfma32(af, ofrag[1][ks], sacc[1]);
-    }
-    // ---- exchange: hand the other waves their quarters ----------------------------------------------
-#pragma unroll
-    for (int dst = 0; dst < 4; dst++) {
-      // (the wave's own quarter is written too: one branch-free store pattern for all waves)
-#pragma unroll
-      for (int qd = 0; qd < 2; qd++) {
-        f32x4 v;
-#pragma unroll
-        for (int x = 0; x < 4; x++) v[x] = sacc[dst >> 1][8 * (dst & 1) + 4 * qd + x];
-        X[((w * 4 + dst) * 2 + qd) * 64 + lane] = v;
-      }
+    if (gw) {
+      // lane (w, l16, g16) holds rows 4 g16 + 0..3 of owner row 16 w + l16: half (g16 & 1) of the A fragment
+      // element vector of lane 16 (w & 1) + l16 + 32 (g16 >> 1) in m-tile w >> 1
+      *(bf16x4*)(Gb + (((par0 * 2 + (w >> 1)) * 64 + 16 * (w & 1) + l16 + 32 * (g16 >> 1)) * 16) + 8 * (g16 & 1)) = gq;
     }
     __syncthreads();
-    float sv[8];
+    f32x4 xr[4];
+    if (xw) {
 #pragma unroll
-    for (int e = 0; e < 8; e++) sv[e] = 0.f;
-#pragma unroll
-    for (int src = 0; src < 4; src++) {  // fixed order: bit-identical whichever wave sums
-#pragma unroll
-      for (int qd = 0; qd < 2; qd++) {
-        f32x4 v = X[((src * 4 + w) * 2 + qd) * 64 + lane];
-#pragma unroll
-        for (int x = 0; x < 4; x++) sv[4 * qd + x] += v[x];
-      }
+      for (int src = 0; src < 4; src++) xr[src] = *(const f32x4*)(Xb + (((par1 * 4 + src) * 4 + w) * 64 + lane) * 16);
     }
-    // ---- g = softmax - Y for the 8 finished scores of this lane ------------------------------------------
-    unsigned gp[4];
-    {
-      float gv[8];
+    bf16x8 gf[2];
+    if (gw) {
 #pragma unroll
-      for (int e = 0; e < 8; e++) {
-        const int b = t0 + brel + 8 * (e >> 2) + (e & 3);  // streamed row
+      for (int mt = 0; mt < 2; mt++) gf[mt] = *(const bf16x8*)(Gb + ((par0 * 2 + mt) * 64 + lane) * 16);
+    }
+    f32x4 lse_r = {0.f, 0.f, 0.f, 0.f}; i32x4 pos_r = {0, 0, 0, 0};
+    if (!OWNER_IS_Q && xw) {  // row statistics of tile u+1 ride in its LDS stage
+      const unsigned char* st = rs_wave + ((u + 1) & (GR_STAGES - 1)) * C::STAGE + C::TILE_SLOTS * 16;
+      lse_r = *(const f32x4*)(st + 16 * g16);
+      pos_r = *(const i32x4*)(st + 64 + 16 * g16);
+    }
+    if (p1) {
+      if (STEADY) wait_vmem<C::NI>(); else wait_vmem<0>();  // tile u+2 has landed (tile u+3 may be in flight)
+    }
+    f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+    if (xw) {
+#pragma unroll
+      for (int src = 0; src < 4; src++) sv += xr[src];  // fixed order: bit-identical whichever wave sums
+    }
+    if (p1) phase1(u + 2);
+    if (gw) phase2(u, gf);
+    if (xw) {
+      typedef __attribute__((ext_vector_type(4))) float f32x4v;
+      const int t1 = sbeg + (u + 1) * GR_T;
+      f32x4v gv;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int b = t1 + 4 * g16 + e;  // streamed row
         float lse_i; int r_i, i, j;
         if (OWNER_IS_Q) {
           lse_i = lse_a; r_i = r_a; i = a_q; j = b;
         } else {
-          lse_i = cur_lse[e >> 2][e & 3]; r_i = cur_pos[e >> 2][e & 3]; i = b; j = a_q;
+          lse_i = lse_r[e]; r_i = pos_r[e]; i = b; j = a_q;
         }
-        float p = fast_exp2(sv[e] * ga.alpha2 - lse_i);
-        float g = p - ((j == r_i) ? 1.f : 0.f);
-        if (b >= send || (ga.mask_self && i == j)) g = 0.f;
-        gv[e] = g;
+        const float p = fast_exp2(sv[e] * ga.alpha2 - lse_i);
+        const float g = p - ((j == r_i) ? 1.f : 0.f);
+        const bool dead = (b >= send) | ((ga.mask_self != 0) & (i == j));
+        gv[e] = dead ? 0.f : g;
       }
-#pragma unroll
-      for (int x = 0; x < 4; x++) gp[x] = pack2bf(gv[2 * x], gv[2 * x + 1]);
+      gq = __builtin_convertvector(gv, bf16x4);
     }
-    {
-      u32x4 pk = {gp[0], gp[1], gp[2], gp[3]};
-      ((u32x4*)Gf)[w * 64 + lane] = pk;  // fragment (mt = nt_q, k-step = s_q)
-    }
-    __syncthreads();
-    // ---- phase 2: dO += g * R_tile slice ---------------------------------------------------------------------
-    bf16x8 gf[2][2];
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int s = 0; s < 2; s++) gf[mt][s] = Gf[(mt * 2 + s) * 64 + lane];
-#pragma unroll
-    for (int ct = 0; ct < C::CT; ct++) {
-#pragma unroll
-      for (int s = 0; s < 2; s++) {
-        const int col = 32 * ct + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        const int row = 16 * s + 4 * h + ((lane & 15) >> 2);
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Rs + row * C::LD + col));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Rs + (row + 8) * C::LD + col));
-        s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        bf16x8 bfr = __builtin_bit_cast(bf16x8, bb);
-        acc[0][ct] = mfma32(gf[0][s], bfr, acc[0][ct]);
-        acc[1][ct] = mfma32(gf[1][s], bfr, acc[1][ct]);
-      }
-    }
-  }
+    if (pf) prefetch(u + 4, STEADY);  // a steady iteration never starts the last (possibly ragged) tile
+  };
+
+  // ---- prologue: start the first tiles, phase 1 of tile 0 ------------------------------------------------------
+#pragma unroll 1
+  for (int u = 0; u < min(nt, GR_STAGES); u++) prefetch(u, false);
+  wait_vmem<0>();
+  phase1(0);
+  body(-1, std::false_type{});
+  int u = 0;
+#pragma unroll 1
+  for (; u + 5 < nt; u++) body(u, std::true_type{});
+#pragma unroll 1
+  for (; u < nt; u++) body(u, std::false_type{});
 
   // ---- epilogue: scale by alpha / B and store the owned rows ---------------------------------------------------------
   float* out = OWNER_IS_Q ? (ga.dq_out + (size_t)split * ga.dq_split_stride) : (ga.dp_out + (size_t)split * ga.dp_split_stride);
