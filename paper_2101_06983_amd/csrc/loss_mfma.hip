@@ -272,20 +272,26 @@ struct GradCfg {
   static constexpr int KS = DS / 32;      // MFMA k-steps of phase 1 (k = 32 each)
   static constexpr int CT = DS / 32;      // 32-column output tiles of phase 2
   static constexpr int C16 = DS / 8;      // 16-byte chunks per slice row
-  static constexpr int SLOTS = C16 + 1;   // + one 16-byte pad chunk per row (bank skew)
-  static constexpr int LD = SLOTS * 8;    // LDS row stride of the streamed slice (bf16 elements)
+  // LDS layout of a streamed slice: 16 rows of C16 chunks.  When C16 = 8 (mod 16) the rows are
+  // stored unpadded with the low three bits of the chunk index XORed by swz3(row): the 16 rows
+  // of a phase-1 fragment read and the 4 rows x 4 chunks of a transposing phase-2 read then fall
+  // into 16 different 16-byte bank groups.  Other widths keep one pad chunk per row instead.
+  static constexpr bool SWZ = (C16 % 16) == 8;
+  static constexpr int SLOTS = SWZ ? C16 : C16 + 1;
+  static constexpr int LDB = SLOTS * 16;                // LDS row stride in bytes
   static constexpr int TILE_SLOTS = GR_T * SLOTS;       // 16-byte slots holding tile data
-  static constexpr int NI = (TILE_SLOTS + 63) / 64;     // direct-to-LDS load instructions per tile slice
-  static constexpr int STAGE = NI * 1024;               // bytes: one wave, one stage
+  static constexpr int NI_Q = (TILE_SLOTS + 63) / 64;   // direct-to-LDS load instructions (1 KB each) per tile slice
+  // one more 1 KB block per stage carries the row statistics of the streamed rows (dP role):
+  // 64 bytes of lse2, then 64 bytes of pos_idx
+  static constexpr int STAGE = (NI_Q + 1) * 1024;       // bytes: one wave, one stage
   static constexpr int RS_BYTES = 4 * GR_STAGES * STAGE;
   static constexpr int X_BYTES = 2 * 4 * 4 * 64 * 16;   // [parity][src][dst][lane] float4
   static constexpr int G_BYTES = 2 * 2 * 64 * 16;       // [parity][m-tile][lane] bf16x8
   static constexpr int SMEM = RS_BYTES + X_BYTES + G_BYTES;
-  // the slots after the tile data in the last load instruction carry the row statistics of the
-  // streamed rows (dP role): 4 slots of lse2, 4 slots of pos_idx
-  static_assert(NI * 64 - TILE_SLOTS >= 8, "no room for the row statistics");
   static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
+
+__device__ __forceinline__ int swz3(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
 
 struct GradArgs {
   const unsigned short* Q;
@@ -305,20 +311,42 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// 16 bytes per lane from global memory straight into LDS at lds_base + lane * 16 (wave-uniform
-// base in M0).  The compiler does not see these loads: the reader waits with wait_vmem<N>().
-__device__ __forceinline__ void dma16(const void* gbase, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
-}
-__device__ __forceinline__ void dma16v(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+// N (1..4) direct global->LDS loads of 16 bytes per lane that share one M0 value.  Load k lands at
+// lds_base + 1024 k + lane * 16 and reads gbase + voff[k] + 1024 k: the instruction's immediate
+// offset moves both addresses, so callers pass voff[k] with 1024 k already subtracted.  The
+// compiler does not see these loads: the reader waits with wait_vmem<N>().
+template <int N>
+__device__ __forceinline__ void dma_group(const void* gbase, const unsigned* voff, unsigned lds_base) {
+  if constexpr (N == 1) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff[0]), "s"(gbase) : "memory");
+  } else if constexpr (N == 2) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\tglobal_load_lds_dwordx4 %2, %3 offset:1024"
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "s"(gbase) : "memory");
+  } else if constexpr (N == 3) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %4\n\tglobal_load_lds_dwordx4 %2, %4 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %3, %4 offset:2048"
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(gbase) : "memory");
+  } else {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\tglobal_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %3, %5 offset:2048\n\tglobal_load_lds_dwordx4 %4, %5 offset:3072"
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase) : "memory");
+  }
 }
 template <int N>
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+template <int D>
+constexpr bool grad_offsets_fit() {  // voff[k] - 1024 (k % 4) must stay >= 0 for a full tile
+  using C = GradCfg<D>;
+  for (int it = 0; it < C::NI_Q; it++)
+    if ((64 * it / C::SLOTS) * 2 * D < (it & 3) * 1024) return false;
+  return true;
+}
+
 template <int D, bool OWNER_IS_Q>
 __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
   using C = GradCfg<D>;
+  static_assert(grad_offsets_fit<D>(), "direct-to-LDS load offsets");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, ln = lane & 31;
   const int l16 = lane & 15, g16 = lane >> 4;
   const unsigned short* O = OWNER_IS_Q ? ga.Q : ga.P;
@@ -329,10 +357,31 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   const int sbeg = split * slen, send = min(Nr, sbeg + slen);
   const int nt = (send - sbeg + GR_T - 1) / GR_T;  // streamed tiles of this workgroup (>= 1)
 
-  unsigned char* rs_wave = smem + w * (GR_STAGES * C::STAGE);  // this wave's ring of stages
-  const unsigned rs_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)rs_wave);
-  unsigned char* Xb = smem + C::RS_BYTES;
-  unsigned char* Gb = smem + C::RS_BYTES + C::X_BYTES;
+  // ---- LDS map (bytes): [wave rings: 4 waves x 4 stages x STAGE][X: 2 x 4 x 4 x 1024][G: 2 x 2 x 1024]
+  constexpr int NT = C::NI_Q;                                 // load instructions that carry tile data
+  const unsigned ring_off = w * (GR_STAGES * C::STAGE);       // this wave's ring of stages
+  const unsigned ring_m0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)smem + ring_off);
+  // per-lane byte offsets; every access adds a compile-time constant (stage, parity, k-step ...)
+  auto lane_base = [&](int row, int j, int parity) __attribute__((always_inline)) -> unsigned {
+    // chunk 4 i + j of a row is stored at 4 (i ^ s2) + (j ^ s01), (s2, s01) from swz3(row): one
+    // base for even i and one for odd i, the loops add the compile-time part 64 i
+    const int sw = C::SWZ ? swz3(row) : 0;
+    const int s2 = sw >> 2, s01 = sw & 3;
+    return ring_off + (unsigned)(row * C::LDB + 16 * (j ^ s01) + (parity ? -64 * s2 : 64 * s2));
+  };
+  // phase 1 reads row l16, chunk 4 ks + g16
+  const unsigned char* p1p[2] = {smem + lane_base(l16, g16, 0), smem + lane_base(l16, g16, 1)};
+  // phase 2 (transposing read): rows 8 h + l16 / 4 (+4), chunk 4 ct + 2 (g16 & 1) + (lane & 3) / 2, 8 bytes
+  const int tr_row = 8 * h + (l16 >> 2), tr_j = 2 * (g16 & 1) + ((lane & 3) >> 1), tr_in = 8 * (lane & 1);
+  const unsigned char* p2lo[2] = {smem + lane_base(tr_row, tr_j, 0) + tr_in, smem + lane_base(tr_row, tr_j, 1) + tr_in};
+  const unsigned char* p2hi[2] = {smem + lane_base(tr_row + 4, tr_j, 0) + tr_in, smem + lane_base(tr_row + 4, tr_j, 1) + tr_in};
+  unsigned char* xwp = smem + C::RS_BYTES + (w * 4) * 1024 + lane * 16;          // + par * 16384 + dst * 1024
+  const unsigned char* xrp = smem + C::RS_BYTES + w * 1024 + lane * 16;          // + par * 16384 + src * 4096
+  // lane (w, l16, g16) finishes rows 4 g16 + 0..3 of owner row 16 w + l16: half (g16 & 1) of the A fragment
+  // elements of lane 16 (w & 1) + l16 + 32 (g16 >> 1) in m-tile w >> 1
+  unsigned char* gwp = smem + C::RS_BYTES + C::X_BYTES + ((w >> 1) * 64 + 16 * (w & 1) + l16 + 32 * (g16 >> 1)) * 16 + 8 * (g16 & 1);
+  const unsigned char* grp = smem + C::RS_BYTES + C::X_BYTES + lane * 16;        // + par * 2048 + mt * 1024
+  const unsigned char* rip = smem + ring_off + NT * 1024 + 16 * g16;             // + stage * STAGE (+ 64: pos_idx)
 
   // owner slice, kept in registers as MFMA B fragments of phase 1 (16 owner rows per fragment)
   bf16x8 ofrag[4][C::KS];
@@ -351,41 +400,41 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     r_a = ga.pos_pad[a_q];
   }
 
-  // per-lane byte offsets of the direct-to-LDS loads inside a streamed tile (slot q = it * 64 + lane
-  // -> row, chunk); a full tile needs no clamping, the ragged last tile recomputes them
-  unsigned src_off[C::NI];
+  // ---- direct-to-LDS loads of a streamed tile: slot q = it * 64 + lane -> (row, chunk) -------------------------
+  auto slot_src = [&](int q, int max_row) __attribute__((always_inline)) -> unsigned {
+    const int row = min(min(q / C::SLOTS, GR_T - 1), max_row);
+    int c = min(q % C::SLOTS, C::C16 - 1);
+    if (C::SWZ) c ^= swz3(row);
+    return (unsigned)((row * D + w * C::DS + c * 8) * 2);
+  };
+  unsigned src_off[NT];  // full tile, with the instruction offset 1024 (it % 4) pre-subtracted
 #pragma unroll
-  for (int it = 0; it < C::NI; it++) {
-    const int q = it * 64 + lane;
-    const int row = min(q / C::SLOTS, GR_T - 1), c = min(q % C::SLOTS, C::C16 - 1);
-    src_off[it] = (unsigned)((row * D + w * C::DS + c * 8) * 2);
-  }
-  const int q_last = (C::NI - 1) * 64 + lane;  // slot of this lane in the last load instruction
-  auto prefetch = [&](int u, bool known_full) {  // tile u -> stage u & 3
+  for (int it = 0; it < NT; it++) src_off[it] = slot_src(it * 64 + lane, GR_T - 1) - 1024u * (it & 3);
+  // row statistics of the streamed rows (dP role): one more load, lanes 0-3 lse2[t0 + 4 l ..], 4-7 pos_pad
+  const unsigned ri_off = (lane & 4) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 3) : 16u * (lane & 3);
+  auto prefetch = [&](int u, int stage, bool known_full) __attribute__((always_inline)) {  // tile u -> ring stage `stage`
     const int t0 = sbeg + u * GR_T;
     const unsigned short* tile = R + (size_t)t0 * D;  // wave-uniform
-    const unsigned lds0 = rs_base + (u & (GR_STAGES - 1)) * C::STAGE;
-    const bool full = known_full || (t0 + GR_T <= Nr);
+    const unsigned lds0 = ring_m0 + stage * C::STAGE;
+    if (known_full || t0 + GR_T <= Nr) {
 #pragma unroll
-    for (int it = 0; it < C::NI; it++) {
-      unsigned off = src_off[it];
-      if (!full) {
-        const int q = it * 64 + lane;
-        const int row = min(min(q / C::SLOTS, GR_T - 1), Nr - 1 - t0), c = min(q % C::SLOTS, C::C16 - 1);
-        off = (unsigned)((row * D + w * C::DS + c * 8) * 2);
+      for (int g = 0; g < NT; g += 4) {
+        constexpr int dummy = 0; (void)dummy;
+        if (NT - g >= 4) dma_group<4>(tile, &src_off[g], lds0 + g * 1024);
+        else if (NT - g == 3) dma_group<3>(tile, &src_off[g], lds0 + g * 1024);
+        else if (NT - g == 2) dma_group<2>(tile, &src_off[g], lds0 + g * 1024);
+        else dma_group<1>(tile, &src_off[g], lds0 + g * 1024);
       }
-      if (OWNER_IS_Q || it + 1 < C::NI) {
-        dma16(tile, off, lds0 + it * 1024);
-      } else {
-        // last instruction of the dP role: slots TILE_SLOTS..+3 fetch lse2[t0 .. t0+15], the next four pos_pad
-        const char* ptr = (const char*)tile + off;
-        const int e = q_last - C::TILE_SLOTS;
-        if (e >= 0 && e < 4) ptr = (const char*)(ga.lse2 + t0 + 4 * e);
-        if (e >= 4 && e < 8) ptr = (const char*)(ga.pos_pad + t0 + 4 * (e - 4));
-        dma16v(ptr, lds0 + it * 1024);
+    } else {  // ragged last tile: rows past the end re-read the last valid row (their g is forced to 0)
+#pragma unroll
+      for (int it = 0; it < NT; it++) {
+        const unsigned off = slot_src(it * 64 + lane, Nr - 1 - t0);
+        dma_group<1>(tile, &off, lds0 + it * 1024);
       }
     }
+    if (!OWNER_IS_Q) dma_group<1>(ga.lse2 + t0, &ri_off, lds0 + NT * 1024);
   };
+  constexpr int NI = OWNER_IS_Q ? NT : NT + 1;  // load instructions per tile
 
   f32x16 acc[2][C::CT];
 #pragma unroll
@@ -396,27 +445,33 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       for (int r = 0; r < 16; r++) acc[mt][ct][r] = 0.f;
 
   f32x4 sacc[4];  // partial S^T of the tile most recently through phase 1: [owner 16-block]
-  auto phase1 = [&](int u) {
-    const unsigned short* Rs = (const unsigned short*)(rs_wave + (u & (GR_STAGES - 1)) * C::STAGE);
+  bf16x8 afr[C::KS];  // phase-1 A fragments of the tile being started
+  auto p1_load = [&](int stage, int ks0, int ks1) __attribute__((always_inline)) {
 #pragma unroll
-    for (int nq = 0; nq < 4; nq++) sacc[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ks++) {
-      const bf16x8 af = *(const bf16x8*)(Rs + l16 * C::LD + 32 * ks + 8 * g16);
-#pragma unroll
-      for (int nq = 0; nq < 4; nq++) sacc[nq] = mfma16(af, ofrag[nq][ks], sacc[nq]);
-    }
+#ifndef GC_EXP_NOP1READ
+    for (int ks = ks0; ks < ks1; ks++) afr[ks] = *(const bf16x8*)(p1p[ks & 1] + stage * C::STAGE + 64 * ks);
+#else
+    for (int ks = ks0; ks < ks1; ks++) afr[ks] = ofrag[ks & 3][ks];
+#endif
   };
-  auto phase2 = [&](int u, const bf16x8 (&gf)[2]) {
-    const unsigned short* Rs = (const unsigned short*)(rs_wave + (u & (GR_STAGES - 1)) * C::STAGE);
-    const int col = 16 * (g16 & 1) + 4 * (lane & 3);
-    const int row = 8 * h + (l16 >> 2);
+  auto p1_mfma = [&](int ks0, int ks1) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = ks0; ks < ks1; ks++)
+#pragma unroll
+      for (int nq = 0; nq < 4; nq++)
+        sacc[nq] = mfma16(afr[ks], ofrag[nq][ks], ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : sacc[nq]);
+  };
+  auto phase2 = [&](int stage, const bf16x8 (&gf)[2]) {
 #pragma unroll
     for (int ct = 0; ct < C::CT; ct++) {
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Rs + row * C::LD + 32 * ct + col));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Rs + (row + 4) * C::LD + 32 * ct + col));
+#ifndef GC_EXP_NOTR
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2lo[ct & 1] + stage * C::STAGE + 64 * ct));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2hi[ct & 1] + stage * C::STAGE + 64 * ct));
+#else
+      s16x4 lo = {(short)ct, 1, 2, (short)stage}, hi = {4, 5, 6, (short)lane};
+#endif
       s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      bf16x8 bfr = __builtin_bit_cast(bf16x8, bb);
+      const bf16x8 bfr = __builtin_bit_cast(bf16x8, bb);
       acc[0][ct] = mfma32(gf[0], bfr, acc[0][ct]);
       acc[1][ct] = mfma32(gf[1], bfr, acc[1][ct]);
     }
@@ -424,79 +479,90 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 
   bf16x4 gq = {0, 0, 0, 0};  // g of the tile whose scores were finished last (4 streamed rows of owner row a_q)
 
-  // One pipeline iteration (see the header comment).  STEADY: every stage is live and every tile full.
-  auto body = [&](int u, auto steady_tag) {
+  // One pipeline iteration (see the header comment).  STEADY: every pipeline slot is live, the tiles
+  // involved are full and not the last ones.
+  auto body = [&](int u, auto steady_tag) __attribute__((always_inline)) {
     constexpr bool STEADY = decltype(steady_tag)::value;
+    const int ST0 = u & 3, ST1 = (u + 1) & 3, ST2 = (u + 2) & 3;  // ring stages of tiles u, u+1, u+2 (u+4 reuses ST0)
+    const int PAR0 = u & 1, PAR1 = PAR0 ^ 1;                      // X / G parity of tiles u and u+1
     const bool xw = STEADY || (u + 1 < nt);            // tile u+1: publish partials, finish scores
     const bool gw = STEADY || (u >= 0);                // tile u: publish fragments, phase 2   (u < nt always)
     const bool p1 = STEADY || (u + 2 < nt);            // tile u+2: phase 1
     const bool pf = STEADY || (u >= 0 && u + 4 < nt);  // tile u+4: start its loads
-    const int par1 = (u + 1) & 1, par0 = u & 1;
+    constexpr int KS_PRE = (C::KS + 1) / 2;            // k-steps of phase 1 issued before the barrier
+    __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the LDS reads with the MFMA stream
+#ifndef GC_EXP_NOX
     if (xw) {
 #pragma unroll
-      for (int dst = 0; dst < 4; dst++)
-        *(f32x4*)(Xb + (((par1 * 4 + w) * 4 + dst) * 64 + lane) * 16) = sacc[dst];
+      for (int dst = 0; dst < 4; dst++) *(f32x4*)(xwp + PAR1 * 16384 + dst * 1024) = sacc[dst];
     }
-    if (gw) {
-      // lane (w, l16, g16) holds rows 4 g16 + 0..3 of owner row 16 w + l16: half (g16 & 1) of the A fragment
-      // element vector of lane 16 (w & 1) + l16 + 32 (g16 >> 1) in m-tile w >> 1
-      *(bf16x4*)(Gb + (((par0 * 2 + (w >> 1)) * 64 + 16 * (w & 1) + l16 + 32 * (g16 >> 1)) * 16) + 8 * (g16 & 1)) = gq;
+#endif
+    if (gw) *(bf16x4*)(gwp + PAR0 * 2048) = gq;
+    if (p1) {
+      if (STEADY) wait_vmem<NI>(); else wait_vmem<0>();  // tile u+2 has landed (tile u+3 may be in flight)
+      p1_load(ST2, 0, KS_PRE);
+      p1_mfma(0, KS_PRE);  // runs while the writes above drain and the barrier gathers the waves
+      p1_load(ST2, KS_PRE, C::KS);
     }
+#ifndef GC_EXP_NOBAR
     __syncthreads();
+#endif
     f32x4 xr[4];
     if (xw) {
+#ifndef GC_EXP_NOX
 #pragma unroll
-      for (int src = 0; src < 4; src++) xr[src] = *(const f32x4*)(Xb + (((par1 * 4 + src) * 4 + w) * 64 + lane) * 16);
+      for (int src = 0; src < 4; src++) xr[src] = *(const f32x4*)(xrp + PAR1 * 16384 + src * 4096);
+#else
+#pragma unroll
+      for (int src = 0; src < 4; src++) xr[src] = sacc[src];
+#endif
     }
     bf16x8 gf[2];
     if (gw) {
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++) gf[mt] = *(const bf16x8*)(Gb + ((par0 * 2 + mt) * 64 + lane) * 16);
+      for (int mt = 0; mt < 2; mt++) gf[mt] = *(const bf16x8*)(grp + PAR0 * 2048 + mt * 1024);
     }
     f32x4 lse_r = {0.f, 0.f, 0.f, 0.f}; i32x4 pos_r = {0, 0, 0, 0};
     if (!OWNER_IS_Q && xw) {  // row statistics of tile u+1 ride in its LDS stage
-      const unsigned char* st = rs_wave + ((u + 1) & (GR_STAGES - 1)) * C::STAGE + C::TILE_SLOTS * 16;
-      lse_r = *(const f32x4*)(st + 16 * g16);
-      pos_r = *(const i32x4*)(st + 64 + 16 * g16);
+      lse_r = *(const f32x4*)(rip + ST1 * C::STAGE);
+      pos_r = *(const i32x4*)(rip + ST1 * C::STAGE + 64);
     }
-    if (p1) {
-      if (STEADY) wait_vmem<C::NI>(); else wait_vmem<0>();  // tile u+2 has landed (tile u+3 may be in flight)
-    }
-    f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+    if (p1) p1_mfma(KS_PRE, C::KS);
+    if (gw) phase2(ST0, gf);
     if (xw) {
+      const f32x4 sv = ((xr[0] + xr[1]) + xr[2]) + xr[3];  // fixed order: bit-identical whichever wave sums
+      const int b0 = sbeg + (u + 1) * GR_T + 4 * g16;      // first of this lane's 4 streamed rows
+      f32x4 gv;
 #pragma unroll
-      for (int src = 0; src < 4; src++) sv += xr[src];  // fixed order: bit-identical whichever wave sums
-    }
-    if (p1) phase1(u + 2);
-    if (gw) phase2(u, gf);
-    if (xw) {
-      typedef __attribute__((ext_vector_type(4))) float f32x4v;
-      const int t1 = sbeg + (u + 1) * GR_T;
-      f32x4v gv;
+      for (int e = 0; e < 4; e++) gv[e] = fast_exp2(sv[e] * ga.alpha2 - (OWNER_IS_Q ? lse_a : lse_r[e]));  // softmax
+      // the rest touches few tiles and is decided per wave: -1 at the positive (j == r_i), zeros for rows
+      // past the end of the split and on the diagonal (i == j)
+      bool hit_any;
+      if (OWNER_IS_Q) hit_any = (unsigned)(r_a - b0) < 4u;
+      else hit_any = (pos_r[0] == a_q) | (pos_r[1] == a_q) | (pos_r[2] == a_q) | (pos_r[3] == a_q);
+      const int t1 = b0 - 4 * g16;
+      const bool tail = !STEADY && (t1 + GR_T > send);
+      const bool diag = ga.mask_self && (t1 < a0 + GR_OWN) && (t1 + GR_T > a0);
+      if (__builtin_amdgcn_ballot_w64(hit_any) != 0 || tail || diag) {
 #pragma unroll
-      for (int e = 0; e < 4; e++) {
-        const int b = t1 + 4 * g16 + e;  // streamed row
-        float lse_i; int r_i, i, j;
-        if (OWNER_IS_Q) {
-          lse_i = lse_a; r_i = r_a; i = a_q; j = b;
-        } else {
-          lse_i = lse_r[e]; r_i = pos_r[e]; i = b; j = a_q;
+        for (int e = 0; e < 4; e++) {
+          const bool hit = OWNER_IS_Q ? (r_a - b0 == e) : (pos_r[e] == a_q);
+          if (hit) gv[e] -= 1.f;
+          if (b0 + e >= send || (ga.mask_self && b0 + e == a_q)) gv[e] = 0.f;
         }
-        const float p = fast_exp2(sv[e] * ga.alpha2 - lse_i);
-        const float g = p - ((j == r_i) ? 1.f : 0.f);
-        const bool dead = (b >= send) | ((ga.mask_self != 0) & (i == j));
-        gv[e] = dead ? 0.f : g;
       }
       gq = __builtin_convertvector(gv, bf16x4);
     }
-    if (pf) prefetch(u + 4, STEADY);  // a steady iteration never starts the last (possibly ragged) tile
+#ifndef GC_EXP_NODMA
+    if (pf) prefetch(u + 4, ST0, STEADY);  // a steady iteration never starts the last (possibly ragged) tile
+#endif
   };
-
   // ---- prologue: start the first tiles, phase 1 of tile 0 ------------------------------------------------------
 #pragma unroll 1
-  for (int u = 0; u < min(nt, GR_STAGES); u++) prefetch(u, false);
+  for (int u = 0; u < min(nt, GR_STAGES); u++) prefetch(u, u, false);
   wait_vmem<0>();
-  phase1(0);
+  p1_load(0, 0, C::KS);
+  p1_mfma(0, C::KS);
   body(-1, std::false_type{});
   int u = 0;
 #pragma unroll 1
