@@ -132,7 +132,8 @@ int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, 
 /*
  * Stand-in encoder  y = GELU(x W1 + b1) W2 + b2  (exact erf GELU), bf16 storage,
  * fp32 accumulation.  W1[din,dh], b1[dh], W2[dh,dout], b2[dout], all device bf16.
- * din, dh, dout must be multiples of 64.
+ * din must be a multiple of 64, dh and dout multiples of 128 (else
+ * GC_ERR_UNSUPPORTED); the number of rows of a sub-batch is free.
  */
 typedef struct {
   const void* W1;

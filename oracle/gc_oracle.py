@@ -26,7 +26,7 @@ from scipy.special import erf
 
 __all__ = [
     "loss_and_rep_grad", "ntxent", "mlp_forward", "mlp_backward",
-    "mlp_fullbatch_grad", "mlp_chunked_grad", "mlp_accumulation_grad",
+    "mlp_fullbatch_grad", "mlp_chunked_grad", "mlp_accumulation_grad", "round_to_bf16",
 ]
 
 
@@ -164,11 +164,31 @@ def _zeros_like_params(params):
     return {k: np.zeros_like(_f64(params[k])) for k in ("W1", "b1", "W2", "b2")}
 
 
-def mlp_fullbatch_grad(xq, xp, pos_idx, params, scale=1.0, temp=1.0):
+def round_to_bf16(a):
+    """Round-to-nearest-even of every entry to the bf16 grid (8 significant bits),
+    returned as float64.  Models ONE thing: a workload that says its stored
+    representations are bf16 (Step 1 "collect and store all representations").
+    Pinned against torch's bfloat16 cast in the tests."""
+    x = np.ascontiguousarray(np.asarray(a, dtype=np.float64).astype(np.float32))
+    u = x.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape).astype(np.float64)
+
+
+def _store(rep, rep_dtype):
+    if rep_dtype is None:
+        return rep
+    assert rep_dtype == "bf16"
+    return round_to_bf16(rep)
+
+
+def mlp_fullbatch_grad(xq, xp, pos_idx, params, scale=1.0, temp=1.0, rep_dtype=None):
     """Direct large-batch update (Eq. 2-3): encode everything, loss, backprop
-    all B + P rows at once."""
-    fq = mlp_forward(xq, params)
-    gp = mlp_forward(xp, params)
+    all B + P rows at once.  rep_dtype="bf16": the loss sees representations
+    rounded to their storage type (the gradient still flows through the
+    un-rounded encoder, as it does when the cached rows are back-propagated)."""
+    fq = _store(mlp_forward(xq, params), rep_dtype)
+    gp = _store(mlp_forward(xp, params), rep_dtype)
     out = loss_and_rep_grad(fq, gp, pos_idx, scale, temp)
     grads = _zeros_like_params(params)
     _add(grads, mlp_backward(xq, params, out["dq"]))
@@ -180,7 +200,7 @@ def _chunks(n, size):
     return [(a, min(a + size, n)) for a in range(0, n, size)]
 
 
-def mlp_chunked_grad(xq, xp, pos_idx, params, chunk_q, chunk_p, scale=1.0, temp=1.0):
+def mlp_chunked_grad(xq, xp, pos_idx, params, chunk_q, chunk_p, scale=1.0, temp=1.0, rep_dtype=None):
     """Gradient Cache, Steps 1-3: graph-less forward per sub-batch, loss and
     representation-gradient cache on the stored representations, then per
     sub-batch re-encode and backprop of the cached rows (Eq. 8-9).  Sub-batches
@@ -188,8 +208,8 @@ def mlp_chunked_grad(xq, xp, pos_idx, params, chunk_q, chunk_p, scale=1.0, temp=
     xq = _f64(xq)
     xp = _f64(xp)
     # Step 1
-    fq = np.concatenate([mlp_forward(xq[a:b], params) for a, b in _chunks(len(xq), chunk_q)])
-    gp = np.concatenate([mlp_forward(xp[a:b], params) for a, b in _chunks(len(xp), chunk_p)])
+    fq = _store(np.concatenate([mlp_forward(xq[a:b], params) for a, b in _chunks(len(xq), chunk_q)]), rep_dtype)
+    gp = _store(np.concatenate([mlp_forward(xp[a:b], params) for a, b in _chunks(len(xp), chunk_p)]), rep_dtype)
     # Step 2
     out = loss_and_rep_grad(fq, gp, pos_idx, scale, temp)
     u, v = out["dq"], out["dp"]          # the Representation Gradient Cache

@@ -1,0 +1,105 @@
+"""GPU parity of the stand-in encoder steps (graph-less forward, chunk surrogate
+backward, whole Gradient Cache step) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gc_oracle as O
+from paper_2101_06983_amd import binding as gc
+from paper_2101_06983_amd import synth
+from parity import TOL_BF16, relerr, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+# A value stored in bf16 may land on the neighbouring bf16 number on the two sides: one ulp (2^-8)
+# of the largest entry on top of the arithmetic tolerance.
+TOL_STORED = TOL_BF16 + 2.0 ** -8
+# End to end (Steps 1-3) the representations the loss sees are such stored values, so the scores of
+# the two sides differ by more than arithmetic error alone; every stage is held to TOL_BF16 on its
+# own in the tests above and in the loss parity tests, the chained result to three times that.
+TOL_CHAIN = 3 * TOL_BF16
+
+
+def widen_params(params):
+    return {k: synth.widen(v) for k, v in params.items()}
+
+
+def dev_params(params):
+    return {k: v.to(DEV) for k, v in params.items()}
+
+
+def small_problem(B=48, P=96, din=128, dh=256, dout=128, seed=9):
+    return synth.mlp_problem(B, P, din, dh, dout, seed=synth.SEED0 + seed)
+
+
+@pytest.mark.parametrize("rows", [1, 32, 40, 100])
+def test_forward_nograd(rows):
+    xq, _, _, params = small_problem(B=rows)
+    want = O.mlp_forward(synth.widen(xq), widen_params(params))
+    y = gc.gc_mlp_forward_nograd_bf16(xq.to(DEV), dev_params(params))
+    torch.cuda.synchronize()
+    assert relerr(to_np(y), want) <= TOL_STORED
+
+
+@pytest.mark.parametrize("rows", [1, 16, 32, 45])
+def test_chunk_surrogate_backward(rows):
+    xq, _, _, params = small_problem(B=rows)
+    g = np.random.default_rng(rows)
+    u = torch.from_numpy((g.standard_normal((rows, 128)) * 1e-3).astype(np.float32))
+    want = O.mlp_backward(synth.widen(xq), widen_params(params), synth.widen(u))
+    dp = dev_params(params)
+    grads = gc.zero_mlp_grads(dp)
+    gc.gc_chunk_surrogate_backward_bf16(xq.to(DEV), dp, u.to(DEV), grads)
+    torch.cuda.synchronize()
+    for k in ("W1", "b1", "W2", "b2"):
+        assert relerr(to_np(grads[k]), want[k]) <= TOL_BF16, k
+    # accumulation (+=): a second call doubles the sums
+    gc.gc_chunk_surrogate_backward_bf16(xq.to(DEV), dp, u.to(DEV), grads)
+    torch.cuda.synchronize()
+    for k in ("W1", "b1", "W2", "b2"):
+        assert relerr(to_np(grads[k]), 2 * want[k]) <= TOL_BF16, k
+
+
+@pytest.mark.parametrize("cq,cp", [(16, 16), (32, 32), (7, 24), (48, 96)])
+def test_step_small_matches_fullbatch_oracle(cq, cp):
+    xq, xp, r, params = small_problem()
+    # the workload stores representations in bf16: the oracle rounds F, G the same way before Step 2
+    want = O.mlp_fullbatch_grad(synth.widen(xq), synth.widen(xp), synth.widen(r), widen_params(params), 1.0, 0.05,
+                                rep_dtype="bf16")
+    out = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), cq, cp, dev_params(params), 1.0, 0.05, keep=True)
+    torch.cuda.synchronize()
+    assert abs(out["loss"].item() - want["loss"]) <= TOL_BF16 * abs(want["loss"])
+    assert relerr(to_np(out["dq"]), want["dq"]) <= TOL_CHAIN
+    assert relerr(to_np(out["dp"]), want["dp"]) <= TOL_CHAIN
+    for k in ("W1", "b1", "W2", "b2"):
+        assert relerr(to_np(out["grads"][k]), want["grads"][k]) <= TOL_CHAIN, k
+
+
+def test_chunking_does_not_change_the_update():
+    # the method's exactness claim (Sec. "Gradient Cache Technique", Step 3): any sub-batching gives the
+    # full-batch gradient; on the GPU only the fp32 summation order differs
+    xq, xp, r, params = small_problem()
+    dp = dev_params(params)
+    a = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 48, 96, dp, 1.0, 0.05)
+    b = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 16, 8, dp, 1.0, 0.05)
+    c = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 16, 8, dp, 1.0, 0.05)
+    torch.cuda.synchronize()
+    assert a["loss"].item() == b["loss"].item()
+    for k in ("W1", "b1", "W2", "b2"):
+        assert relerr(to_np(b["grads"][k]), to_np(a["grads"][k])) <= 1e-5, k
+        assert torch.equal(b["grads"][k], c["grads"][k]), k      # run-to-run reproducible
+
+
+def test_config5_full_size():
+    xq, xp, r, params = synth.mlp_problem()
+    want = O.mlp_chunked_grad(synth.widen(xq), synth.widen(xp), synth.widen(r), widen_params(params), 32, 32,
+                              rep_dtype="bf16")
+    out = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 32, 32, dev_params(params), keep=True)
+    torch.cuda.synchronize()
+    assert abs(out["loss"].item() - want["loss"]) <= TOL_BF16 * abs(want["loss"])
+    assert relerr(to_np(out["q"]), want["q"]) <= TOL_STORED
+    assert relerr(to_np(out["p"]), want["p"]) <= TOL_STORED
+    assert relerr(to_np(out["dq"]), want["dq"]) <= TOL_CHAIN
+    assert relerr(to_np(out["dp"]), want["dp"]) <= TOL_CHAIN
+    for k in ("W1", "b1", "W2", "b2"):
+        assert relerr(to_np(out["grads"][k]), want["grads"][k]) <= TOL_CHAIN, k

@@ -327,6 +327,23 @@ def test_negative_control_accumulation_differs():
     assert_close_norm(one["grads"]["W1"], full["grads"]["W1"], 1e-13)
 
 
+def test_round_to_bf16_matches_torch_cast_and_keeps_exactness():
+    g = rng(70)
+    a = np.concatenate([g.standard_normal(4000) * 10.0 ** g.integers(-6, 6, 4000), [0.0, 1.0, -1.0, 1.00390625, 1.01171875]])
+    want = torch.tensor(a, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(a), want)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.round_to_bf16([1.00390625])[0] == 1.0 and O.round_to_bf16([1.01171875])[0] == 1.015625
+    # with stored-representation rounding the chunked and full-batch updates still agree (same rounded F, G)
+    xq, xp, r, params = small_mlp(seed=64)
+    full = O.mlp_fullbatch_grad(xq, xp, r, params, rep_dtype="bf16")
+    ch = O.mlp_chunked_grad(xq, xp, r, params, 4, 5, rep_dtype="bf16")
+    for k in full["grads"]:
+        assert_close_norm(ch["grads"][k], full["grads"][k], 1e-12)
+    exact = O.mlp_fullbatch_grad(xq, xp, r, params)
+    assert 0 < np.abs(full["dq"] - exact["dq"]).max() / np.abs(exact["dq"]).max() < 0.05
+
+
 # ------------------------------------------------- planted mistakes are caught
 @pytest.mark.parametrize("mutation", ["no_alpha_on_grad", "eps_only_first", "normalise_by_P", "transpose_g"])
 def test_planted_mistakes_fail_the_pins(mutation):
