@@ -60,8 +60,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a 64 MiB device-to-device copy kernel 4 times (known HBM traffic, used to scale "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+                    help="also run a plain elementwise kernel 4 times that reads 1 GiB and writes 1 GiB (known HBM "
+                         "traffic, larger than the 256 MB Infinity Cache; scales rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is the one-GPU hot path; --gpus must be 1 (no collectives are part of it)", file=sys.stderr)
@@ -89,11 +89,12 @@ def main():
         step()
     torch.cuda.synchronize()
     if args.copy_calibration:
-        src = torch.ones(16 * 1024 * 1024, dtype=torch.float32, device=dev)
+        src = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(4):
-            dst.copy_(src)
+            torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
+        del src, dst
     gc.gc_profile_begin(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
