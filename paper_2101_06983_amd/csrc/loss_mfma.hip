@@ -20,6 +20,14 @@ namespace gc {
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+// Workgroups are handed to the 8 XCDs round-robin by their id, and each XCD has its own L2.  This
+// turns the hardware id into a task id such that each XCD works on one contiguous range of tasks
+// (tasks that stream the same rows are numbered consecutively by the launchers).
+__device__ __forceinline__ int xcd_task_id() {
+  const int id = blockIdx.x, n = gridDim.x;
+  return (n % 8 == 0) ? (id % 8) * (n / 8) + id / 8 : id;
+}
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -52,7 +60,8 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
-  const int ablk = blockIdx.x % n_ablk, split = blockIdx.x / n_ablk;
+  const int task = xcd_task_id();
+  const int ablk = task % n_ablk, split = task / n_ablk;
   const int a0 = ablk * ST_TN;
   const int cbeg = split * cols_per_split, cend = min(P, cbeg + cols_per_split);
   const int nk = d / ST_KC;
@@ -587,7 +596,7 @@ template <int D>
 __global__ void __launch_bounds__(256) grad_mfma_kernel(GradArgs ga) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
   const int nQ = ga.obQ * ga.nsq;
-  const int id = blockIdx.x;
+  const int id = xcd_task_id();
   if (id < nQ) {
     grad_body<D, true>(ga, id % ga.obQ, id / ga.obQ, gsmem);
   } else {
