@@ -28,9 +28,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-# HBM bytes per gradient-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/grad_mfma_kernel_config3_pmc.txt); None until measured.
-TRAFFIC_BYTES = None
+# HBM bytes per gradient-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
+# readings of a plain 1 GiB read + 1 GiB write kernel (profiles/loss_path_config3_rocprofv3.txt):
+# 76.1 MB read + 50.3 MB written.
+TRAFFIC_BYTES = 126.4e6
 
 
 def cpu_baseline(q, p, r, flops):
