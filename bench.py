@@ -54,12 +54,53 @@ def cpu_baseline(q, p, r, flops):
             "sample": "full workload batch (B=4096,P=8192,d=768), fp64 numpy oracle, mean of %d runs, %.2f s each" % (reps, sec)}
 
 
+def side_workload(args, gc, synth, dev):
+    """Timing of the other configurations (parity-test cases; not the headline line)."""
+    if args.workload == "config2":
+        q, p, r = synth.config2()
+        qd, pd, rd = q.to(dev), p.to(dev), r.to(dev)
+        ws = gc.alloc_workspace(gc.gc_workspace_bytes(128, 256, 768, gc.GC_BF16), dev)
+        out = {}
+        step = lambda: out.update(gc.gc_loss_and_rep_grad_ex(qd, pd, rd, 1.0, 1.0, 0, ("loss", "dq", "dp"), ws, out))
+        flops, what = 6.0 * 128 * 256 * 768, "loss+rep-grad, B=128 P=256 d=768 bf16"
+    elif args.workload == "config4":
+        z = synth.ntxent_views().to(dev)
+        ws = gc.alloc_workspace(gc.load().gc_ntxent_workspace_bytes(16384, 128), dev)
+        step = lambda: gc.gc_ntxent_loss_and_grad_bf16(z, 0.07, ws)
+        flops, what = 6.0 * 16384 * 16384 * 128, "NT-Xent loss+grad, 2N=16384 d=128 bf16 tau=0.07"
+    else:
+        xq, xp, r, params = synth.mlp_problem()
+        xq, xp, r = xq.to(dev), xp.to(dev), r.to(dev)
+        params = {k: v.to(dev) for k, v in params.items()}
+        grads = gc.zero_mlp_grads(params)
+        res = gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, grads=grads)
+        ws = res["workspace"]
+        step = lambda: gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, grads=grads, workspace=ws)
+        rows = 512 + 1024
+        flops = rows * 2.0 * (1024 * 3072 + 3072 * 768) * 4 + 6.0 * 512 * 1024 * 768   # fwd + (re-fwd layer 1, 3 bwd GEMMs) + loss
+        what = "Gradient Cache step, MLP 1024-3072-768, B=512 P=1024, chunk 32"
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    print(json.dumps({"metric": "ms/step", "value": round(ms, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": False, "dtype": "bf16",
+                      "data": "synthetic", "config": {"workload": args.workload + ": " + what},
+                      "algorithmic_tflops": round(flops / (ms * 1e-3) / 1e12, 2)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5"],
+                    help="config3 (default) is the headline workload; the others print a shorter timing line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise kernel 4 times that reads 1 GiB and writes 1 GiB (known HBM "
                          "traffic, larger than the 256 MB Infinity Cache; scales rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -75,6 +116,8 @@ def main():
     from paper_2101_06983_amd import synth
 
     dev = torch.device("cuda:0")
+    if args.workload != "config3":
+        return side_workload(args, gc, synth, dev)
     B, P, d = 4096, 8192, 768
     q, p, r = synth.config3()
     qd, pd, rd = q.to(dev), p.to(dev), r.to(dev)

@@ -17,6 +17,7 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   if (pl.use_mfma) {
     const int n_ablk = ceil_div(B, 256), tiles = ceil_div(P, 256);
     int splits = ceil_div(kNumCU, n_ablk);
+    if (splits > 64) splits = 64;  // the merge kernel combines at most 64 splits per anchor
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;
     pl.stat_cols_per_split = ceil_div(tiles, splits) * 256;

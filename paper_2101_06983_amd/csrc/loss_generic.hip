@@ -6,6 +6,8 @@
 //
 // Scores are kept in the base-2 domain: t_ij = s_ij * log2(e), so that
 // softmax_j = 2^(t_ij - lse2_i) with lse2_i = log2 sum_j 2^t_ij (Eq. 4).
+#include <type_traits>
+
 #include "gc_common.h"
 
 namespace gc {
@@ -94,32 +96,44 @@ __global__ void __launch_bounds__(256) stats_generic_kernel(const T* __restrict_
 }
 
 // Merge of the split statistics of every anchor: lse2_i, row loss (Eq. 1's summand), argmax.
-// lse2 and the copy of pos_idx are padded to b_pad rows with +inf / -1, so that the gradient pass
-// can read whole tiles without bounds checks (a padded row gives g = 0).
+// LANES (a power of two >= nsplit, <= 64) consecutive lanes share one anchor, one split each, and
+// combine with a fixed butterfly, so every load of the kernel is issued at once.  lse2 and the
+// copy of pos_idx are padded to b_pad rows with +inf / -1, so that the gradient pass can read
+// whole tiles without bounds checks (a padded row gives g = 0).
+template <int LANES>
 __global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restrict__ part_m, const float* __restrict__ part_l,
                                                          const int* __restrict__ part_idx, const float* __restrict__ pos_t,
                                                          const int32_t* __restrict__ pos_idx, int B, int P, int nsplit,
                                                          int b_pad, float* __restrict__ lse2, int32_t* __restrict__ pos_pad,
                                                          float* __restrict__ rowloss, float* __restrict__ lse_out,
                                                          int32_t* __restrict__ argmax_out) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= b_pad) return;
+  constexpr int ROWS = 256 / LANES;
+  const int s = threadIdx.x % LANES;
+  const int i = blockIdx.x * ROWS + threadIdx.x / LANES;
+  const bool live = (i < B) && (s < nsplit);
+  float m = live ? part_m[(size_t)s * B + i] : -INFINITY;
+  float l = live ? part_l[(size_t)s * B + i] : 0.f;
+  int bi = live ? part_idx[(size_t)s * B + i] : 0x7fffffff;
+#pragma unroll
+  for (int w = 1; w < LANES; w <<= 1) {
+    const float m2 = __shfl_xor(m, w), l2 = __shfl_xor(l, w);
+    const int b2 = __shfl_xor(bi, w);
+    const float mn = fmaxf(m, m2);
+    const float ms = (mn == -INFINITY) ? 0.f : mn;
+    // both partners evaluate the same expression with the operands in the same (lower lane first) order
+    const bool lower = (s & w) == 0;
+    const float la = lower ? l : l2, ma = lower ? m : m2, lb = lower ? l2 : l, mb = lower ? m2 : m;
+    l = la * exp2f(ma - ms) + lb * exp2f(mb - ms);
+    bi = (m2 > m || (m2 == m && b2 < bi)) ? b2 : bi;
+    m = mn;
+  }
+  if (s != 0 || i >= b_pad) return;
   if (i >= B) { lse2[i] = INFINITY; pos_pad[i] = -1; return; }
-  float m = -INFINITY; int bi = 0x7fffffff;
-  for (int s = 0; s < nsplit; s++) {
-    float v = part_m[(size_t)s * B + i]; int x = part_idx[(size_t)s * B + i];
-    if (v > m || (v == m && x < bi)) { m = v; bi = x; }
-  }
-  float l = 0.f;
-  for (int s = 0; s < nsplit; s++) {
-    float v = part_m[(size_t)s * B + i];
-    if (v > -INFINITY) l += part_l[(size_t)s * B + i] * exp2f(v - m);
-  }
-  float l2 = m + log2f(l);
+  const float l2 = m + log2f(l);
   lse2[i] = l2;
-  int r = pos_idx[i];
+  const int r = pos_idx[i];
   pos_pad[i] = r;
-  bool ok = (r >= 0 && r < P);
+  const bool ok = (r >= 0 && r < P);
   rowloss[i] = ok ? (l2 - pos_t[i]) * kLn2 : NAN;
   if (lse_out) lse_out[i] = l2 * kLn2;
   if (argmax_out) argmax_out[i] = bi;
@@ -244,10 +258,18 @@ hipError_t launch_stats_generic(const LossArgs& a, const LossPlan& pl) {
 
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
-  stats_merge_kernel<<<(pl.b_pad + 255) / 256, 256, 0, a.stream>>>(
-      (const float*)(ws + pl.off_part_m), (const float*)(ws + pl.off_part_l), (const int*)(ws + pl.off_part_idx),
-      (const float*)(ws + pl.off_pos), a.pos_idx, a.B, a.P, pl.stat_splits, pl.b_pad, (float*)(ws + pl.off_lse2),
-      (int32_t*)(ws + pl.off_pos_pad), (float*)(ws + pl.off_rowloss), a.lse, a.argmax);
+  auto merge = [&](auto lanes_tag) {
+    constexpr int LANES = decltype(lanes_tag)::value;
+    constexpr int ROWS = 256 / LANES;
+    stats_merge_kernel<LANES><<<(pl.b_pad + ROWS - 1) / ROWS, 256, 0, a.stream>>>(
+        (const float*)(ws + pl.off_part_m), (const float*)(ws + pl.off_part_l), (const int*)(ws + pl.off_part_idx),
+        (const float*)(ws + pl.off_pos), a.pos_idx, a.B, a.P, pl.stat_splits, pl.b_pad, (float*)(ws + pl.off_lse2),
+        (int32_t*)(ws + pl.off_pos_pad), (float*)(ws + pl.off_rowloss), a.lse, a.argmax);
+  };
+  if (pl.stat_splits <= 1) merge(std::integral_constant<int, 1>{});
+  else if (pl.stat_splits <= 4) merge(std::integral_constant<int, 4>{});
+  else if (pl.stat_splits <= 16) merge(std::integral_constant<int, 16>{});
+  else merge(std::integral_constant<int, 64>{});
   loss_reduce_kernel<<<1, 1024, 0, a.stream>>>((const float*)(ws + pl.off_rowloss), a.pos_idx, a.B, a.P, a.loss,
                                                (int*)(ws + pl.off_err));
   return hipGetLastError();

@@ -115,6 +115,7 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
       if (kc + 1 < nk) gload(kc + 1);
       const unsigned short* As = smem + (kc & 1) * ST_STAGE;
       const unsigned short* Bs = As + ST_TM * ST_LD;
+      __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the fragment reads with the MFMA stream
 #pragma unroll
       for (int ks = 0; ks < ST_KC / 16; ks++) {
         bf16x8 af[4], bfg[2];

@@ -33,6 +33,10 @@ def compare(out, want, tol, q=None, p=None, alpha=1.0, gap_tol=1e-5):
 def test_config1_tiny_fp32():
     q, p, r = synth.config1()
     want = oracle_loss(q, p, r)
+    import json
+    import os
+    gold = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "config1_oracle.json")))
+    assert abs(want["loss"] - gold["loss"]) < 1e-12   # the stored oracle values are the ones compared against
     loss, dq, dp = gc.gc_loss_and_rep_grad_f32(q.to(DEV), p.to(DEV), r.to(DEV))
     torch.cuda.synchronize()
     assert gc.gc_check_async_error() == gc.GC_OK

@@ -344,6 +344,20 @@ def test_round_to_bf16_matches_torch_cast_and_keeps_exactness():
     assert 0 < np.abs(full["dq"] - exact["dq"]).max() / np.abs(exact["dq"]).max() < 0.05
 
 
+def test_golden_config1_is_what_the_oracle_gives():
+    # regression fixture written by tests/golden/make_golden.py (oracle only); not a pin by itself
+    import json
+    import os
+    rec = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "config1_oracle.json")))
+    q, p, r = (synth.widen(t) for t in synth.config1())
+    out = O.loss_and_rep_grad(q, p, r)
+    assert out["loss"] == pytest.approx(rec["loss"], rel=1e-13)
+    np.testing.assert_allclose(out["lse"], rec["lse"], rtol=1e-13)
+    assert out["argmax"].tolist() == rec["argmax"]
+    np.testing.assert_allclose(out["dq"][0], rec["dq_row0"], rtol=1e-11, atol=1e-16)
+    np.testing.assert_allclose(out["dp"][1], rec["dp_row1"], rtol=1e-11, atol=1e-16)
+
+
 # ------------------------------------------------- planted mistakes are caught
 @pytest.mark.parametrize("mutation", ["no_alpha_on_grad", "eps_only_first", "normalise_by_P", "transpose_g"])
 def test_planted_mistakes_fail_the_pins(mutation):
