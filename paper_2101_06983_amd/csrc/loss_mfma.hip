@@ -32,14 +32,40 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// N (1..4) direct global->LDS loads of 16 bytes per lane that share one M0 value.  Load k lands at
+// lds_base + 1024 k + lane * 16 and reads gbase + voff[k] + 1024 k: the instruction's immediate
+// offset moves both addresses, so callers pass voff[k] with 1024 k already subtracted.  The
+// compiler does not see these loads: the reader waits with wait_vmem<N>().
+template <int N>
+__device__ __forceinline__ void dma_group(const void* gbase, const unsigned* voff, unsigned lds_base) {
+  if constexpr (N == 1) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff[0]), "s"(gbase) : "memory");
+  } else if constexpr (N == 2) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\tglobal_load_lds_dwordx4 %2, %3 offset:1024"
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "s"(gbase) : "memory");
+  } else if constexpr (N == 3) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %4\n\tglobal_load_lds_dwordx4 %2, %4 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %3, %4 offset:2048"
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(gbase) : "memory");
+  } else {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\tglobal_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %3, %5 offset:2048\n\tglobal_load_lds_dwordx4 %4, %5 offset:3072"
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase) : "memory");
+  }
+}
+template <int N>
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
 // ===========================================================================
 // Statistics pass.  Workgroup = 512 threads = 8 waves as 2 (targets, M) x 4 (anchors, N);
 // workgroup tile 256 targets x 256 anchors, wave tile 128 x 64 (4 x 2 MFMA tiles).
 // k is staged through LDS in chunks of 64, two stages.
 // ===========================================================================
 constexpr int ST_TM = 256, ST_TN = 256, ST_KC = 64;
-constexpr int ST_LD = ST_KC + 8;  // LDS row stride in bf16 elements (144 B: 16 B skew per row)
-constexpr int ST_STAGE = (ST_TM + ST_TN) * ST_LD;  // elements per stage
+constexpr int ST_ROWB = ST_KC * 2;                       // bytes per LDS row (8 chunks of 16 bytes, unpadded)
+constexpr int ST_STAGE_BYTES = (ST_TM + ST_TN) * ST_ROWB;  // one stage: 256 target rows, then 256 anchor rows
+// LDS layout: chunk c of row r is stored at chunk position c ^ ((r >> 1) & 7): the 16 rows that a
+// 16-lane group reads in one fragment load then fall into 16 different 16-byte bank groups.
 
 __device__ __forceinline__ void stat_merge(float& m, float& l, int& idx, float m2, float l2, int idx2) {
   // (m, idx): larger value wins, ties to the smaller index
@@ -57,7 +83,7 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
                                                          float alpha2, int mask_self, int n_ablk, int cols_per_split,
                                                          float* __restrict__ part_m, float* __restrict__ part_l,
                                                          int* __restrict__ part_idx, float* __restrict__ pos_t) {
-  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_b[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int task = xcd_task_id();
@@ -66,8 +92,49 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
   const int cbeg = split * cols_per_split, cend = min(P, cbeg + cols_per_split);
   const int nk = d / ST_KC;
 
-  // global -> LDS mapping: a row of a stage is 64 bf16 = 8 x 16 B; thread covers (row = tid/8 + 64*pass, c16 = tid%8)
-  const int lrow = tid >> 3, lc16 = tid & 7;
+  // ---- direct global->LDS loads: wave w fills rows 64 w .. 64 w + 63 of a stage (waves 0-3 the target
+  // rows, waves 4-7 the anchor rows), 8 instructions of 8 rows x 8 chunks each -------------------------
+  const bool loads_q = wave >= 4;
+  const unsigned short* lmat = loads_q ? Q : Pm;
+  const int lrows = loads_q ? B : P;
+  const int lrow_in = (wave & 3) * 64 + (lane >> 3);  // + 8 j: row inside the 256-row tile
+  const unsigned stage_m0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)smem_b + wave * 64 * ST_ROWB);
+  auto src_of = [&](int j, int tile_row0, bool clamp) -> unsigned {  // byte offset from the tile's first row, chunk kc = 0
+    int r = lrow_in + 8 * j;
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    if (clamp) r = min(r, lrows - 1 - tile_row0);
+    return (unsigned)(r * d * 2 + c * 16);
+  };
+  unsigned voff_full[8];  // full tile, with the instruction offset 1024 (j % 4) pre-subtracted
+#pragma unroll
+  for (int j = 0; j < 8; j++) voff_full[j] = src_of(j, 0, false) - 1024u * (j & 3);
+  auto prefetch = [&](int tile_row0, int kc, int stage) __attribute__((always_inline)) {
+    const unsigned short* base_v = lmat + (size_t)tile_row0 * d + kc * ST_KC;  // the same in every lane of a wave
+    const unsigned long long bu = (unsigned long long)(uintptr_t)base_v;
+    const unsigned short* base = (const unsigned short*)(uintptr_t)(
+        // readfirstlane returns int: go through unsigned, or the low half sign-extends into the high one
+        ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(bu >> 32)) << 32) |
+        (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)bu));
+    const unsigned m0 = stage_m0 + stage * ST_STAGE_BYTES;
+    if (tile_row0 + 256 <= lrows) {
+      dma_group<4>(base, &voff_full[0], m0);
+      dma_group<4>(base, &voff_full[4], m0 + 4096);
+    } else {  // ragged tile: rows past the end re-read the last valid row (masked later)
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        const unsigned off = src_of(j, tile_row0, true);
+        dma_group<1>(base, &off, m0 + j * 1024);
+      }
+    }
+  };
+
+  // ---- fragment addresses: row (lane & 31) of an MFMA tile, chunk 2 ks + (lane >> 5), swizzled ---------
+  const int swz_l = ((lane & 31) >> 1) & 7;
+  unsigned koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ks++) koff[ks] = (unsigned)(((2 * ks + (lane >> 5)) ^ swz_l) * 16);
+  const unsigned char* a_base = smem_b + (wm * 128 + (lane & 31)) * ST_ROWB;               // + mt * 32 rows
+  const unsigned char* b_base = smem_b + (ST_TM + wn * 64 + (lane & 31)) * ST_ROWB;        // + nt * 32 rows
 
   // per-lane running statistics for its two anchor columns
   float rm[2], rl[2], rpos[2];
@@ -88,51 +155,33 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
 
-    u32x4 stg[8];
-    auto gload = [&](int kc) {
-#pragma unroll
-      for (int ps = 0; ps < 4; ps++) {
-        int rb = min(b0 + lrow + 64 * ps, P - 1);
-        stg[ps] = *(const u32x4*)(Pm + (size_t)rb * d + kc * ST_KC + lc16 * 8);
-        int ra = min(a0 + lrow + 64 * ps, B - 1);
-        stg[4 + ps] = *(const u32x4*)(Q + (size_t)ra * d + kc * ST_KC + lc16 * 8);
-      }
-    };
-    auto lstore = [&](int stage) {
-      unsigned short* As = smem + stage * ST_STAGE;
-      unsigned short* Bs = As + ST_TM * ST_LD;
-#pragma unroll
-      for (int ps = 0; ps < 4; ps++) {
-        *(u32x4*)(As + (lrow + 64 * ps) * ST_LD + lc16 * 8) = stg[ps];
-        *(u32x4*)(Bs + (lrow + 64 * ps) * ST_LD + lc16 * 8) = stg[4 + ps];
-      }
-    };
-    __syncthreads();  // previous tile's readers are done with both stages
-    gload(0);
-    lstore(0);
+    const int tile_row0 = loads_q ? a0 : b0;
+    __syncthreads();  // the previous tile's readers (and the epilogue's LDS use) are done with both stages
+    prefetch(tile_row0, 0, 0);
+    wait_vmem<0>();
     __syncthreads();
     for (int kc = 0; kc < nk; kc++) {
-      if (kc + 1 < nk) gload(kc + 1);
-      const unsigned short* As = smem + (kc & 1) * ST_STAGE;
-      const unsigned short* Bs = As + ST_TM * ST_LD;
+      if (kc + 1 < nk) prefetch(tile_row0, kc + 1, (kc + 1) & 1);
+      const int so = (kc & 1) * ST_STAGE_BYTES;
       __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the fragment reads with the MFMA stream
+      bf16x8 af[2][4], bfg[2][2];
+      auto load_frags = [&](int ks, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mt = 0; mt < 4; mt++) af[buf][mt] = *(const bf16x8*)(a_base + so + mt * 32 * ST_ROWB + koff[ks]);
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++) bfg[buf][nt] = *(const bf16x8*)(b_base + so + nt * 32 * ST_ROWB + koff[ks]);
+      };
+      load_frags(0, 0);
 #pragma unroll
       for (int ks = 0; ks < ST_KC / 16; ks++) {
-        bf16x8 af[4], bfg[2];
-        const int kof = ks * 16 + 8 * (lane >> 5);
-#pragma unroll
-        for (int mt = 0; mt < 4; mt++)
-          af[mt] = *(const bf16x8*)(As + (wm * 128 + mt * 32 + (lane & 31)) * ST_LD + kof);
-#pragma unroll
-        for (int nt = 0; nt < 2; nt++)
-          bfg[nt] = *(const bf16x8*)(Bs + (wn * 64 + nt * 32 + (lane & 31)) * ST_LD + kof);
+        if (ks + 1 < ST_KC / 16) load_frags(ks + 1, (ks + 1) & 1);
 #pragma unroll
         for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-          for (int nt = 0; nt < 2; nt++) acc[mt][nt] = mfma32(af[mt], bfg[nt], acc[mt][nt]);
+          for (int nt = 0; nt < 2; nt++) acc[mt][nt] = mfma32(af[ks & 1][mt], bfg[ks & 1][nt], acc[mt][nt]);
       }
-      if (kc + 1 < nk) lstore((kc + 1) & 1);
-      __syncthreads();
+      wait_vmem<0>();   // this wave's part of the next stage has landed
+      __syncthreads();  // ... and everybody's; nobody still reads the stage that is overwritten next
     }
 
     // ---- tile epilogue: online softmax statistics, all in registers -----------------------------
@@ -195,7 +244,7 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
   }
   // ---- combine the two waves along M through LDS, then write the split partial ------------------
   __syncthreads();
-  float* xs = (float*)smem;  // [4 wn][2 nt][32][3]
+  float* xs = (float*)smem_b;  // [4 wn][2 nt][32][3]
   if (wm == 1 && lane < 32) {
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
@@ -234,7 +283,7 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
   const int n_ablk = (a.B + ST_TN - 1) / ST_TN;
-  const size_t smem = (size_t)2 * ST_STAGE * sizeof(unsigned short);
+  const size_t smem = (size_t)2 * ST_STAGE_BYTES;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)stats_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -320,30 +369,6 @@ struct GradArgs {
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-
-// N (1..4) direct global->LDS loads of 16 bytes per lane that share one M0 value.  Load k lands at
-// lds_base + 1024 k + lane * 16 and reads gbase + voff[k] + 1024 k: the instruction's immediate
-// offset moves both addresses, so callers pass voff[k] with 1024 k already subtracted.  The
-// compiler does not see these loads: the reader waits with wait_vmem<N>().
-template <int N>
-__device__ __forceinline__ void dma_group(const void* gbase, const unsigned* voff, unsigned lds_base) {
-  if constexpr (N == 1) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff[0]), "s"(gbase) : "memory");
-  } else if constexpr (N == 2) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\tglobal_load_lds_dwordx4 %2, %3 offset:1024"
-                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "s"(gbase) : "memory");
-  } else if constexpr (N == 3) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %4\n\tglobal_load_lds_dwordx4 %2, %4 offset:1024\n\t"
-                 "global_load_lds_dwordx4 %3, %4 offset:2048"
-                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(gbase) : "memory");
-  } else {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\tglobal_load_lds_dwordx4 %2, %5 offset:1024\n\t"
-                 "global_load_lds_dwordx4 %3, %5 offset:2048\n\tglobal_load_lds_dwordx4 %4, %5 offset:3072"
-                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase) : "memory");
-  }
-}
-template <int N>
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 template <int D>
 constexpr bool grad_offsets_fit() {  // voff[k] - 1024 (k % 4) must stay >= 0 for a full tile
