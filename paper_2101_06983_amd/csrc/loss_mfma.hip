@@ -53,6 +53,39 @@ __device__ __forceinline__ void dma_group(const void* gbase, const unsigned* vof
                  ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase) : "memory");
   }
 }
+// One such load with immediate offset IMM (a multiple of 1024 below 4096): lands at lds_base + IMM +
+// lane * 16 and reads gbase + voff + IMM.  No memory clobber: the compiler may move unrelated LDS
+// traffic across it; callers order it against the readers of its target with wait_vmem / barriers.
+template <int IMM>
+__device__ __forceinline__ void dma_piece(const void* gbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3" ::"s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+}
+// The same, placed by data dependences instead of fences: the statement claims to rewrite the
+// registers pin_a / pin_b (it does not touch them), so it is scheduled after the last reader of
+// their old values and before the first reader of the new ones, and nothing else is held up.
+// LANES8: only lanes 0-7 load (128 bytes); EXEC is narrowed inside the statement and restored.
+template <int IMM, bool LANES8, bool TWO>
+__device__ __forceinline__ void dma_piece_pinned(const void* gbase, unsigned voff, unsigned lds_base, u32x4& pin_a, u32x4& pin_b) {
+  unsigned pa = pin_a[0], pb = TWO ? pin_b[0] : 0u;
+  if constexpr (LANES8) {
+    unsigned long long keep;
+    if constexpr (TWO)
+      asm volatile("s_mov_b64 %2, exec\n\ts_mov_b64 exec, 0xff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %5 offset:%6\n\ts_mov_b64 exec, %2"
+                   : "+v"(pa), "+v"(pb), "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+    else
+      asm volatile("s_mov_b64 %1, exec\n\ts_mov_b64 exec, 0xff\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %4 offset:%5\n\ts_mov_b64 exec, %1"
+                   : "+v"(pa), "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+  } else {
+    if constexpr (TWO)
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %4 offset:%5"
+                   : "+v"(pa), "+v"(pb) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+    else
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 offset:%4"
+                   : "+v"(pa) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+  }
+  pin_a[0] = pa;
+  if constexpr (TWO) pin_b[0] = pb;
+}
 template <int N>
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
@@ -323,7 +356,7 @@ hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
 // ds_read_b64_tr_b16: in each group of 16 lanes, lane j supplies the address of 4 consecutive
 // 16-bit elements; lane i receives element (i % 4) of the addresses of lanes i / 4 + {0, 4, 8, 12}.
 // ===========================================================================
-constexpr int GR_OWN = 64, GR_T = 16, GR_STAGES = 4;
+constexpr int GR_OWN = 64, GR_T = 16, GR_STAGES = 5;
 
 template <int D>
 struct GradCfg {
@@ -340,9 +373,10 @@ struct GradCfg {
   static constexpr int LDB = SLOTS * 16;                // LDS row stride in bytes
   static constexpr int TILE_SLOTS = GR_T * SLOTS;       // 16-byte slots holding tile data
   static constexpr int NI_Q = (TILE_SLOTS + 63) / 64;   // direct-to-LDS load instructions (1 KB each) per tile slice
-  // one more 1 KB block per stage carries the row statistics of the streamed rows (dP role):
-  // 64 bytes of lse2, then 64 bytes of pos_idx
-  static constexpr int STAGE = (NI_Q + 1) * 1024;       // bytes: one wave, one stage
+  // a stage starts with the row statistics of the streamed rows (dP role): 64 bytes of lse2, then
+  // 64 bytes of pos_idx; the tile data follows
+  static constexpr int TOFF = 128;
+  static constexpr int STAGE = TOFF + NI_Q * 1024;      // bytes: one wave, one stage
   static constexpr int RS_BYTES = 4 * GR_STAGES * STAGE;
   static constexpr int X_BYTES = 2 * 4 * 4 * 64 * 16;   // [parity][src][dst][lane] float4
   static constexpr int G_BYTES = 2 * 2 * 64 * 16;       // [parity][m-tile][lane] bf16x8
@@ -370,6 +404,14 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {  // f(integral_constant<int, I>) for I = 0 .. N-1
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
 template <int D>
 constexpr bool grad_offsets_fit() {  // voff[k] - 1024 (k % 4) must stay >= 0 for a full tile
   using C = GradCfg<D>;
@@ -392,17 +434,18 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   const int sbeg = split * slen, send = min(Nr, sbeg + slen);
   const int nt = (send - sbeg + GR_T - 1) / GR_T;  // streamed tiles of this workgroup (>= 1)
 
-  // ---- LDS map (bytes): [wave rings: 4 waves x 4 stages x STAGE][X: 2 x 4 x 4 x 1024][G: 2 x 2 x 1024]
+  // ---- LDS map (bytes): [wave rings: 4 waves x 5 stages x STAGE][X: 2 x 4 x 4 x 1024][G: 2 x 2 x 1024]
   constexpr int NT = C::NI_Q;                                 // load instructions that carry tile data
-  const unsigned ring_off = w * (GR_STAGES * C::STAGE);       // this wave's ring of stages
+  constexpr unsigned RING = GR_STAGES * C::STAGE;
+  const unsigned ring_off = w * RING;                         // this wave's ring of stages
   const unsigned ring_m0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)smem + ring_off);
-  // per-lane byte offsets; every access adds a compile-time constant (stage, parity, k-step ...)
+  // per-lane byte offsets; every access adds the stage offset and a compile-time constant (k-step ...)
   auto lane_base = [&](int row, int j, int parity) __attribute__((always_inline)) -> unsigned {
     // chunk 4 i + j of a row is stored at 4 (i ^ s2) + (j ^ s01), (s2, s01) from swz3(row): one
     // base for even i and one for odd i, the loops add the compile-time part 64 i
     const int sw = C::SWZ ? swz3(row) : 0;
     const int s2 = sw >> 2, s01 = sw & 3;
-    return ring_off + (unsigned)(row * C::LDB + 16 * (j ^ s01) + (parity ? -64 * s2 : 64 * s2));
+    return ring_off + C::TOFF + (unsigned)(row * C::LDB + 16 * (j ^ s01) + (parity ? -64 * s2 : 64 * s2));
   };
   // phase 1 reads row l16, chunk 4 ks + g16
   const unsigned char* p1p[2] = {smem + lane_base(l16, g16, 0), smem + lane_base(l16, g16, 1)};
@@ -416,7 +459,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   // elements of lane 16 (w & 1) + l16 + 32 (g16 >> 1) in m-tile w >> 1
   unsigned char* gwp = smem + C::RS_BYTES + C::X_BYTES + ((w >> 1) * 64 + 16 * (w & 1) + l16 + 32 * (g16 >> 1)) * 16 + 8 * (g16 & 1);
   const unsigned char* grp = smem + C::RS_BYTES + C::X_BYTES + lane * 16;        // + par * 2048 + mt * 1024
-  const unsigned char* rip = smem + ring_off + NT * 1024 + 16 * g16;             // + stage * STAGE (+ 64: pos_idx)
+  const unsigned char* rip = smem + ring_off + 16 * g16;                         // + stage offset (+ 64: pos_idx)
 
   // owner slice, kept in registers as MFMA B fragments of phase 1 (16 owner rows per fragment)
   bf16x8 ofrag[4][C::KS];
@@ -445,16 +488,30 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   unsigned src_off[NT];  // full tile, with the instruction offset 1024 (it % 4) pre-subtracted
 #pragma unroll
   for (int it = 0; it < NT; it++) src_off[it] = slot_src(it * 64 + lane, GR_T - 1) - 1024u * (it & 3);
-  // row statistics of the streamed rows (dP role): one more load, lanes 0-3 lse2[t0 + 4 l ..], 4-7 pos_pad
+  // row statistics of the streamed rows (dP role): lanes 0-3 load lse2[t0 + 4 l ..], lanes 4-7 pos_pad
   const unsigned ri_off = (lane & 4) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 3) : 16u * (lane & 3);
-  auto prefetch = [&](int u, int stage, bool known_full) __attribute__((always_inline)) {  // tile u -> ring stage `stage`
+  constexpr int NI = OWNER_IS_Q ? NT : NT + 1;  // load instructions per tile
+  // piece k (0 .. NI-1) of the loads of a full tile that starts at row t0, into the stage at byte offset so
+  auto prefetch_piece = [&](auto k_tag, auto two_tag, int t0, unsigned so, u32x4& pin_a, u32x4& pin_b) __attribute__((always_inline)) {
+    constexpr int K = decltype(k_tag)::value;
+    constexpr bool TWO = decltype(two_tag)::value;
+    if constexpr (!OWNER_IS_Q && K == 0) {
+      dma_piece_pinned<0, true, TWO>(ga.lse2 + t0, ri_off, ring_m0 + so, pin_a, pin_b);
+    } else {
+      constexpr int IT = OWNER_IS_Q ? K : K - 1;
+      dma_piece_pinned<1024 * (IT & 3), false, TWO>(R + (size_t)t0 * D, src_off[IT], ring_m0 + so + C::TOFF + 4096 * (IT >> 2), pin_a, pin_b);
+    }
+  };
+  auto prefetch = [&](int u, unsigned so) __attribute__((always_inline)) {  // whole tile u -> stage at offset so
     const int t0 = sbeg + u * GR_T;
     const unsigned short* tile = R + (size_t)t0 * D;  // wave-uniform
-    const unsigned lds0 = ring_m0 + stage * C::STAGE;
-    if (known_full || t0 + GR_T <= Nr) {
+    const unsigned lds0 = ring_m0 + so + C::TOFF;
+    if (!OWNER_IS_Q) {
+      if (lane < 8) dma_piece<0>(ga.lse2 + t0, ri_off, ring_m0 + so);
+    }
+    if (t0 + GR_T <= Nr) {
 #pragma unroll
       for (int g = 0; g < NT; g += 4) {
-        constexpr int dummy = 0; (void)dummy;
         if (NT - g >= 4) dma_group<4>(tile, &src_off[g], lds0 + g * 1024);
         else if (NT - g == 3) dma_group<3>(tile, &src_off[g], lds0 + g * 1024);
         else if (NT - g == 2) dma_group<2>(tile, &src_off[g], lds0 + g * 1024);
@@ -467,9 +524,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         dma_group<1>(tile, &off, lds0 + it * 1024);
       }
     }
-    if (!OWNER_IS_Q) dma_group<1>(ga.lse2 + t0, &ri_off, lds0 + NT * 1024);
   };
-  constexpr int NI = OWNER_IS_Q ? NT : NT + 1;  // load instructions per tile
 
   f32x16 acc[2][C::CT];
 #pragma unroll
@@ -480,13 +535,13 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       for (int r = 0; r < 16; r++) acc[mt][ct][r] = 0.f;
 
   f32x4 sacc[4];  // partial S^T of the tile most recently through phase 1: [owner 16-block]
-  bf16x8 afr[C::KS];  // phase-1 A fragments of the tile being started
-  auto p1_load = [&](int stage, int ks0, int ks1) __attribute__((always_inline)) {
+  u32x4 afr[C::KS];  // phase-1 A fragments of the tile being started (bf16x8 each)
+  auto p1_load = [&](unsigned so, int ks0, int ks1) __attribute__((always_inline)) {
 #pragma unroll
 #ifndef GC_EXP_NOP1READ
-    for (int ks = ks0; ks < ks1; ks++) afr[ks] = *(const bf16x8*)(p1p[ks & 1] + stage * C::STAGE + 64 * ks);
+    for (int ks = ks0; ks < ks1; ks++) afr[ks] = *(const u32x4*)(p1p[ks & 1] + so + 64 * ks);
 #else
-    for (int ks = ks0; ks < ks1; ks++) afr[ks] = ofrag[ks & 3][ks];
+    for (int ks = ks0; ks < ks1; ks++) afr[ks] = __builtin_bit_cast(u32x4, ofrag[ks & 3][ks]);
 #endif
   };
   auto p1_mfma = [&](int ks0, int ks1) __attribute__((always_inline)) {
@@ -494,38 +549,107 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     for (int ks = ks0; ks < ks1; ks++)
 #pragma unroll
       for (int nq = 0; nq < 4; nq++)
-        sacc[nq] = mfma16(afr[ks], ofrag[nq][ks], ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : sacc[nq]);
+        sacc[nq] = mfma16(__builtin_bit_cast(bf16x8, afr[ks]), ofrag[nq][ks], ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : sacc[nq]);
   };
-  auto phase2 = [&](int stage, const bf16x8 (&gf)[2]) {
+  // The load unit of a compute unit takes one 1 KB load every 16 cycles, and a wave waits at the load
+  // until the unit accepts it.  The four waves run in step (one barrier per tile), so a steady iteration
+  // spreads its 4 NI loads evenly over the MFMA time of the iteration and the waves take turns: the code
+  // of the steady loop is specialised per wave (WAVE = 0 .. 3), piece k of wave WAVE follows the MFMA
+  // that runs at 1 / (4 NI) * (4 k + WAVE) of that time.  Sections: 0 = phase 1 before the barrier,
+  // 1 = phase 1 after it, 2 = phase 2.
+  constexpr int KS_PRE = (C::KS + 1) / 2;            // k-steps of phase 1 issued before the barrier
+  constexpr int MA = 4 * KS_PRE, MB = 4 * (C::KS - KS_PRE), MC = 2 * C::CT;  // MFMAs per section
+  constexpr int T16 = 19, T32 = 33;                  // measured issue-to-issue cycles of the two MFMA shapes
+  auto slot_of = [](int wave, int k, int sec) constexpr -> int {  // MFMA index in section sec, or -1
+    constexpr int TOTAL = T16 * (MA + MB) + T32 * MC;
+    int t = ((4 * k + wave) * TOTAL) / (4 * NI);
+    if (t < T16 * MA) return sec == 0 ? t / T16 : -1;
+    t -= T16 * MA;
+    if (t < T16 * MB) return sec == 1 ? t / T16 : -1;
+    t -= T16 * MB;
+    return sec == 2 ? (t / T32 < MC ? t / T32 : MC - 1) : -1;
+  };
+  // called after MFMA number IDX of section SEC; pin_a: a register that MFMA read, pin_b: one that the
+  // next MFMA reads (TWO: they differ)
+  auto spread = [&](auto wave_tag, auto sec_tag, auto idx_tag, auto two_tag, int t_pf, unsigned so_pf, u32x4& pin_a, u32x4& pin_b) __attribute__((always_inline)) {
+    constexpr int WAVE = decltype(wave_tag)::value, SEC = decltype(sec_tag)::value, IDX = decltype(idx_tag)::value;
+#ifndef GC_EXP_NODMA
+    if constexpr (WAVE >= 0) {
+      static_for<NI>([&](auto k_tag) __attribute__((always_inline)) {
+        if constexpr (slot_of(WAVE, decltype(k_tag)::value, SEC) == IDX) prefetch_piece(k_tag, two_tag, t_pf, so_pf, pin_a, pin_b);
+      });
+    }
+#endif
+  };
+  auto p1_mfma_spread = [&](auto wave_tag, auto sec_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
+    constexpr int SEC = decltype(sec_tag)::value;
+    constexpr int KS0 = SEC == 0 ? 0 : KS_PRE, KS1 = SEC == 0 ? KS_PRE : C::KS;
+    static_for<4 * (KS1 - KS0)>([&](auto i_tag) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_tag)::value, ks = KS0 + i / 4, nq = i % 4;
+      sacc[nq] = mfma16(__builtin_bit_cast(bf16x8, afr[ks]), ofrag[nq][ks], ks == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : sacc[nq]);
+      constexpr int ksn = KS0 + (i + 1) / 4;  // k-step of the next MFMA of the section
+      if constexpr (ksn != ks && ksn < KS1) spread(wave_tag, sec_tag, i_tag, std::true_type{}, t_pf, so_pf, afr[ks], afr[ksn]);
+      else spread(wave_tag, sec_tag, i_tag, std::false_type{}, t_pf, so_pf, afr[ks], afr[ks]);
+    });
+  };
+  // phase 2 of the tile in the stage at `so` (WAVE >= 0: a steady iteration, which also issues its share
+  // of the loads of the tile that starts at row t_pf into the stage at so_pf)
+  auto phase2 = [&](unsigned so, const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
+    u32x4 bfr[C::CT];
 #pragma unroll
     for (int ct = 0; ct < C::CT; ct++) {
 #ifndef GC_EXP_NOTR
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2lo[ct & 1] + stage * C::STAGE + 64 * ct));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2hi[ct & 1] + stage * C::STAGE + 64 * ct));
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2lo[ct & 1] + so + 64 * ct));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2hi[ct & 1] + so + 64 * ct));
 #else
-      s16x4 lo = {(short)ct, 1, 2, (short)stage}, hi = {4, 5, 6, (short)lane};
+      s16x4 lo = {(short)ct, 1, 2, (short)so}, hi = {4, 5, 6, (short)lane};
 #endif
       s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      const bf16x8 bfr = __builtin_bit_cast(bf16x8, bb);
-      acc[0][ct] = mfma32(gf[0], bfr, acc[0][ct]);
-      acc[1][ct] = mfma32(gf[1], bfr, acc[1][ct]);
+      bfr[ct] = __builtin_bit_cast(u32x4, bb);
     }
+    static_for<MC>([&](auto i_tag) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_tag)::value, ct = i / 2, mt = i % 2;
+      acc[mt][ct] = mfma32(gf[mt], __builtin_bit_cast(bf16x8, bfr[ct]), acc[mt][ct]);
+      constexpr std::integral_constant<int, 2> sec{};
+      if constexpr (mt == 1 && ct + 1 < C::CT) spread(wave_tag, sec, i_tag, std::true_type{}, t_pf, so_pf, bfr[ct], bfr[ct + 1]);
+      else spread(wave_tag, sec, i_tag, std::false_type{}, t_pf, so_pf, bfr[ct], bfr[ct]);
+    });
   };
 
+#ifdef GC_EXP_TIMING
+  long long tacc[4] = {0, 0, 0, 0}, tq1 = 0;
+#endif
   bf16x4 gq = {0, 0, 0, 0};  // g of the tile whose scores were finished last (4 streamed rows of owner row a_q)
 
-  // One pipeline iteration (see the header comment).  STEADY: every pipeline slot is live, the tiles
-  // involved are full and not the last ones.
-  auto body = [&](int u, auto steady_tag) __attribute__((always_inline)) {
-    constexpr bool STEADY = decltype(steady_tag)::value;
-    const int ST0 = u & 3, ST1 = (u + 1) & 3, ST2 = (u + 2) & 3;  // ring stages of tiles u, u+1, u+2 (u+4 reuses ST0)
-    const int PAR0 = u & 1, PAR1 = PAR0 ^ 1;                      // X / G parity of tiles u and u+1
+  // One pipeline iteration (see the header comment); so0 = ring offset of the stage of tile u.  STEADY:
+  // every pipeline slot is live, the tiles involved are full and not the last ones.
+  auto body = [&](int u, unsigned so0, auto wave_tag) __attribute__((always_inline)) {
+    constexpr int WAVE = decltype(wave_tag)::value;
+    constexpr bool STEADY = WAVE >= 0;
+    const int t_pf = sbeg + (u + 4) * GR_T;  // first row of tile u+4
+    const unsigned so1 = (so0 + C::STAGE >= RING) ? so0 + C::STAGE - RING : so0 + C::STAGE;   // tile u+1
+    const unsigned so2 = (so1 + C::STAGE >= RING) ? so1 + C::STAGE - RING : so1 + C::STAGE;   // tile u+2
+    const unsigned so4 = (so0 == 0) ? RING - C::STAGE : so0 - C::STAGE;                        // tile u+4 (= u-1)
+    const int PAR0 = u & 1, PAR1 = PAR0 ^ 1;           // X / G parity of tiles u and u+1
     const bool xw = STEADY || (u + 1 < nt);            // tile u+1: publish partials, finish scores
     const bool gw = STEADY || (u >= 0);                // tile u: publish fragments, phase 2   (u < nt always)
     const bool p1 = STEADY || (u + 2 < nt);            // tile u+2: phase 1
     const bool pf = STEADY || (u >= 0 && u + 4 < nt);  // tile u+4: start its loads
-    constexpr int KS_PRE = (C::KS + 1) / 2;            // k-steps of phase 1 issued before the barrier
-    __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the LDS reads with the MFMA stream
+#ifdef GC_EXP_IGLP
+    __builtin_amdgcn_iglp_opt(0);
+#endif
+#ifdef GC_EXP_TIMING
+    const long long tq0 = clock64();
+#endif
+    if (p1) {
+      // tile u+2 has landed (in a steady iteration the loads of tile u+3 may still be in flight).  Its
+      // fragment reads are issued ahead of the writes below, so they come back first.
+      if (STEADY) wait_vmem<NI>(); else wait_vmem<0>();
+#ifdef GC_EXP_TIMING
+      tq1 = clock64();
+#endif
+      p1_load(so2, 0, C::KS);
+    }
 #ifndef GC_EXP_NOX
     if (xw) {
 #pragma unroll
@@ -533,12 +657,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     }
 #endif
     if (gw) *(bf16x4*)(gwp + PAR0 * 2048) = gq;
-    if (p1) {
-      if (STEADY) wait_vmem<NI>(); else wait_vmem<0>();  // tile u+2 has landed (tile u+3 may be in flight)
-      p1_load(ST2, 0, KS_PRE);
-      p1_mfma(0, KS_PRE);  // runs while the writes above drain and the barrier gathers the waves
-      p1_load(ST2, KS_PRE, C::KS);
-    }
+    if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 0>{}, t_pf, so4);  // while the writes drain and the barrier gathers the waves
 #ifndef GC_EXP_NOBAR
     __syncthreads();
 #endif
@@ -559,11 +678,20 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     }
     f32x4 lse_r = {0.f, 0.f, 0.f, 0.f}; i32x4 pos_r = {0, 0, 0, 0};
     if (!OWNER_IS_Q && xw) {  // row statistics of tile u+1 ride in its LDS stage
-      lse_r = *(const f32x4*)(rip + ST1 * C::STAGE);
-      pos_r = *(const i32x4*)(rip + ST1 * C::STAGE + 64);
+      lse_r = *(const f32x4*)(rip + so1);
+      pos_r = *(const i32x4*)(rip + so1 + 64);
     }
-    if (p1) p1_mfma(KS_PRE, C::KS);
-    if (gw) phase2(ST0, gf);
+    if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
+#ifdef GC_EXP_TIMING
+    const long long tq2 = clock64();
+#endif
+    if (gw) {
+      phase2(so0, gf, wave_tag, t_pf, so4);
+    }
+#ifdef GC_EXP_TIMING
+    const long long tq3 = clock64();
+    if (STEADY) { tacc[0] += tq1 - tq0; tacc[1] += tq2 - tq1; tacc[2] += tq3 - tq2; tacc[3] += 1; }
+#endif
     if (xw) {
       const f32x4 sv = ((xr[0] + xr[1]) + xr[2]) + xr[3];  // fixed order: bit-identical whichever wave sums
       const int b0 = sbeg + (u + 1) * GR_T + 4 * g16;      // first of this lane's 4 streamed rows
@@ -589,21 +717,33 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       gq = __builtin_convertvector(gv, bf16x4);
     }
 #ifndef GC_EXP_NODMA
-    if (pf) prefetch(u + 4, ST0, STEADY);  // a steady iteration never starts the last (possibly ragged) tile
+    if (!STEADY && pf) prefetch(u + 4, so4);  // in a steady iteration phase 2 has issued these loads
 #endif
   };
   // ---- prologue: start the first tiles, phase 1 of tile 0 ------------------------------------------------------
 #pragma unroll 1
-  for (int u = 0; u < min(nt, GR_STAGES); u++) prefetch(u, u, false);
+  for (int u = 0; u < min(nt, 4); u++) prefetch(u, u * C::STAGE);
   wait_vmem<0>();
   p1_load(0, 0, C::KS);
   p1_mfma(0, C::KS);
-  body(-1, std::false_type{});
+  auto next_stage = [&](unsigned so) __attribute__((always_inline)) -> unsigned { return (so + C::STAGE >= RING) ? so + C::STAGE - RING : so + C::STAGE; };
+  unsigned so = RING - C::STAGE;  // stage of "tile -1"
+  constexpr std::integral_constant<int, -1> unsteady{};
+  body(-1, so, unsteady);
+  so = 0;
   int u = 0;
+  auto steady_loop = [&](auto wave_tag) __attribute__((always_inline)) {
 #pragma unroll 1
-  for (; u + 5 < nt; u++) body(u, std::true_type{});
+    for (; u + 5 < nt; u++) { body(u, so, wave_tag); so = next_stage(so); }
+  };
+  switch (__builtin_amdgcn_readfirstlane(w)) {
+    case 0: steady_loop(std::integral_constant<int, 0>{}); break;
+    case 1: steady_loop(std::integral_constant<int, 1>{}); break;
+    case 2: steady_loop(std::integral_constant<int, 2>{}); break;
+    default: steady_loop(std::integral_constant<int, 3>{}); break;
+  }
 #pragma unroll 1
-  for (; u < nt; u++) body(u, std::false_type{});
+  for (; u < nt; u++) { body(u, so, unsteady); so = next_stage(so); }
 
   // ---- epilogue: scale by alpha / B and store the owned rows ---------------------------------------------------------
   float* out = OWNER_IS_Q ? (ga.dq_out + (size_t)split * ga.dq_split_stride) : (ga.dp_out + (size_t)split * ga.dp_split_stride);
@@ -616,6 +756,14 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         const int a = a0 + 32 * mt + 8 * (r >> 2) + 4 * h + (r & 3);
         if (a < No) out[(size_t)a * D + w * C::DS + 32 * ct + ln] = acc[mt][ct][r] * ga.out_scale;
       }
+#ifdef GC_EXP_TIMING
+  __threadfence();
+  __syncthreads();
+  if (oblk == 0 && split == 0 && lane == 0) {
+    long long* tp = (long long*)out + 4 * w;
+    for (int i = 0; i < 4; i++) tp[i] = tacc[i];
+  }
+#endif
 }
 
 template <int D>
