@@ -193,12 +193,17 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
     prefetch(tile_row0, 0, 0);
     wait_vmem<0>();
     __syncthreads();
+    bf16x8 af[2][4], bfg[2][2];
     for (int kc = 0; kc < nk; kc++) {
+#ifndef GC_EXP_ST_NODMA
       if (kc + 1 < nk) prefetch(tile_row0, kc + 1, (kc + 1) & 1);
+#endif
       const int so = (kc & 1) * ST_STAGE_BYTES;
       __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the fragment reads with the MFMA stream
-      bf16x8 af[2][4], bfg[2][2];
       auto load_frags = [&](int ks, int buf) __attribute__((always_inline)) {
+#ifdef GC_EXP_ST_NOLDSREAD
+        if (kc > 0) return;
+#endif
 #pragma unroll
         for (int mt = 0; mt < 4; mt++) af[buf][mt] = *(const bf16x8*)(a_base + so + mt * 32 * ST_ROWB + koff[ks]);
 #pragma unroll
@@ -213,10 +218,17 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 #pragma unroll
           for (int nt = 0; nt < 2; nt++) acc[mt][nt] = mfma32(af[ks & 1][mt], bfg[ks & 1][nt], acc[mt][nt]);
       }
+#ifndef GC_EXP_ST_NOWAIT
       wait_vmem<0>();   // this wave's part of the next stage has landed
+#endif
+#ifndef GC_EXP_ST_NOBAR
       __syncthreads();  // ... and everybody's; nobody still reads the stage that is overwritten next
+#endif
     }
 
+#ifdef GC_EXP_ST_NOEPI
+    if (alpha2 != 12345.f) { rl[0] += acc[0][0][0] + acc[1][1][3] + acc[2][0][5] + acc[3][1][7]; continue; }
+#endif
     // ---- tile epilogue: online softmax statistics, all in registers -----------------------------
     const int brow0 = b0 + wm * 128 + 4 * (lane >> 5);  // + mt*32 + 8*(r/4) + r%4
     const bool edge = (b0 + ST_TM > cend);
@@ -268,6 +280,12 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
     }
   }
 
+#if defined(GC_EXP_ST_NOWAIT)
+  wait_vmem<0>();
+#endif
+#ifdef GC_EXP_ST_NOEPI
+  if (alpha2 != 12345.f) return;
+#endif
   // ---- combine the two half-waves (same anchor column, different target rows) -------------------
 #pragma unroll
   for (int nt = 0; nt < 2; nt++) {
@@ -594,8 +612,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   };
   // phase 2 of the tile in the stage at `so` (WAVE >= 0: a steady iteration, which also issues its share
   // of the loads of the tile that starts at row t_pf into the stage at so_pf)
-  auto phase2 = [&](unsigned so, const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
-    u32x4 bfr[C::CT];
+  u32x4 bfr[C::CT];  // phase-2 B fragments (bf16x8 each)
+  auto p2_load = [&](unsigned so) __attribute__((always_inline)) {
 #pragma unroll
     for (int ct = 0; ct < C::CT; ct++) {
 #ifndef GC_EXP_NOTR
@@ -607,6 +625,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       bfr[ct] = __builtin_bit_cast(u32x4, bb);
     }
+  };
+  auto phase2 = [&](const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
     static_for<MC>([&](auto i_tag) __attribute__((always_inline)) {
       constexpr int i = decltype(i_tag)::value, ct = i / 2, mt = i % 2;
       acc[mt][ct] = mfma32(gf[mt], __builtin_bit_cast(bf16x8, bfr[ct]), acc[mt][ct]);
@@ -635,9 +655,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     const bool gw = STEADY || (u >= 0);                // tile u: publish fragments, phase 2   (u < nt always)
     const bool p1 = STEADY || (u + 2 < nt);            // tile u+2: phase 1
     const bool pf = STEADY || (u >= 0 && u + 4 < nt);  // tile u+4: start its loads
-#ifdef GC_EXP_IGLP
-    __builtin_amdgcn_iglp_opt(0);
-#endif
+    __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the LDS reads with the MFMA stream
 #ifdef GC_EXP_TIMING
     const long long tq0 = clock64();
 #endif
@@ -648,7 +666,11 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 #ifdef GC_EXP_TIMING
       tq1 = clock64();
 #endif
+#ifndef GC_EXP_WRFIRST
       p1_load(so2, 0, C::KS);
+#else
+      p1_load(so2, 0, 1);
+#endif
     }
 #ifndef GC_EXP_NOX
     if (xw) {
@@ -657,6 +679,10 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     }
 #endif
     if (gw) *(bf16x4*)(gwp + PAR0 * 2048) = gq;
+#ifdef GC_EXP_WRFIRST
+    __builtin_amdgcn_sched_barrier(0);
+    if (p1) p1_load(so2, 1, C::KS);
+#endif
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 0>{}, t_pf, so4);  // while the writes drain and the barrier gathers the waves
 #ifndef GC_EXP_NOBAR
     __syncthreads();
@@ -681,12 +707,18 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       lse_r = *(const f32x4*)(rip + so1);
       pos_r = *(const i32x4*)(rip + so1 + 64);
     }
+#ifdef GC_EXP_TRFIRST
+    if (gw) p2_load(so0);
+#endif
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
 #ifdef GC_EXP_TIMING
     const long long tq2 = clock64();
 #endif
     if (gw) {
-      phase2(so0, gf, wave_tag, t_pf, so4);
+#ifndef GC_EXP_TRFIRST
+      p2_load(so0);
+#endif
+      phase2(gf, wave_tag, t_pf, so4);
     }
 #ifdef GC_EXP_TIMING
     const long long tq3 = clock64();
