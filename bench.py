@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # HBM bytes per gradient-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # readings of a plain 1 GiB read + 1 GiB write kernel (profiles/loss_path_config3_rocprofv3.txt):
 # 76.1 MB read + 50.3 MB written.
-TRAFFIC_BYTES = 126.4e6
+TRAFFIC_BYTES = 126.6e6
 
 
 def cpu_baseline(q, p, r, flops):

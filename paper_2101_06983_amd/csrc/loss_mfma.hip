@@ -357,8 +357,9 @@ hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
 //            contraction over d is split four ways over the waves (wave w takes columns
 //            [w*D/4, (w+1)*D/4)), so that each wave keeps its slice of the owner rows in
 //            registers for the whole kernel and only ever touches its own D/4-column slice of
-//            every streamed tile (a wave-private LDS ring of four stages, filled by direct
-//            global->LDS loads issued three tiles ahead).
+//            every streamed tile (a wave-private LDS ring of five stages, filled by direct
+//            global->LDS loads issued four tiles ahead: the loads of iteration u go to the stage
+//            that iteration u-1 has finished with, so they can sit anywhere in the iteration).
 //   exchange the four partial tiles are summed through LDS (each wave finishes 16 owner rows, in
 //            a fixed order), turned into g = 2^(t - lse2) - [j = r_i] (Eq. 5 / Eq. 6 with eps_j
 //            of Eq. 7 folded in), rounded to bf16 and published as ready-made MFMA A fragments.
