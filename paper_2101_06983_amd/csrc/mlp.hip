@@ -2,16 +2,21 @@
 // Step 1, the per-sub-batch re-encode and surrogate backward of Step 3 (the inner sums of Eq. 8 / 9)
 // and the one-GPU driver that runs Steps 1-3.
 //
-// Every contraction is the same skinny-GEMM tile kernel: a workgroup (4 waves) produces a
-// 32 x 128 tile of C = A * B with v_mfma_f32_32x32x16_bf16, each wave one 32 x 32 block, the
-// k dimension staged through LDS 64 (or 32) at a time.  An operand is stored either with k
-// contiguous ("KC": fragments are plain 16-byte LDS reads) or with its m / n index contiguous
-// ("MN": fragments come from transposing ds_read_b64_tr_b16 loads).  The five uses:
-//   H  = X  W1          A = X [rows][din]   KC      B = W1 [din][dh]   MN    +b1, GELU
-//   Y  = A  W2          A = Act (fp32) [rows][dh] KC   B = W2 [dh][dout]  MN    +b2
-//   dA = U  W2^T        A = U (fp32) [rows][dout] KC   B = W2 [dh][dout] KC   * GELU'(H), column sums -> db1
-//   dW2 += Act^T U      A = Act (fp32) [rows][dh] MN   B = U (fp32) [rows][dout] MN   k = rows
-//   dW1 += X^T dH       A = X [rows][din]   MN      B = dH (fp32) [rows][dh] MN    k = rows
+// A sub-batch has few rows (32 at the paper's setting), so every contraction is skinny and is bound by
+// how fast the weights stream in, not by the MFMAs.  Two kernels:
+//
+// mlp_skinny_kernel: C[32 x 32 per workgroup] = A[rows x K] * Bt[N x K]^T, both operands with k contiguous, so
+//   every MFMA fragment is a plain 16-byte global load and nothing is staged through LDS.  The four waves of a
+//   workgroup split K (64-wide chunks, round-robin), keep four chunks of loads in flight each, and sum their
+//   partial tiles through LDS in a fixed order.  Used for
+//     H  = X  W1  (+b1, GELU)              Bt = W1^T [dh][din]   (transposed copy, made once per call)
+//     Y  = Act W2 (+b2)                    Bt = W2^T [dout][dh]  (transposed copy)      A = Act, fp32
+//     dA = U  W2^T, dH = dA * GELU'(H)     Bt = W2 [dh][dout] as stored                 A = U, fp32; column sums -> db1
+// mlp_wgrad_kernel: the weight-gradient contractions, whose k index is the row of the sub-batch (the slow index
+//   of both operands in memory): 32 x 128 tiles, operands through LDS and transposing ds_read_b64_tr_b16 loads,
+//   fp32 accumulators in HBM updated in place (+=)
+//     dW2 += Act^T U      A = Act (fp32) [rows][dh]    B = U (fp32) [rows][dout]   db2 += column sums of U
+//     dW1 += X^T dH       A = X [rows][din]            B = dH (fp32) [rows][dh]
 // An fp32 operand (the cached gradient rows U, dH, and the activations kept for Step 3) is fed to the bf16 MFMA as hi + lo, two
 // bf16 numbers per value and two MFMAs per step, so that it keeps ~16 mantissa bits: with only
 // rows <= 32 terms per sum a single bf16 rounding (2^-9) would sit right at the error budget.
@@ -21,20 +26,7 @@ namespace gc {
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4m;
 
-enum Layout { KC = 0, MN = 1 };
-enum Epilogue { EP_GELU = 0, EP_BIAS = 1, EP_DH = 2, EP_ACC = 3 };
-
-struct GemmArgs {
-  const void* A; int lda;   // elements
-  const void* B; int ldb;
-  int M, N, K;              // logical sizes; M or K may be ragged (rows), N is a multiple of 128
-  const unsigned short* bias;   // EP_GELU / EP_BIAS: [N] bf16
-  float* H; int ldh;            // EP_GELU: optional fp32 pre-activation out; EP_DH: fp32 pre-activation in
-  float* ActF;                  // EP_GELU: optional fp32 activation out (ldh)
-  unsigned short* Cb; int ldc;  // bf16 output (EP_GELU: Act, EP_BIAS: Y)
-  float* Cf;                    // EP_ACC: fp32 accumulator, += ; EP_DH: dH out (fp32); ldc
-  float* colsum;                // EP_DH: db1 [N] += column sums of the tile; EP_ACC: db2 [N] += column sums of B (m-tile 0 only)
-};
+enum Epilogue { EP_GELU = 0, EP_BIAS = 1, EP_DH = 2 };
 
 __device__ __forceinline__ float gelu_f(float h) { return 0.5f * h * (1.f + erff(h * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_prime_f(float h) {
@@ -62,16 +54,23 @@ __device__ __forceinline__ void load8(const void* base, size_t idx, bool live, u
   }
 }
 
-template <int KCH, Layout AL, Layout BL, bool A_F32, bool B_F32, Epilogue EP>
-__global__ void __launch_bounds__(256) mlp_gemm_kernel(GemmArgs g) {
-  // LDS tiles (bf16 elements).  KC layout: [rows of m/n][KCH + 8]; MN layout: [KCH rows of k][width + 8]
-  constexpr int A_LD = (AL == KC) ? KCH + 8 : 32 + 8;
-  constexpr int A_ROWS = (AL == KC) ? 32 : KCH;
-  constexpr int B_LD = (BL == KC) ? KCH + 8 : 128 + 8;
-  constexpr int B_ROWS = (BL == KC) ? 128 : KCH;
-  __shared__ __attribute__((aligned(16))) unsigned short As[(A_F32 ? 2 : 1) * A_ROWS * A_LD];  // [hi | lo]
-  __shared__ __attribute__((aligned(16))) unsigned short Bs[(B_F32 ? 2 : 1) * B_ROWS * B_LD];
-  constexpr int A_LO = A_ROWS * A_LD, B_LO = B_ROWS * B_LD;
+// C[M x N] += A^T B over the rows of a sub-batch: A [K][M] (bf16 or fp32), B [K][N] fp32, C fp32 in HBM.
+struct WgradArgs {
+  const void* A; int lda;   // elements
+  const float* B; int ldb;
+  int M, N, K;              // M a multiple of 32, N a multiple of 128, K = rows of the sub-batch (any)
+  float* C; int ldc;        // += in place (one workgroup per tile: single writer)
+  float* colsum;            // optional: [N] += column sums of B (db2; written by the m-tile 0 workgroups)
+};
+
+template <bool A_F32>
+__global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g) {
+  constexpr int KCH = 32;
+  // LDS tiles (bf16 elements): [KCH rows of k][width + 8], hi part then lo part
+  constexpr int A_LD = 32 + 8, B_LD = 128 + 8;
+  __shared__ __attribute__((aligned(16))) unsigned short As[(A_F32 ? 2 : 1) * KCH * A_LD];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * KCH * B_LD];
+  constexpr int A_LO = KCH * A_LD, B_LO = KCH * B_LD;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
   const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 32;
 
@@ -80,137 +79,186 @@ __global__ void __launch_bounds__(256) mlp_gemm_kernel(GemmArgs g) {
   for (int r = 0; r < 16; r++) acc[r] = 0.f;
 
   for (int k0 = 0; k0 < g.K; k0 += KCH) {
-    // ---- stage A ---------------------------------------------------------------------------
-    if (AL == KC) {  // memory A[m][k]: 32 rows x KCH, 16-byte chunks
-      constexpr int CH = KCH / 8;
-      for (int c = tid; c < 32 * CH; c += 256) {
-        const int r = c / CH, cc = c % CH;
-        const int m = min(m0 + r, g.M - 1);
-        u32x4 vh, vl;
-        load8<A_F32>(g.A, (size_t)m * g.lda + k0 + cc * 8, true, vh, vl);
-        *(u32x4*)(As + r * A_LD + cc * 8) = vh;
-        if (A_F32) *(u32x4*)(As + A_LO + r * A_LD + cc * 8) = vl;
-      }
-    } else {         // memory A[k][m]: KCH rows x 32
-      for (int c = tid; c < KCH * 4; c += 256) {
-        const int r = c / 4, cc = c % 4;
-        u32x4 vh, vl;
-        load8<A_F32>(g.A, (size_t)(k0 + r) * g.lda + m0 + cc * 8, k0 + r < g.K, vh, vl);
-        *(u32x4*)(As + r * A_LD + cc * 8) = vh;
-        if (A_F32) *(u32x4*)(As + A_LO + r * A_LD + cc * 8) = vl;
-      }
+    for (int c = tid; c < KCH * 4; c += 256) {   // A[k][m0 .. m0 + 31]
+      const int r = c / 4, cc = c % 4;
+      u32x4 vh, vl;
+      load8<A_F32>(g.A, (size_t)(k0 + r) * g.lda + m0 + cc * 8, k0 + r < g.K, vh, vl);
+      *(u32x4*)(As + r * A_LD + cc * 8) = vh;
+      if (A_F32) *(u32x4*)(As + A_LO + r * A_LD + cc * 8) = vl;
     }
-    // ---- stage B ---------------------------------------------------------------------------
-    if (BL == KC) {  // memory B[n][k]: 128 rows x KCH
-      constexpr int CH = KCH / 8;
-      for (int c = tid; c < 128 * CH; c += 256) {
-        const int r = c / CH, cc = c % CH;
-        u32x4 vh, vl;
-        load8<B_F32>(g.B, (size_t)(n0 + r) * g.ldb + k0 + cc * 8, true, vh, vl);
-        *(u32x4*)(Bs + r * B_LD + cc * 8) = vh;
-        if (B_F32) *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
-      }
-    } else {         // memory B[k][n]: KCH rows x 128
-      for (int c = tid; c < KCH * 16; c += 256) {
-        const int r = c / 16, cc = c % 16;
-        u32x4 vh, vl;
-        load8<B_F32>(g.B, (size_t)(k0 + r) * g.ldb + n0 + cc * 8, k0 + r < g.K, vh, vl);
-        *(u32x4*)(Bs + r * B_LD + cc * 8) = vh;
-        if (B_F32) *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
-      }
+    for (int c = tid; c < KCH * 16; c += 256) {  // B[k][n0 .. n0 + 127]
+      const int r = c / 16, cc = c % 16;
+      u32x4 vh, vl;
+      load8<true>(g.B, (size_t)(k0 + r) * g.ldb + n0 + cc * 8, k0 + r < g.K, vh, vl);
+      *(u32x4*)(Bs + r * B_LD + cc * 8) = vh;
+      *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
     }
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < KCH / 16; ks++) {
-      auto a_frag = [&](const unsigned short* T) -> bf16x8 {
-        if (AL == KC) return *(const bf16x8*)(T + ln * A_LD + 16 * ks + 8 * h);
-        const unsigned short* p = T + (16 * ks + 8 * h + ((lane & 15) >> 2)) * A_LD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      // both operands have k as the slow index in LDS: transposing reads
+      auto frag = [&](const unsigned short* T, int ld, int col0) -> bf16x8 {
+        const unsigned short* p = T + (16 * ks + 8 * h + ((lane & 15) >> 2)) * ld + col0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
         s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4m*)p);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4m*)(p + 4 * A_LD));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4m*)(p + 4 * ld));
         s16x8 t = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, t);
       };
-      auto b_frag = [&](const unsigned short* T) -> bf16x8 {
-        if (BL == KC) return *(const bf16x8*)(T + (wave * 32 + ln) * B_LD + 16 * ks + 8 * h);
-        const unsigned short* p = T + (16 * ks + 8 * h + ((lane & 15) >> 2)) * B_LD + wave * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4m*)p);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4m*)(p + 4 * B_LD));
-        s16x8 t = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        return __builtin_bit_cast(bf16x8, t);
-      };
-      const bf16x8 af = a_frag(As), bfv = b_frag(Bs);
+      const bf16x8 af = frag(As, A_LD, 0), bfv = frag(Bs, B_LD, wave * 32);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfv, acc, 0, 0, 0);
-      if (A_F32) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag(As + A_LO), bfv, acc, 0, 0, 0);
-      if (B_F32) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, b_frag(Bs + B_LO), acc, 0, 0, 0);
+      if (A_F32) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(As + A_LO, A_LD, 0), bfv, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, frag(Bs + B_LO, B_LD, wave * 32), acc, 0, 0, 0);
     }
     __syncthreads();
   }
-
-  // ---- epilogue: lane holds column n, rows m0 + 8 (r / 4) + 4 h + r % 4 -------------------------------------
+  // lane holds column n, rows m0 + 8 (r / 4) + 4 h + r % 4
   const int n = n0 + wave * 32 + ln;
-  if (EP == EP_GELU || EP == EP_BIAS) {
-    const float b = bf2f(g.bias[n]);
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
-      if (m < g.M) {
-        const float v = acc[r] + b;
-        if (EP == EP_GELU) {
-          const float a = gelu_f(v);
-          if (g.H) g.H[(size_t)m * g.ldh + n] = v;
-          if (g.ActF) g.ActF[(size_t)m * g.ldh + n] = a;
-          if (g.Cb) g.Cb[(size_t)m * g.ldc + n] = f2bf(a);
-        } else {
-          g.Cb[(size_t)m * g.ldc + n] = f2bf(v);
-        }
-      }
-    }
-  } else if (EP == EP_DH) {
+  for (int r = 0; r < 16; r++) {
+    const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
+    if (m < g.M) g.C[(size_t)m * g.ldc + n] += acc[r];
+  }
+  if (g.colsum && blockIdx.y == 0 && tid < 128) {
     float s = 0.f;
+    for (int k = 0; k < g.K; k++) s += g.B[(size_t)k * g.ldb + n0 + tid];
+    g.colsum[n0 + tid] += s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+struct SkinnyArgs {
+  const void* A; int lda;            // [M][K], bf16 or fp32
+  const unsigned short* Bt; int ldb; // [N][K] bf16
+  int M, N, K;                       // M may be ragged; N a multiple of 32, K a multiple of 64
+  const unsigned short* bias;        // EP_GELU / EP_BIAS: [N] bf16
+  float* H; int ldh;                 // EP_GELU: optional fp32 pre-activation out; EP_DH: fp32 pre-activation in
+  float* ActF;                       // EP_GELU: fp32 activation out (ldh)
+  unsigned short* Cb; int ldc;       // EP_BIAS: bf16 output
+  float* Cf;                         // EP_DH: dH out (fp32, ldc)
+  float* colsum;                     // EP_DH: db1 [N] += column sums (one m-tile per launch: single writer)
+};
+
+template <bool A_F32, Epilogue EP>
+__global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
+  __shared__ float red[4][32][33];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
+  const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32;
+  const int nch = g.K / 64;
+  // lane (ln, h) holds elements 32 h .. 32 h + 31 of each 64-wide chunk of row ln of A and of Bt; MFMA j of a
+  // chunk contracts elements 8 j .. 8 j + 7 of both half-chunks (any order of k works if both operands share it)
+  constexpr int AE = A_F32 ? 4 : 2;
+  constexpr int AV = A_F32 ? 8 : 4;   // 16-byte loads per chunk for A
+  const int m = min(m0 + ln, g.M - 1);
+  const char* ap = (const char*)g.A + ((size_t)m * g.lda + 32 * h) * AE;
+  const char* bp = (const char*)(g.Bt + (size_t)(n0 + ln) * g.ldb + 32 * h);
+  constexpr int PD = 4;               // chunks in flight per wave
+  u32x4 fa[PD][AV], fb[PD][4];
+  auto issue = [&](int slot, int c) __attribute__((always_inline)) {
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
-      if (m < g.M) {
-        const float v = acc[r] * gelu_prime_f(g.H[(size_t)m * g.ldh + n]);
-        g.Cf[(size_t)m * g.ldc + n] = v;
-        s += v;
+    for (int v = 0; v < AV; v++) fa[slot][v] = *(const u32x4*)(ap + (size_t)c * 64 * AE + 16 * v);
+#pragma unroll
+    for (int v = 0; v < 4; v++) fb[slot][v] = *(const u32x4*)(bp + (size_t)c * 128 + 16 * v);
+  };
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; r++) acc[r] = 0.f;
+#pragma unroll
+  for (int sl = 0; sl < PD; sl++)
+    if (wave + 4 * sl < nch) issue(sl, wave + 4 * sl);
+  for (int base = wave; base < nch; base += 4 * PD) {
+#pragma unroll
+    for (int sl = 0; sl < PD; sl++) {
+      const int c = base + 4 * sl;
+      if (c < nch) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, fb[sl][j]);
+          if (A_F32) {
+            typedef __attribute__((ext_vector_type(8))) float f32x8;
+            const f32x4 x0 = __builtin_bit_cast(f32x4, fa[sl][(2 * j) % AV]), x1 = __builtin_bit_cast(f32x4, fa[sl][(2 * j + 1) % AV]);
+            const f32x8 v = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+            const bf16x8 hi = __builtin_convertvector(v, bf16x8);
+            const bf16x8 lo = __builtin_convertvector(v - __builtin_convertvector(hi, f32x8), bf16x8);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, bv, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, bv, acc, 0, 0, 0);
+          } else {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[sl][j % AV]), bv, acc, 0, 0, 0);
+          }
+        }
+        if (c + 4 * PD < nch) issue(sl, c + 4 * PD);
       }
-    }
-    s += __shfl_xor(s, 32);
-    // one workgroup row (blockIdx.y) at a time would race on db1: the launcher runs EP_DH with a
-    // single m-tile per launch row, see launch_dh
-    if (h == 0) g.colsum[n] += s;
-  } else {  // EP_ACC
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
-      if (m < g.M) g.Cf[(size_t)m * g.ldc + n] += acc[r];
-    }
-    if (g.colsum && blockIdx.y == 0 && tid < 128) {  // db2 += column sums of the fp32 B operand (k = rows)
-      float s = 0.f;
-      for (int k = 0; k < g.K; k++) s += ((const float*)g.B)[(size_t)k * g.ldb + n0 + tid];
-      g.colsum[n0 + tid] += s;
     }
   }
+  // ---- partial tiles of the four waves, summed in a fixed order; lane holds column ln, rows 8 (r / 4) + 4 h + r % 4
+#pragma unroll
+  for (int r = 0; r < 16; r++) red[wave][8 * (r >> 2) + 4 * h + (r & 3)][ln] = acc[r];
+  __syncthreads();
+  const int en = tid & 31, n = n0 + en;
+  float colv = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int em = (tid >> 5) + 8 * i, mm = m0 + em;
+    const float sum = ((red[0][em][en] + red[1][em][en]) + red[2][em][en]) + red[3][em][en];
+    if (EP == EP_GELU) {
+      const float v = sum + bf2f(g.bias[n]);
+      if (mm < g.M) {
+        if (g.H) g.H[(size_t)mm * g.ldh + n] = v;
+        g.ActF[(size_t)mm * g.ldh + n] = gelu_f(v);
+      }
+    } else if (EP == EP_BIAS) {
+      if (mm < g.M) g.Cb[(size_t)mm * g.ldc + n] = f2bf(sum + bf2f(g.bias[n]));
+    } else {  // EP_DH
+      float v = 0.f;
+      if (mm < g.M) {
+        v = sum * gelu_prime_f(g.H[(size_t)mm * g.ldh + n]);
+        g.Cf[(size_t)mm * g.ldc + n] = v;
+      }
+      red[0][em][en] = v;  // own element only: nobody else reads it before the barrier below
+    }
+  }
+  if (EP == EP_DH) {
+    __syncthreads();
+    if (tid < 32) {
+      for (int em = 0; em < 32; em++) colv += red[0][em][tid];
+      g.colsum[n0 + tid] += colv;
+    }
+  }
+}
+
+// Wt[n][k] = W[k][n] (bf16), 32 x 32 tiles through LDS; K and N multiples of 32
+__global__ void __launch_bounds__(256) transpose_bf16_kernel(const unsigned short* __restrict__ W, int K, int N,
+                                                            unsigned short* __restrict__ Wt) {
+  __shared__ unsigned short t[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+#pragma unroll
+  for (int i = 0; i < 4; i++) t[ty + 8 * i][tx] = W[(size_t)(k0 + ty + 8 * i) * N + n0 + tx];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; i++) Wt[(size_t)(n0 + ty + 8 * i) * K + k0 + tx] = t[tx][ty + 8 * i];
 }
 
 struct MlpWs {
   float* H;             // [rows][dh] fp32 pre-activations
   float* ActF;          // [rows][dh] fp32 GELU(H)
   float* dH;            // [rows][dh] fp32
+  unsigned short* W1T;  // [dh][din] bf16: W1 transposed
+  unsigned short* W2T;  // [dout][dh] bf16: W2 transposed
   size_t total;
 };
 
 static inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
-static MlpWs carve_mlp_ws(char* base, int rows, int dh) {
-  MlpWs w{};
+static MlpWs carve_mlp_ws(char* base, int rows, const gc_mlp_params* w) {
+  MlpWs m{};
   size_t off = 0;
-  w.H = (float*)(base + off); off += up256((size_t)rows * dh * 4);
-  w.ActF = (float*)(base + off); off += up256((size_t)rows * dh * 4);
-  w.dH = (float*)(base + off); off += up256((size_t)rows * dh * 4);
-  w.total = off;
-  return w;
+  m.H = (float*)(base + off); off += up256((size_t)rows * w->dh * 4);
+  m.ActF = (float*)(base + off); off += up256((size_t)rows * w->dh * 4);
+  m.dH = (float*)(base + off); off += up256((size_t)rows * w->dh * 4);
+  m.W1T = (unsigned short*)(base + off); off += up256((size_t)w->din * w->dh * 2);
+  m.W2T = (unsigned short*)(base + off); off += up256((size_t)w->dh * w->dout * 2);
+  m.total = off;
+  return m;
 }
 
 static int check_mlp_params(const gc_mlp_params* w) {
@@ -222,19 +270,26 @@ static int check_mlp_params(const gc_mlp_params* w) {
   return GC_OK;
 }
 
-// forward of one sub-batch; keepH: also write the fp32 pre-activations (Step 3)
+// the transposed weight copies that the skinny kernel streams (once per entry-point call: the weights do
+// not change inside a call)
+static hipError_t mlp_prepare(const gc_mlp_params* w, const MlpWs& ws, hipStream_t s) {
+  transpose_bf16_kernel<<<dim3(w->dh / 32, w->din / 32), 256, 0, s>>>((const unsigned short*)w->W1, w->din, w->dh, ws.W1T);
+  transpose_bf16_kernel<<<dim3(w->dout / 32, w->dh / 32), 256, 0, s>>>((const unsigned short*)w->W2, w->dh, w->dout, ws.W2T);
+  return hipGetLastError();
+}
+
+// forward of one sub-batch (after mlp_prepare); keepH: also write the fp32 pre-activations (Step 3)
 static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, const MlpWs& ws, bool keepH, void* y,
                               hipStream_t s) {
-  GemmArgs g{};
-  g.A = x; g.lda = w->din; g.B = w->W1; g.ldb = w->dh; g.M = rows; g.N = w->dh; g.K = w->din;
+  SkinnyArgs g{};
+  g.A = x; g.lda = w->din; g.Bt = ws.W1T; g.ldb = w->din; g.M = rows; g.N = w->dh; g.K = w->din;
   g.bias = (const unsigned short*)w->b1; g.H = keepH ? ws.H : nullptr; g.ActF = ws.ActF; g.ldh = w->dh;
-  g.Cb = nullptr; g.ldc = w->dh;
-  mlp_gemm_kernel<64, KC, MN, false, false, EP_GELU><<<dim3(w->dh / 128, (rows + 31) / 32), 256, 0, s>>>(g);
+  mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(g);
   if (y) {
-    GemmArgs g2{};
-    g2.A = ws.ActF; g2.lda = w->dh; g2.B = w->W2; g2.ldb = w->dout; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
+    SkinnyArgs g2{};
+    g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
     g2.bias = (const unsigned short*)w->b2; g2.Cb = (unsigned short*)y; g2.ldc = w->dout;
-    mlp_gemm_kernel<64, KC, MN, true, false, EP_BIAS><<<dim3(w->dout / 128, (rows + 31) / 32), 256, 0, s>>>(g2);
+    mlp_skinny_kernel<true, EP_BIAS><<<dim3(w->dout / 32, (rows + 31) / 32), 256, 0, s>>>(g2);
   }
   return hipGetLastError();
 }
@@ -247,22 +302,23 @@ static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, 
   // += on db1 has a single writer per column at any time (launches on one stream run in order).
   for (int mb = 0; mb < rows; mb += 32) {
     const int mrows = rows - mb < 32 ? rows - mb : 32;
-    GemmArgs g{};
-    g.A = u + (size_t)mb * w->dout; g.lda = w->dout; g.B = w->W2; g.ldb = w->dout; g.M = mrows; g.N = w->dh; g.K = w->dout;
+    SkinnyArgs g{};
+    g.A = u + (size_t)mb * w->dout; g.lda = w->dout; g.Bt = (const unsigned short*)w->W2; g.ldb = w->dout;
+    g.M = mrows; g.N = w->dh; g.K = w->dout;
     g.H = ws.H + (size_t)mb * w->dh; g.ldh = w->dh; g.Cf = ws.dH + (size_t)mb * w->dh; g.ldc = w->dh; g.colsum = acc->db1;
-    mlp_gemm_kernel<64, KC, KC, true, false, EP_DH><<<dim3(w->dh / 128, 1), 256, 0, s>>>(g);
+    mlp_skinny_kernel<true, EP_DH><<<dim3(w->dh / 32, 1), 256, 0, s>>>(g);
   }
   {  // dW2 += Act^T U, db2 += column sums of U
-    GemmArgs g{};
+    WgradArgs g{};
     g.A = ws.ActF; g.lda = w->dh; g.B = u; g.ldb = w->dout; g.M = w->dh; g.N = w->dout; g.K = rows;
-    g.Cf = acc->dW2; g.ldc = w->dout; g.colsum = acc->db2;
-    mlp_gemm_kernel<32, MN, MN, true, true, EP_ACC><<<dim3(w->dout / 128, w->dh / 32), 256, 0, s>>>(g);
+    g.C = acc->dW2; g.ldc = w->dout; g.colsum = acc->db2;
+    mlp_wgrad_kernel<true><<<dim3(w->dout / 128, w->dh / 32), 256, 0, s>>>(g);
   }
   {  // dW1 += X^T dH
-    GemmArgs g{};
+    WgradArgs g{};
     g.A = x; g.lda = w->din; g.B = ws.dH; g.ldb = w->dh; g.M = w->din; g.N = w->dh; g.K = rows;
-    g.Cf = acc->dW1; g.ldc = w->dh; g.colsum = nullptr;
-    mlp_gemm_kernel<32, MN, MN, false, true, EP_ACC><<<dim3(w->dh / 128, w->din / 32), 256, 0, s>>>(g);
+    g.C = acc->dW1; g.ldc = w->dh; g.colsum = nullptr;
+    mlp_wgrad_kernel<false><<<dim3(w->dh / 128, w->din / 32), 256, 0, s>>>(g);
   }
   return hipGetLastError();
 }
@@ -283,7 +339,7 @@ static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_par
   s.loss_bytes = make_loss_plan(B, P, w->dout, GC_BF16, false).total;
   s.off_loss = take(s.loss_bytes);
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
-  s.mlp_bytes = carve_mlp_ws(nullptr, cmax, w->dh).total;
+  s.mlp_bytes = carve_mlp_ws(nullptr, cmax, w).total;
   s.off_mlp = take(s.mlp_bytes);
   s.total = off;
   return s;
@@ -297,7 +353,7 @@ extern "C" {
 
 size_t gc_mlp_workspace_bytes(int rows, const gc_mlp_params* w) {
   if (rows < 1 || check_mlp_params(w) != GC_OK) return 0;
-  return carve_mlp_ws(nullptr, rows, w->dh).total;
+  return carve_mlp_ws(nullptr, rows, w).total;
 }
 
 int gc_mlp_forward_nograd_bf16(const void* x, int rows, const gc_mlp_params* w, void* y, void* workspace,
@@ -306,9 +362,10 @@ int gc_mlp_forward_nograd_bf16(const void* x, int rows, const gc_mlp_params* w, 
   int rc = check_mlp_params(w);
   if (rc != GC_OK) return rc;
   if (rows < 1 || rows > (1 << 24)) return GC_ERR_SHAPE;
-  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < carve_mlp_ws(nullptr, rows, w->dh).total)
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < carve_mlp_ws(nullptr, rows, w).total)
     return GC_ERR_WORKSPACE;
-  const MlpWs ws = carve_mlp_ws((char*)workspace, rows, w->dh);
+  const MlpWs ws = carve_mlp_ws((char*)workspace, rows, w);
+  if (mlp_prepare(w, ws, (hipStream_t)stream) != hipSuccess) return GC_ERR_HIP;
   return mlp_forward(x, rows, w, ws, false, y, (hipStream_t)stream) == hipSuccess ? GC_OK : GC_ERR_HIP;
 }
 
@@ -319,9 +376,10 @@ int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp
   int rc = check_mlp_params(w);
   if (rc != GC_OK) return rc;
   if (rows < 1 || rows > (1 << 24)) return GC_ERR_SHAPE;
-  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < carve_mlp_ws(nullptr, rows, w->dh).total)
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < carve_mlp_ws(nullptr, rows, w).total)
     return GC_ERR_WORKSPACE;
-  const MlpWs ws = carve_mlp_ws((char*)workspace, rows, w->dh);
+  const MlpWs ws = carve_mlp_ws((char*)workspace, rows, w);
+  if (mlp_prepare(w, ws, (hipStream_t)stream) != hipSuccess) return GC_ERR_HIP;
   return mlp_backward(x_chunk, rows, w, cached_grad_rows, acc, ws, (hipStream_t)stream) == hipSuccess ? GC_OK : GC_ERR_HIP;
 }
 
@@ -348,7 +406,8 @@ int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32
   float* dQ = dq ? dq : (float*)(base + sw.off_dq);
   float* dP = dp ? dp : (float*)(base + sw.off_dp);
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
-  const MlpWs mw = carve_mlp_ws(base + sw.off_mlp, cmax, w->dh);
+  const MlpWs mw = carve_mlp_ws(base + sw.off_mlp, cmax, w);
+  if (mlp_prepare(w, mw, s) != hipSuccess) return GC_ERR_HIP;
   // Step 1: graph-less forward, sub-batch by sub-batch, representations kept
   for (int a = 0; a < B; a += chunk_q) {
     const int rows = B - a < chunk_q ? B - a : chunk_q;
