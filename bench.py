@@ -74,8 +74,7 @@ def side_workload(args, gc, synth, dev):
         params = {k: v.to(dev) for k, v in params.items()}
         grads = gc.zero_mlp_grads(params)
         res = gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, grads=grads)
-        ws = res["workspace"]
-        step = lambda: gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, grads=grads, workspace=ws)
+        step = lambda: gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, out=res)   # same buffers every step
         rows = 512 + 1024
         flops = rows * 2.0 * (1024 * 3072 + 3072 * 768) * 4 + 6.0 * 512 * 1024 * 768   # fwd + (re-fwd layer 1, 3 bwd GEMMs) + loss
         what = "Gradient Cache step, MLP 1024-3072-768, B=512 P=1024, chunk 32"

@@ -152,7 +152,9 @@ typedef struct {
 } gc_mlp_grads;
 
 /* Step 1 for one sub-batch: y[rows,dout] bf16 = encoder(x[rows,din]); no
- * activations are kept.  workspace: gc_mlp_workspace_bytes(rows, w). */
+ * activations are kept.  workspace: gc_mlp_workspace_bytes(rows, w) (fp32
+ * activations of the sub-batch and transposed copies of W1, W2, which every
+ * call rebuilds: the weights may change between calls). */
 size_t gc_mlp_workspace_bytes(int rows, const gc_mlp_params* w);
 int gc_mlp_forward_nograd_bf16(const void* x, int rows, const gc_mlp_params* w, void* y, void* workspace,
                                size_t workspace_bytes, void* stream);
@@ -175,6 +177,12 @@ int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp
  *   q_rep [B,dout], p_rep [P,dout] bf16 and dq [B,dout], dp [P,dout] float:
  *     optional outputs (NULL = kept in the workspace only)
  * workspace: gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, w).
+ * The call enqueues on `stream` and on streams of the library's own (created
+ * once per device, default priority), forked from and joined back into
+ * `stream` with events: when `stream` has drained, everything has.  The order
+ * in which sub-batches are added to the gradients is the index order whatever
+ * the timing, so the result is reproducible bit for bit.  Calls on one device
+ * that overlap in time must not share a workspace; they share those streams.
  */
 size_t gc_step_mlp_workspace_bytes(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w);
 int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32_t* pos_idx, int chunk_q,

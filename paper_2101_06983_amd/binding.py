@@ -271,8 +271,14 @@ def gc_chunk_surrogate_backward_bf16(x_chunk, params, cached_grad_rows, grads, w
 
 
 def gc_step_mlp_bf16(x_q, x_p, pos_idx, chunk_q, chunk_p, params, scale=1.0, temp=1.0, grads=None, keep=False,
-                     workspace=None, stream=None):
-    """One Gradient Cache step.  Returns dict(loss, grads[, q, p, dq, dp])."""
+                     workspace=None, stream=None, out=None):
+    """One Gradient Cache step.  Returns dict(loss, grads[, q, p, dq, dp]).  Passing the dict a
+    previous call returned as `out` reuses its buffers (loss, grads, kept outputs, workspace):
+    the library replays a recorded graph when a call repeats with the same buffers."""
+    if out is not None:
+        grads = out["grads"] if grads is None else grads
+        workspace = out["workspace"] if workspace is None else workspace
+        keep = keep or "q" in out
     lib = load()
     _dev_contig(x_q, torch.bfloat16, "x_q"); _dev_contig(x_p, torch.bfloat16, "x_p")
     _dev_contig(pos_idx, torch.int32, "pos_idx")
@@ -282,13 +288,15 @@ def gc_step_mlp_bf16(x_q, x_p, pos_idx, chunk_q, chunk_p, params, scale=1.0, tem
     g = make_mlp_grads(grads)
     B, P = x_q.shape[0], x_p.shape[0]
     dev = x_q.device
-    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    prev = out or {}
+    loss = prev.get("loss")
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
     out = dict(loss=loss, grads=grads)
     if keep:
-        out["q"] = torch.empty(B, w.dout, dtype=torch.bfloat16, device=dev)
-        out["p"] = torch.empty(P, w.dout, dtype=torch.bfloat16, device=dev)
-        out["dq"] = torch.empty(B, w.dout, dtype=torch.float32, device=dev)
-        out["dp"] = torch.empty(P, w.dout, dtype=torch.float32, device=dev)
+        for name, n, dt in (("q", B, torch.bfloat16), ("p", P, torch.bfloat16), ("dq", B, torch.float32), ("dp", P, torch.float32)):
+            t = prev.get(name)
+            out[name] = t if t is not None else torch.empty(n, w.dout, dtype=dt, device=dev)
     if workspace is None:
         workspace = alloc_workspace(lib.gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, ctypes.byref(w)), dev)
     wp, wn = _ws_ptr(workspace)

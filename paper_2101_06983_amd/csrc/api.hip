@@ -107,6 +107,7 @@ static void prof_mark(int call, int mark, hipStream_t s) {
   if (g_prof.on && call < g_prof.max_calls) (void)hipEventRecord(g_prof.ev[call * kMarks + mark], s);
 }
 void prof_mark_grad_kernel_done(hipStream_t s) { prof_mark(g_prof.calls, 3, s); }
+bool prof_active() { return g_prof.on; }
 
 static int run_loss(const LossArgs& a, const LossPlan& pl) {
   const int call = g_prof.calls;

@@ -79,6 +79,7 @@ hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl);
 void prof_mark_grad_kernel_done(hipStream_t s);  // measurement aid: event after the main gradient kernel(s)
+bool prof_active();  // the measurement events of the loss path are being recorded
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
                                  int nsrc, size_t n, hipStream_t stream);
 

@@ -21,6 +21,9 @@
 // bf16 numbers per value and two MFMAs per step, so that it keeps ~16 mantissa bits: with only
 // rows <= 32 terms per sum a single bf16 rounding (2^-9) would sit right at the error budget.
 #include "gc_common.h"
+#include <mutex>
+#include <vector>
+#include <string.h>
 
 namespace gc {
 
@@ -63,20 +66,24 @@ struct WgradArgs {
   float* colsum;            // optional: [N] += column sums of B (db2; written by the m-tile 0 workgroups)
 };
 
+constexpr int WG_KCH = 32, WG_A_LD = 32 + 8, WG_B_LD = 128 + 8;  // LDS tiles (bf16): [k rows][width + 8], hi then lo part
+
 template <bool A_F32>
-__global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g) {
-  constexpr int KCH = 32;
-  // LDS tiles (bf16 elements): [KCH rows of k][width + 8], hi part then lo part
-  constexpr int A_LD = 32 + 8, B_LD = 128 + 8;
-  __shared__ __attribute__((aligned(16))) unsigned short As[(A_F32 ? 2 : 1) * KCH * A_LD];
-  __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * KCH * B_LD];
+__device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, unsigned short* As, unsigned short* Bs) {
+  constexpr int KCH = WG_KCH, A_LD = WG_A_LD, B_LD = WG_B_LD;
   constexpr int A_LO = KCH * A_LD, B_LO = KCH * B_LD;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
-  const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 32;
+  const int n0 = bx * 128, m0 = by * 32;
 
+  // the accumulator tile starts from its current value in HBM (read issued first: it is the longest wait);
+  // lane holds column n, rows m0 + 8 (r / 4) + 4 h + r % 4
+  const int n = n0 + wave * 32 + ln;
   f32x16 acc;
 #pragma unroll
-  for (int r = 0; r < 16; r++) acc[r] = 0.f;
+  for (int r = 0; r < 16; r++) {
+    const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
+    acc[r] = (m < g.M) ? g.C[(size_t)m * g.ldc + n] : 0.f;
+  }
 
   for (int k0 = 0; k0 < g.K; k0 += KCH) {
     for (int c = tid; c < KCH * 4; c += 256) {   // A[k][m0 .. m0 + 31]
@@ -111,17 +118,30 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g) {
     }
     __syncthreads();
   }
-  // lane holds column n, rows m0 + 8 (r / 4) + 4 h + r % 4
-  const int n = n0 + wave * 32 + ln;
 #pragma unroll
   for (int r = 0; r < 16; r++) {
     const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
-    if (m < g.M) g.C[(size_t)m * g.ldc + n] += acc[r];
+    if (m < g.M) g.C[(size_t)m * g.ldc + n] = acc[r];
   }
-  if (g.colsum && blockIdx.y == 0 && tid < 128) {
+  if (g.colsum && by == 0 && tid < 128) {
     float s = 0.f;
     for (int k = 0; k < g.K; k++) s += g.B[(size_t)k * g.ldb + n0 + tid];
     g.colsum[n0 + tid] += s;
+  }
+}
+
+// both weight gradients of a sub-batch in one launch: workgroups [0, n2) take the tiles of dW2 (A = Act, fp32),
+// the rest the tiles of dW1 (A = X, bf16)
+__global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g2, WgradArgs g1, int n2) {
+  __shared__ __attribute__((aligned(16))) unsigned short As[2 * WG_KCH * WG_A_LD];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * WG_KCH * WG_B_LD];
+  const int id = blockIdx.x;
+  if (id < n2) {
+    const int nb = g2.N / 128;
+    wgrad_tile<true>(g2, id % nb, id / nb, As, Bs);
+  } else {
+    const int nb = g1.N / 128;
+    wgrad_tile<false>(g1, (id - n2) % nb, (id - n2) / nb, As, Bs);
   }
 }
 
@@ -294,8 +314,9 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
   return hipGetLastError();
 }
 
-static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
-                               const MlpWs& ws, hipStream_t s) {
+// first half of the surrogate backward of one sub-batch: re-encode, dH, db1
+static hipError_t mlp_backward_act(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
+                                   const MlpWs& ws, hipStream_t s) {
   hipError_t e = mlp_forward(x, rows, w, ws, true, nullptr, s);  // re-encode keeping H and Act
   if (e != hipSuccess) return e;
   // dA = U W2^T, dH = dA * GELU'(H), db1 += column sums.  One launch per 32-row block so that the
@@ -308,24 +329,67 @@ static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, 
     g.H = ws.H + (size_t)mb * w->dh; g.ldh = w->dh; g.Cf = ws.dH + (size_t)mb * w->dh; g.ldc = w->dh; g.colsum = acc->db1;
     mlp_skinny_kernel<true, EP_DH><<<dim3(w->dh / 32, 1), 256, 0, s>>>(g);
   }
-  {  // dW2 += Act^T U, db2 += column sums of U
-    WgradArgs g{};
-    g.A = ws.ActF; g.lda = w->dh; g.B = u; g.ldb = w->dout; g.M = w->dh; g.N = w->dout; g.K = rows;
-    g.C = acc->dW2; g.ldc = w->dout; g.colsum = acc->db2;
-    mlp_wgrad_kernel<true><<<dim3(w->dout / 128, w->dh / 32), 256, 0, s>>>(g);
-  }
-  {  // dW1 += X^T dH
-    WgradArgs g{};
-    g.A = x; g.lda = w->din; g.B = ws.dH; g.ldb = w->dh; g.M = w->din; g.N = w->dh; g.K = rows;
-    g.C = acc->dW1; g.ldc = w->dh; g.colsum = nullptr;
-    mlp_wgrad_kernel<false><<<dim3(w->dh / 128, w->din / 32), 256, 0, s>>>(g);
+  return hipGetLastError();
+}
+
+// second half: the weight gradients, from what the first half left in ws
+static hipError_t mlp_backward_wgrad(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
+                                     const MlpWs& ws, hipStream_t s) {
+  {  // dW2 += Act^T U, db2 += column sums of U;  dW1 += X^T dH
+    WgradArgs g2{}, g1{};
+    g2.A = ws.ActF; g2.lda = w->dh; g2.B = u; g2.ldb = w->dout; g2.M = w->dh; g2.N = w->dout; g2.K = rows;
+    g2.C = acc->dW2; g2.ldc = w->dout; g2.colsum = acc->db2;
+    g1.A = x; g1.lda = w->din; g1.B = ws.dH; g1.ldb = w->dh; g1.M = w->din; g1.N = w->dh; g1.K = rows;
+    g1.C = acc->dW1; g1.ldc = w->dh; g1.colsum = nullptr;
+    const int n2 = (w->dout / 128) * (w->dh / 32), n1 = (w->dh / 128) * (w->din / 32);
+    mlp_wgrad_kernel<<<n2 + n1, 256, 0, s>>>(g2, g1, n2);
   }
   return hipGetLastError();
 }
 
+static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
+                               const MlpWs& ws, hipStream_t s) {
+  hipError_t e = mlp_backward_act(x, rows, w, u, acc, ws, s);
+  if (e != hipSuccess) return e;
+  return mlp_backward_wgrad(x, rows, w, u, acc, ws, s);
+}
+
+// ---- the one-GPU driver of Steps 1-3 -----------------------------------------------------------------------
+// Sub-batches are small, so one of them cannot fill the GPU.  Step 1's sub-batches do not depend on each other:
+// they are dealt round-robin to kLanes streams (the caller's and three of the library's), each with its own
+// activation buffers.  In Step 3 the accumulation order is fixed (sub-batch order), so only two stages overlap:
+// the caller's stream re-encodes sub-batch c+1 and forms its dH while a second stream adds the weight gradients
+// of sub-batch c (two sets of buffers, handed over with events).
+constexpr int kLanes = 4;
+struct StepStreams {
+  bool made = false;
+  hipStream_t side[kLanes - 1];
+  hipEvent_t fork, join[kLanes - 1], act_done[2], wgrad_done[2];
+};
+static std::mutex g_step_mutex;
+static StepStreams g_step_streams[64];
+
+static StepStreams* step_streams() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_step_mutex);
+  StepStreams& ss = g_step_streams[dev];
+  if (!ss.made) {
+    bool ok = true;
+    for (int i = 0; i < kLanes - 1; i++) ok = ok && hipStreamCreateWithFlags(&ss.side[i], hipStreamNonBlocking) == hipSuccess;
+    auto mk = [&](hipEvent_t* e) { ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess; };
+    mk(&ss.fork);
+    for (int i = 0; i < kLanes - 1; i++) mk(&ss.join[i]);
+    for (int i = 0; i < 2; i++) { mk(&ss.act_done[i]); mk(&ss.wgrad_done[i]); }
+    if (!ok) return nullptr;
+    ss.made = true;
+  }
+  return &ss;
+}
+
 struct StepWs {
-  size_t off_q, off_p, off_dq, off_dp, off_loss, off_mlp, total;
-  size_t loss_bytes, mlp_bytes;
+  size_t off_q, off_p, off_dq, off_dp, off_loss, off_mlp, off_act, total;
+  size_t loss_bytes, mlp_bytes, act_bytes;
 };
 
 static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w) {
@@ -341,8 +405,127 @@ static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_par
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
   s.mlp_bytes = carve_mlp_ws(nullptr, cmax, w).total;
   s.off_mlp = take(s.mlp_bytes);
+  s.act_bytes = 3 * up256((size_t)cmax * w->dh * 4);       // H, Act, dH of one more lane
+  s.off_act = take((kLanes - 1) * s.act_bytes);
   s.total = off;
   return s;
+}
+
+// everything a step call depends on besides the contents of its buffers
+struct StepCall {
+  const void* x_q; const void* x_p; const int32_t* pos_idx;
+  int B, P, chunk_q, chunk_p;
+  gc_mlp_params w;
+  float scale, temp;
+  float* loss;
+  gc_mlp_grads grads;
+  void* q_rep; void* p_rep; float* dq; float* dp;
+  void* workspace;
+};
+
+// enqueues Steps 1-3 on s and on the library's side streams (forked from s, joined back into it)
+static int enqueue_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
+  const void* x_q = c.x_q; const void* x_p = c.x_p; const int32_t* pos_idx = c.pos_idx;
+  const int B = c.B, P = c.P, chunk_q = c.chunk_q, chunk_p = c.chunk_p;
+  const gc_mlp_params* w = &c.w; const gc_mlp_grads* grads = &c.grads;
+  const float scale = c.scale, temp = c.temp;
+  float* loss = c.loss; void* q_rep = c.q_rep; void* p_rep = c.p_rep; float* dq = c.dq; float* dp = c.dp;
+  void* workspace = c.workspace;
+  const StepWs sw = plan_step(B, P, chunk_q, chunk_p, w);
+  char* base = (char*)workspace;
+  unsigned short* Q = q_rep ? (unsigned short*)q_rep : (unsigned short*)(base + sw.off_q);
+  unsigned short* Pm = p_rep ? (unsigned short*)p_rep : (unsigned short*)(base + sw.off_p);
+  float* dQ = dq ? dq : (float*)(base + sw.off_dq);
+  float* dP = dp ? dp : (float*)(base + sw.off_dp);
+  const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
+  MlpWs lane[kLanes];  // lane 0: the caller's stream; all share the transposed weights
+  lane[0] = carve_mlp_ws(base + sw.off_mlp, cmax, w);
+  for (int l = 1; l < kLanes; l++) {
+    lane[l] = lane[0];
+    char* ab = base + sw.off_act + (size_t)(l - 1) * sw.act_bytes;
+    const size_t one = up256((size_t)cmax * w->dh * 4);
+    lane[l].H = (float*)ab; lane[l].ActF = (float*)(ab + one); lane[l].dH = (float*)(ab + 2 * one);
+  }
+  auto ok = [](hipError_t e) { return e == hipSuccess; };
+  if (!ok(mlp_prepare(w, lane[0], s))) return GC_ERR_HIP;
+  // the sub-batches in index order: anchors first, then targets
+  struct Sub { const unsigned short* x; int rows; unsigned short* y; const float* u; };
+  std::vector<Sub> subs;
+  for (int a = 0; a < B; a += chunk_q)
+    subs.push_back({(const unsigned short*)x_q + (size_t)a * w->din, B - a < chunk_q ? B - a : chunk_q, Q + (size_t)a * w->dout, dQ + (size_t)a * w->dout});
+  for (int a = 0; a < P; a += chunk_p)
+    subs.push_back({(const unsigned short*)x_p + (size_t)a * w->din, P - a < chunk_p ? P - a : chunk_p, Pm + (size_t)a * w->dout, dP + (size_t)a * w->dout});
+  const int nsub = (int)subs.size();
+  // Step 1: graph-less forward, sub-batch by sub-batch, representations kept
+  if (!ok(hipEventRecord(ss->fork, s))) return GC_ERR_HIP;
+  for (int l = 1; l < kLanes; l++)
+    if (!ok(hipStreamWaitEvent(ss->side[l - 1], ss->fork, 0))) return GC_ERR_HIP;
+  for (int c = 0; c < nsub; c++) {
+    const int l = c % kLanes;
+    if (!ok(mlp_forward(subs[c].x, subs[c].rows, w, lane[l], false, subs[c].y, l ? ss->side[l - 1] : s))) return GC_ERR_HIP;
+  }
+  for (int l = 1; l < kLanes; l++) {
+    if (!ok(hipEventRecord(ss->join[l - 1], ss->side[l - 1]))) return GC_ERR_HIP;
+    if (!ok(hipStreamWaitEvent(s, ss->join[l - 1], 0))) return GC_ERR_HIP;
+  }
+  // Step 2: loss and the representation gradient cache
+  int rc = gc_loss_and_rep_grad_ex(GC_BF16, Q, Pm, pos_idx, B, P, w->dout, scale, temp, 0, loss, dQ, dP, nullptr, nullptr,
+                               base + sw.off_loss, sw.loss_bytes, (void*)s);
+  if (rc != GC_OK) return rc;
+  // Step 3: per sub-batch re-encode and backward of the cached rows; gradients accumulated in index order
+  hipStream_t wg = ss->side[0];
+  for (int c = 0; c < nsub; c++) {
+    const int b = c & 1;
+    if (c >= 2 && !ok(hipStreamWaitEvent(s, ss->wgrad_done[b], 0))) return GC_ERR_HIP;  // buffers b are free again
+    if (!ok(mlp_backward_act(subs[c].x, subs[c].rows, w, subs[c].u, grads, lane[b], s))) return GC_ERR_HIP;
+    if (!ok(hipEventRecord(ss->act_done[b], s)) || !ok(hipStreamWaitEvent(wg, ss->act_done[b], 0))) return GC_ERR_HIP;
+    if (!ok(mlp_backward_wgrad(subs[c].x, subs[c].rows, w, subs[c].u, grads, lane[b], wg))) return GC_ERR_HIP;
+    if (!ok(hipEventRecord(ss->wgrad_done[b], wg))) return GC_ERR_HIP;
+  }
+  for (int b = 0; b < 2 && b < nsub; b++)
+    if (!ok(hipStreamWaitEvent(s, ss->wgrad_done[b], 0))) return GC_ERR_HIP;  // the caller's stream ends after all of it
+  return GC_OK;
+}
+
+// A step is some hundreds of small launches, and the host takes longer to enqueue them than the GPU to run
+// them.  The second time a call comes with exactly the same arguments, it is recorded into a HIP graph (on a
+// stream of the library's: the caller's may be the null stream, which cannot be captured) and from then on
+// replayed with one launch.  The graph holds kernels and event dependencies only, no memset nodes.  Up to
+// kMaxGraphs argument sets are remembered per device (a graph in flight is never destroyed); others, calls
+// made while the measurement events of the loss path are on, and calls whose capture fails are enqueued directly.
+constexpr int kMaxGraphs = 8;
+struct StepGraph { StepCall call; int seen; hipGraphExec_t exec; };
+struct StepGraphs { StepGraph g[kMaxGraphs]; int n = 0; hipStream_t cap = nullptr; };
+static StepGraphs g_step_graphs[64];
+
+static int run_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+  if (prof_active()) return enqueue_step(c, s, ss);
+  std::lock_guard<std::mutex> lock(g_step_mutex);
+  StepGraphs& G = g_step_graphs[dev];
+  StepGraph* e = nullptr;
+  for (int i = 0; i < G.n; i++)
+    if (memcmp(&G.g[i].call, &c, sizeof(StepCall)) == 0) e = &G.g[i];
+  if (!e) {
+    if (G.n < kMaxGraphs) { G.g[G.n].call = c; G.g[G.n].seen = 1; G.g[G.n].exec = nullptr; G.n++; }
+    return enqueue_step(c, s, ss);
+  }
+  if (!e->exec && e->seen == 1) {
+    e->seen = 2;  // one attempt
+    if (!G.cap && hipStreamCreateWithFlags(&G.cap, hipStreamNonBlocking) != hipSuccess) G.cap = nullptr;
+    if (G.cap && hipStreamBeginCapture(G.cap, hipStreamCaptureModeThreadLocal) == hipSuccess) {
+      const int rc = enqueue_step(c, G.cap, ss);
+      hipGraph_t graph = nullptr;
+      const hipError_t ee = hipStreamEndCapture(G.cap, &graph);
+      hipGraphExec_t exec = nullptr;
+      if (rc == GC_OK && ee == hipSuccess && graph && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess) e->exec = exec;
+      if (graph) (void)hipGraphDestroy(graph);
+      (void)hipGetLastError();
+    }
+  }
+  if (e->exec) return hipGraphLaunch(e->exec, s) == hipSuccess ? GC_OK : GC_ERR_HIP;
+  return enqueue_step(c, s, ss);
 }
 
 }  // namespace gc
@@ -399,42 +582,14 @@ int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32
   if (!(scale > 0.f) || !(temp > 0.f) || !(scale / temp > 0.f) || !(scale / temp < 3.0e38f)) return GC_ERR_SHAPE;
   const StepWs sw = plan_step(B, P, chunk_q, chunk_p, w);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sw.total) return GC_ERR_WORKSPACE;
-  char* base = (char*)workspace;
-  hipStream_t s = (hipStream_t)stream;
-  unsigned short* Q = q_rep ? (unsigned short*)q_rep : (unsigned short*)(base + sw.off_q);
-  unsigned short* Pm = p_rep ? (unsigned short*)p_rep : (unsigned short*)(base + sw.off_p);
-  float* dQ = dq ? dq : (float*)(base + sw.off_dq);
-  float* dP = dp ? dp : (float*)(base + sw.off_dp);
-  const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
-  const MlpWs mw = carve_mlp_ws(base + sw.off_mlp, cmax, w);
-  if (mlp_prepare(w, mw, s) != hipSuccess) return GC_ERR_HIP;
-  // Step 1: graph-less forward, sub-batch by sub-batch, representations kept
-  for (int a = 0; a < B; a += chunk_q) {
-    const int rows = B - a < chunk_q ? B - a : chunk_q;
-    if (mlp_forward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, mw, false, Q + (size_t)a * w->dout, s) != hipSuccess)
-      return GC_ERR_HIP;
-  }
-  for (int a = 0; a < P; a += chunk_p) {
-    const int rows = P - a < chunk_p ? P - a : chunk_p;
-    if (mlp_forward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, mw, false, Pm + (size_t)a * w->dout, s) != hipSuccess)
-      return GC_ERR_HIP;
-  }
-  // Step 2: loss and the representation gradient cache
-  rc = gc_loss_and_rep_grad_ex(GC_BF16, Q, Pm, pos_idx, B, P, w->dout, scale, temp, 0, loss, dQ, dP, nullptr, nullptr,
-                               base + sw.off_loss, sw.loss_bytes, stream);
-  if (rc != GC_OK) return rc;
-  // Step 3: per sub-batch re-encode and backward of the cached rows, gradients accumulated in index order
-  for (int a = 0; a < B; a += chunk_q) {
-    const int rows = B - a < chunk_q ? B - a : chunk_q;
-    if (mlp_backward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, dQ + (size_t)a * w->dout, grads, mw, s) != hipSuccess)
-      return GC_ERR_HIP;
-  }
-  for (int a = 0; a < P; a += chunk_p) {
-    const int rows = P - a < chunk_p ? P - a : chunk_p;
-    if (mlp_backward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, dP + (size_t)a * w->dout, grads, mw, s) != hipSuccess)
-      return GC_ERR_HIP;
-  }
-  return GC_OK;
+  StepCall c;
+  memset(&c, 0, sizeof(c));  // the struct is compared bytewise: no stray padding
+  c.x_q = x_q; c.x_p = x_p; c.pos_idx = pos_idx; c.B = B; c.P = P; c.chunk_q = chunk_q; c.chunk_p = chunk_p;
+  c.w = *w; c.scale = scale; c.temp = temp; c.loss = loss; c.grads = *grads; c.q_rep = q_rep; c.p_rep = p_rep;
+  c.dq = dq; c.dp = dp; c.workspace = workspace;
+  StepStreams* ss = step_streams();
+  if (!ss) return GC_ERR_HIP;
+  return run_step(c, (hipStream_t)stream, ss);
 }
 
 }  // extern "C"

@@ -103,3 +103,33 @@ def test_config5_full_size():
     assert relerr(to_np(out["dp"]), want["dp"]) <= TOL_CHAIN
     for k in ("W1", "b1", "W2", "b2"):
         assert relerr(to_np(out["grads"][k]), want["grads"][k]) <= TOL_CHAIN, k
+    # the driver overlaps sub-batches on several streams: the accumulation order must not depend on timing
+    again = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 32, 32, dev_params(params), keep=True)
+    torch.cuda.synchronize()
+    for k in ("W1", "b1", "W2", "b2"):
+        assert torch.equal(out["grads"][k], again["grads"][k]), k
+    assert torch.equal(out["q"], again["q"]) and torch.equal(out["dp"], again["dp"])
+
+
+def test_step_replayed_with_the_same_buffers_matches_the_first_call():
+    # a call that repeats with the same buffers is recorded into a graph and replayed: every replay must
+    # give the bits of the directly enqueued first call, with other GPU work in between
+    xq, xp, r, params = small_problem()
+    dp = dev_params(params)
+    xq, xp, r = xq.to(DEV), xp.to(DEV), r.to(DEV)
+    first = gc.gc_step_mlp_bf16(xq, xp, r, 16, 32, dp, 1.0, 0.05, keep=True)
+    torch.cuda.synchronize()
+    ref = {k: first["grads"][k].clone() for k in first["grads"]}
+    ref_loss, ref_dq = first["loss"].clone(), first["dq"].clone()
+    for rep in range(4):
+        for k in first["grads"]:
+            first["grads"][k].zero_()
+        first["dq"].fill_(7.0)
+        filler = torch.randn(1 << 20, device=DEV).sum()      # unrelated eager work between the replays
+        out = gc.gc_step_mlp_bf16(xq, xp, r, 16, 32, dp, 1.0, 0.05, out=first)
+        torch.cuda.synchronize()
+        assert torch.isfinite(filler)
+        assert torch.equal(out["loss"], ref_loss), rep
+        assert torch.equal(out["dq"], ref_dq), rep
+        for k in ref:
+            assert torch.equal(out["grads"][k], ref[k]), (rep, k)
