@@ -314,11 +314,10 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
   return hipGetLastError();
 }
 
-// first half of the surrogate backward of one sub-batch: re-encode, dH, db1
-static hipError_t mlp_backward_act(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
-                                   const MlpWs& ws, hipStream_t s) {
-  hipError_t e = mlp_forward(x, rows, w, ws, true, nullptr, s);  // re-encode keeping H and Act
-  if (e != hipSuccess) return e;
+// the surrogate backward of one sub-batch in three parts: (1) re-encode keeping H and Act = mlp_forward with
+// keepH, (2) dH and db1, (3) the weight gradients
+static hipError_t mlp_backward_dh(int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
+                                  const MlpWs& ws, hipStream_t s) {
   // dA = U W2^T, dH = dA * GELU'(H), db1 += column sums.  One launch per 32-row block so that the
   // += on db1 has a single writer per column at any time (launches on one stream run in order).
   for (int mb = 0; mb < rows; mb += 32) {
@@ -349,22 +348,25 @@ static hipError_t mlp_backward_wgrad(const void* x, int rows, const gc_mlp_param
 
 static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
                                const MlpWs& ws, hipStream_t s) {
-  hipError_t e = mlp_backward_act(x, rows, w, u, acc, ws, s);
+  hipError_t e = mlp_forward(x, rows, w, ws, true, nullptr, s);
+  if (e != hipSuccess) return e;
+  e = mlp_backward_dh(rows, w, u, acc, ws, s);
   if (e != hipSuccess) return e;
   return mlp_backward_wgrad(x, rows, w, u, acc, ws, s);
 }
 
 // ---- the one-GPU driver of Steps 1-3 -----------------------------------------------------------------------
-// Sub-batches are small, so one of them cannot fill the GPU.  Step 1's sub-batches do not depend on each other:
-// they are dealt round-robin to kLanes streams (the caller's and three of the library's), each with its own
-// activation buffers.  In Step 3 the accumulation order is fixed (sub-batch order), so only two stages overlap:
-// the caller's stream re-encodes sub-batch c+1 and forms its dH while a second stream adds the weight gradients
-// of sub-batch c (two sets of buffers, handed over with events).
-constexpr int kLanes = 4;
+// Sub-batches are small, so one of them cannot fill the GPU.  Step 1 keeps nothing but the representations and
+// its rows do not depend on each other, so kGroup consecutive sub-batches go through each launch (the rows
+// come out bit for bit as they do one sub-batch at a time; only transient buffers grow).  In Step 3 the accumulation order is fixed (sub-batch order), so it runs as a pipeline of
+// three stages, each on a stream of its own and each in sub-batch order: re-encode (sub-batch c+2), dH and db1
+// (c+1, on the caller's stream), weight gradients (c); three sets of buffers are handed over with events.
+constexpr int kLanes = 3;   // buffer sets / pipeline stages of Step 3
+constexpr int kGroup = 8;   // sub-batches per launch in Step 1
 struct StepStreams {
   bool made = false;
-  hipStream_t side[kLanes - 1];
-  hipEvent_t fork, join[kLanes - 1], act_done[2], wgrad_done[2];
+  hipStream_t side[2];
+  hipEvent_t fork, enc_done[3], dh_done[3], wgrad_done[3];
 };
 static std::mutex g_step_mutex;
 static StepStreams g_step_streams[64];
@@ -376,15 +378,20 @@ static StepStreams* step_streams() {
   StepStreams& ss = g_step_streams[dev];
   if (!ss.made) {
     bool ok = true;
-    for (int i = 0; i < kLanes - 1; i++) ok = ok && hipStreamCreateWithFlags(&ss.side[i], hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; i < 2; i++) ok = ok && hipStreamCreateWithFlags(&ss.side[i], hipStreamNonBlocking) == hipSuccess;
     auto mk = [&](hipEvent_t* e) { ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess; };
     mk(&ss.fork);
-    for (int i = 0; i < kLanes - 1; i++) mk(&ss.join[i]);
-    for (int i = 0; i < 2; i++) { mk(&ss.act_done[i]); mk(&ss.wgrad_done[i]); }
+    for (int i = 0; i < 3; i++) { mk(&ss.enc_done[i]); mk(&ss.dh_done[i]); mk(&ss.wgrad_done[i]); }
     if (!ok) return nullptr;
     ss.made = true;
   }
   return &ss;
+}
+
+// rows of kGroup sub-batches of `chunk` rows, at most n
+static int group_rows(int chunk, int n) {
+  const long long g = (long long)kGroup * chunk;
+  return (int)(g < n ? g : n);
 }
 
 struct StepWs {
@@ -403,7 +410,7 @@ static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_par
   s.loss_bytes = make_loss_plan(B, P, w->dout, GC_BF16, false).total;
   s.off_loss = take(s.loss_bytes);
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
-  s.mlp_bytes = carve_mlp_ws(nullptr, cmax, w).total;
+  s.mlp_bytes = carve_mlp_ws(nullptr, group_rows(cmax, B > P ? B : P), w).total;
   s.off_mlp = take(s.mlp_bytes);
   s.act_bytes = 3 * up256((size_t)cmax * w->dh * 4);       // H, Act, dH of one more lane
   s.off_act = take((kLanes - 1) * s.act_bytes);
@@ -438,8 +445,8 @@ static int enqueue_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
   float* dQ = dq ? dq : (float*)(base + sw.off_dq);
   float* dP = dp ? dp : (float*)(base + sw.off_dp);
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
-  MlpWs lane[kLanes];  // lane 0: the caller's stream; all share the transposed weights
-  lane[0] = carve_mlp_ws(base + sw.off_mlp, cmax, w);
+  MlpWs lane[kLanes];  // buffer sets (set 0 also serves Step 1); all share the transposed weights
+  lane[0] = carve_mlp_ws(base + sw.off_mlp, group_rows(cmax, B > P ? B : P), w);
   for (int l = 1; l < kLanes; l++) {
     lane[l] = lane[0];
     char* ab = base + sw.off_act + (size_t)(l - 1) * sw.act_bytes;
@@ -456,34 +463,36 @@ static int enqueue_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
   for (int a = 0; a < P; a += chunk_p)
     subs.push_back({(const unsigned short*)x_p + (size_t)a * w->din, P - a < chunk_p ? P - a : chunk_p, Pm + (size_t)a * w->dout, dP + (size_t)a * w->dout});
   const int nsub = (int)subs.size();
-  // Step 1: graph-less forward, sub-batch by sub-batch, representations kept
-  if (!ok(hipEventRecord(ss->fork, s))) return GC_ERR_HIP;
-  for (int l = 1; l < kLanes; l++)
-    if (!ok(hipStreamWaitEvent(ss->side[l - 1], ss->fork, 0))) return GC_ERR_HIP;
-  for (int c = 0; c < nsub; c++) {
-    const int l = c % kLanes;
-    if (!ok(mlp_forward(subs[c].x, subs[c].rows, w, lane[l], false, subs[c].y, l ? ss->side[l - 1] : s))) return GC_ERR_HIP;
+  // Step 1: graph-less forward, kGroup sub-batches per launch, representations kept
+  const int gq = group_rows(chunk_q, B), gp = group_rows(chunk_p, P);
+  for (int a = 0; a < B; a += gq) {
+    const int rows = B - a < gq ? B - a : gq;
+    if (!ok(mlp_forward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, lane[0], false, Q + (size_t)a * w->dout, s))) return GC_ERR_HIP;
   }
-  for (int l = 1; l < kLanes; l++) {
-    if (!ok(hipEventRecord(ss->join[l - 1], ss->side[l - 1]))) return GC_ERR_HIP;
-    if (!ok(hipStreamWaitEvent(s, ss->join[l - 1], 0))) return GC_ERR_HIP;
+  for (int a = 0; a < P; a += gp) {
+    const int rows = P - a < gp ? P - a : gp;
+    if (!ok(mlp_forward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, lane[0], false, Pm + (size_t)a * w->dout, s))) return GC_ERR_HIP;
   }
   // Step 2: loss and the representation gradient cache
   int rc = gc_loss_and_rep_grad_ex(GC_BF16, Q, Pm, pos_idx, B, P, w->dout, scale, temp, 0, loss, dQ, dP, nullptr, nullptr,
                                base + sw.off_loss, sw.loss_bytes, (void*)s);
   if (rc != GC_OK) return rc;
   // Step 3: per sub-batch re-encode and backward of the cached rows; gradients accumulated in index order
-  hipStream_t wg = ss->side[0];
+  hipStream_t enc = ss->side[1], wg = ss->side[0];
+  if (!ok(hipEventRecord(ss->fork, s)) || !ok(hipStreamWaitEvent(enc, ss->fork, 0))) return GC_ERR_HIP;  // Step 1 is over
   for (int c = 0; c < nsub; c++) {
-    const int b = c & 1;
-    if (c >= 2 && !ok(hipStreamWaitEvent(s, ss->wgrad_done[b], 0))) return GC_ERR_HIP;  // buffers b are free again
-    if (!ok(mlp_backward_act(subs[c].x, subs[c].rows, w, subs[c].u, grads, lane[b], s))) return GC_ERR_HIP;
-    if (!ok(hipEventRecord(ss->act_done[b], s)) || !ok(hipStreamWaitEvent(wg, ss->act_done[b], 0))) return GC_ERR_HIP;
+    const int b = c % 3;
+    if (c >= 3 && !ok(hipStreamWaitEvent(enc, ss->wgrad_done[b], 0))) return GC_ERR_HIP;  // buffers b are free again
+    if (!ok(mlp_forward(subs[c].x, subs[c].rows, w, lane[b], true, nullptr, enc))) return GC_ERR_HIP;
+    if (!ok(hipEventRecord(ss->enc_done[b], enc)) || !ok(hipStreamWaitEvent(s, ss->enc_done[b], 0))) return GC_ERR_HIP;
+    if (!ok(mlp_backward_dh(subs[c].rows, w, subs[c].u, grads, lane[b], s))) return GC_ERR_HIP;
+    if (!ok(hipEventRecord(ss->dh_done[b], s)) || !ok(hipStreamWaitEvent(wg, ss->dh_done[b], 0))) return GC_ERR_HIP;
     if (!ok(mlp_backward_wgrad(subs[c].x, subs[c].rows, w, subs[c].u, grads, lane[b], wg))) return GC_ERR_HIP;
     if (!ok(hipEventRecord(ss->wgrad_done[b], wg))) return GC_ERR_HIP;
   }
-  for (int b = 0; b < 2 && b < nsub; b++)
-    if (!ok(hipStreamWaitEvent(s, ss->wgrad_done[b], 0))) return GC_ERR_HIP;  // the caller's stream ends after all of it
+  // the caller's stream ends after all of it (the weight-gradient stream is in order: its last event covers it;
+  // the re-encode stream's work is covered through dH)
+  if (!ok(hipStreamWaitEvent(s, ss->wgrad_done[(nsub - 1) % 3], 0))) return GC_ERR_HIP;
   return GC_OK;
 }
 
