@@ -177,12 +177,12 @@ int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp
  *   q_rep [B,dout], p_rep [P,dout] bf16 and dq [B,dout], dp [P,dout] float:
  *     optional outputs (NULL = kept in the workspace only)
  * workspace: gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, w).
- * The call enqueues on `stream` and on streams of the library's own (created
- * once per device, default priority), forked from and joined back into
- * `stream` with events: when `stream` has drained, everything has.  The order
- * in which sub-batches are added to the gradients is the index order whatever
- * the timing, so the result is reproducible bit for bit.  Calls on one device
- * that overlap in time must not share a workspace; they share those streams.
+ * Everything is enqueued on `stream`; the order in which sub-batches are added
+ * to the gradients is the index order, so the result is reproducible bit for
+ * bit.  A call that repeats with exactly the same arguments (same buffers) is
+ * recorded into a HIP graph the second time and replayed afterwards; the
+ * contents of the buffers may change between calls, their addresses and sizes
+ * select the recording.
  */
 size_t gc_step_mlp_workspace_bytes(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w);
 int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32_t* pos_idx, int chunk_q,

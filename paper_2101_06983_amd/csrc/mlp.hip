@@ -158,11 +158,14 @@ struct SkinnyArgs {
   float* colsum;                     // EP_DH: db1 [N] += column sums (one m-tile per launch: single writer)
 };
 
-template <bool A_F32, Epilogue EP>
-__global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
-  __shared__ float red[4][32][33];
+typedef float SkinnyRed[32][33];   // one partial tile; a workgroup holds four
+
+// one 32 x 32 output tile (n-tile bx, m-tile by); red: the workgroup's four partial tiles in LDS;
+// PD: 64-wide chunks of loads in flight per wave (registers against latency)
+template <bool A_F32, Epilogue EP, int PD>
+__device__ __forceinline__ void skinny_tile(const SkinnyArgs& g, int bx, int by, SkinnyRed* red) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
-  const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32;
+  const int n0 = bx * 32, m0 = by * 32;
   const int nch = g.K / 64;
   // lane (ln, h) holds elements 32 h .. 32 h + 31 of each 64-wide chunk of row ln of A and of Bt; MFMA j of a
   // chunk contracts elements 8 j .. 8 j + 7 of both half-chunks (any order of k works if both operands share it)
@@ -171,7 +174,6 @@ __global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
   const int m = min(m0 + ln, g.M - 1);
   const char* ap = (const char*)g.A + ((size_t)m * g.lda + 32 * h) * AE;
   const char* bp = (const char*)(g.Bt + (size_t)(n0 + ln) * g.ldb + 32 * h);
-  constexpr int PD = 4;               // chunks in flight per wave
   u32x4 fa[PD][AV], fb[PD][4];
   auto issue = [&](int slot, int c) __attribute__((always_inline)) {
 #pragma unroll
@@ -243,6 +245,56 @@ __global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
       g.colsum[n0 + tid] += colv;
     }
   }
+  __syncthreads();  // red may be reused by the caller's next tile
+}
+
+// grid (N / 32, m-tiles); EP_DH: grid (N / 32, 1), the workgroup walks the m-tiles itself so that each column
+// sum has one writer
+template <bool A_F32, Epilogue EP>
+__global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
+  __shared__ float red[4][32][33];
+  if (EP == EP_DH) {
+    for (int by = 0; by * 32 < g.M; by++) skinny_tile<A_F32, EP, 4>(g, blockIdx.x, by, red);
+  } else {
+    skinny_tile<A_F32, EP, 4>(g, blockIdx.x, blockIdx.y, red);
+  }
+}
+
+// One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
+// sub-batch c-1 and the re-encode of sub-batch c are independent of each other (three sets of buffers), and none of
+// them fills the GPU alone.  Workgroups [0, n_wg) take the weight-gradient tiles (n_wg2 of them dW2), the next n_dh
+// the n-tiles of dH, the rest the tiles of the re-encode.  A count of 0 switches a part off (pipeline ends).
+struct Step3Args {
+  WgradArgs g2, g1; int n_wg2, n_wg;
+  SkinnyArgs dh; int n_dh;
+  SkinnyArgs enc; int n_enc;
+};
+__global__ void __launch_bounds__(256, 3) mlp_step3_kernel(Step3Args a) {
+  constexpr size_t kA = sizeof(unsigned short) * 2 * WG_KCH * WG_A_LD, kB = sizeof(unsigned short) * 2 * WG_KCH * WG_B_LD;
+  constexpr size_t kLds = kA + kB > sizeof(SkinnyRed) * 4 ? kA + kB : sizeof(SkinnyRed) * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
+  int id = blockIdx.x;
+  if (id < a.n_wg) {
+    unsigned short* As = (unsigned short*)lds;
+    unsigned short* Bs = (unsigned short*)(lds + kA);
+    if (id < a.n_wg2) {
+      const int nb = a.g2.N / 128;
+      wgrad_tile<true>(a.g2, id % nb, id / nb, As, Bs);
+    } else {
+      const int nb = a.g1.N / 128;
+      wgrad_tile<false>(a.g1, (id - a.n_wg2) % nb, (id - a.n_wg2) / nb, As, Bs);
+    }
+    return;
+  }
+  id -= a.n_wg;
+  SkinnyRed* red = (SkinnyRed*)lds;
+  if (id < a.n_dh) {
+    for (int by = 0; by * 32 < a.dh.M; by++) skinny_tile<true, EP_DH, 2>(a.dh, id, by, red);
+    return;
+  }
+  id -= a.n_dh;
+  const int nb = a.enc.N / 32;
+  skinny_tile<false, EP_GELU, 2>(a.enc, id % nb, id / nb, red);
 }
 
 // Wt[n][k] = W[k][n] (bf16), 32 x 32 tiles through LDS; K and N multiples of 32
@@ -298,13 +350,34 @@ static hipError_t mlp_prepare(const gc_mlp_params* w, const MlpWs& ws, hipStream
   return hipGetLastError();
 }
 
-// forward of one sub-batch (after mlp_prepare); keepH: also write the fp32 pre-activations (Step 3)
-static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, const MlpWs& ws, bool keepH, void* y,
-                              hipStream_t s) {
+// H = x W1 + b1 (kept when keepH), Act = GELU(H)
+static SkinnyArgs layer1_args(const void* x, int rows, const gc_mlp_params* w, const MlpWs& ws, bool keepH) {
   SkinnyArgs g{};
   g.A = x; g.lda = w->din; g.Bt = ws.W1T; g.ldb = w->din; g.M = rows; g.N = w->dh; g.K = w->din;
   g.bias = (const unsigned short*)w->b1; g.H = keepH ? ws.H : nullptr; g.ActF = ws.ActF; g.ldh = w->dh;
-  mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(g);
+  return g;
+}
+// dA = U W2^T, dH = dA * GELU'(H), db1 += column sums
+static SkinnyArgs dh_args(int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc, const MlpWs& ws) {
+  SkinnyArgs g{};
+  g.A = u; g.lda = w->dout; g.Bt = (const unsigned short*)w->W2; g.ldb = w->dout; g.M = rows; g.N = w->dh; g.K = w->dout;
+  g.H = ws.H; g.ldh = w->dh; g.Cf = ws.dH; g.ldc = w->dh; g.colsum = acc->db1;
+  return g;
+}
+// dW2 += Act^T U, db2 += column sums of U (g2);  dW1 += X^T dH (g1)
+static void wgrad_args(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
+                       const MlpWs& ws, WgradArgs& g2, WgradArgs& g1) {
+  g2 = WgradArgs{}; g1 = WgradArgs{};
+  g2.A = ws.ActF; g2.lda = w->dh; g2.B = u; g2.ldb = w->dout; g2.M = w->dh; g2.N = w->dout; g2.K = rows;
+  g2.C = acc->dW2; g2.ldc = w->dout; g2.colsum = acc->db2;
+  g1.A = x; g1.lda = w->din; g1.B = ws.dH; g1.ldb = w->dh; g1.M = w->din; g1.N = w->dh; g1.K = rows;
+  g1.C = acc->dW1; g1.ldc = w->dh; g1.colsum = nullptr;
+}
+
+// forward of one sub-batch (after mlp_prepare); keepH: also write the fp32 pre-activations (Step 3)
+static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, const MlpWs& ws, bool keepH, void* y,
+                              hipStream_t s) {
+  mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(layer1_args(x, rows, w, ws, keepH));
   if (y) {
     SkinnyArgs g2{};
     g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
@@ -318,31 +391,17 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
 // keepH, (2) dH and db1, (3) the weight gradients
 static hipError_t mlp_backward_dh(int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
                                   const MlpWs& ws, hipStream_t s) {
-  // dA = U W2^T, dH = dA * GELU'(H), db1 += column sums.  One launch per 32-row block so that the
-  // += on db1 has a single writer per column at any time (launches on one stream run in order).
-  for (int mb = 0; mb < rows; mb += 32) {
-    const int mrows = rows - mb < 32 ? rows - mb : 32;
-    SkinnyArgs g{};
-    g.A = u + (size_t)mb * w->dout; g.lda = w->dout; g.Bt = (const unsigned short*)w->W2; g.ldb = w->dout;
-    g.M = mrows; g.N = w->dh; g.K = w->dout;
-    g.H = ws.H + (size_t)mb * w->dh; g.ldh = w->dh; g.Cf = ws.dH + (size_t)mb * w->dh; g.ldc = w->dh; g.colsum = acc->db1;
-    mlp_skinny_kernel<true, EP_DH><<<dim3(w->dh / 32, 1), 256, 0, s>>>(g);
-  }
+  mlp_skinny_kernel<true, EP_DH><<<dim3(w->dh / 32, 1), 256, 0, s>>>(dh_args(rows, w, u, acc, ws));
   return hipGetLastError();
 }
 
 // second half: the weight gradients, from what the first half left in ws
 static hipError_t mlp_backward_wgrad(const void* x, int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
                                      const MlpWs& ws, hipStream_t s) {
-  {  // dW2 += Act^T U, db2 += column sums of U;  dW1 += X^T dH
-    WgradArgs g2{}, g1{};
-    g2.A = ws.ActF; g2.lda = w->dh; g2.B = u; g2.ldb = w->dout; g2.M = w->dh; g2.N = w->dout; g2.K = rows;
-    g2.C = acc->dW2; g2.ldc = w->dout; g2.colsum = acc->db2;
-    g1.A = x; g1.lda = w->din; g1.B = ws.dH; g1.ldb = w->dh; g1.M = w->din; g1.N = w->dh; g1.K = rows;
-    g1.C = acc->dW1; g1.ldc = w->dh; g1.colsum = nullptr;
-    const int n2 = (w->dout / 128) * (w->dh / 32), n1 = (w->dh / 128) * (w->din / 32);
-    mlp_wgrad_kernel<<<n2 + n1, 256, 0, s>>>(g2, g1, n2);
-  }
+  WgradArgs g2, g1;
+  wgrad_args(x, rows, w, u, acc, ws, g2, g1);
+  const int n2 = (w->dout / 128) * (w->dh / 32), n1 = (w->dh / 128) * (w->din / 32);
+  mlp_wgrad_kernel<<<n2 + n1, 256, 0, s>>>(g2, g1, n2);
   return hipGetLastError();
 }
 
@@ -358,35 +417,14 @@ static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, 
 // ---- the one-GPU driver of Steps 1-3 -----------------------------------------------------------------------
 // Sub-batches are small, so one of them cannot fill the GPU.  Step 1 keeps nothing but the representations and
 // its rows do not depend on each other, so kGroup consecutive sub-batches go through each launch (the rows
-// come out bit for bit as they do one sub-batch at a time; only transient buffers grow).  In Step 3 the accumulation order is fixed (sub-batch order), so it runs as a pipeline of
-// three stages, each on a stream of its own and each in sub-batch order: re-encode (sub-batch c+2), dH and db1
-// (c+1, on the caller's stream), weight gradients (c); three sets of buffers are handed over with events.
-constexpr int kLanes = 3;   // buffer sets / pipeline stages of Step 3
+// come out bit for bit as they do one sub-batch at a time; only transient buffers grow).  In Step 3 the
+// accumulation order is fixed (sub-batch order), so it runs as a software pipeline of three stages, one launch
+// (mlp_step3_kernel) per iteration: re-encode of sub-batch c, dH and db1 of c-1, weight gradients of c-2, on three
+// sets of activation buffers.  Everything is enqueued on the caller's stream, in an order that does not depend
+// on timing.
+constexpr int kLanes = 3;   // buffer sets = pipeline stages of Step 3
 constexpr int kGroup = 8;   // sub-batches per launch in Step 1
-struct StepStreams {
-  bool made = false;
-  hipStream_t side[2];
-  hipEvent_t fork, enc_done[3], dh_done[3], wgrad_done[3];
-};
 static std::mutex g_step_mutex;
-static StepStreams g_step_streams[64];
-
-static StepStreams* step_streams() {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  std::lock_guard<std::mutex> lock(g_step_mutex);
-  StepStreams& ss = g_step_streams[dev];
-  if (!ss.made) {
-    bool ok = true;
-    for (int i = 0; i < 2; i++) ok = ok && hipStreamCreateWithFlags(&ss.side[i], hipStreamNonBlocking) == hipSuccess;
-    auto mk = [&](hipEvent_t* e) { ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess; };
-    mk(&ss.fork);
-    for (int i = 0; i < 3; i++) { mk(&ss.enc_done[i]); mk(&ss.dh_done[i]); mk(&ss.wgrad_done[i]); }
-    if (!ok) return nullptr;
-    ss.made = true;
-  }
-  return &ss;
-}
 
 // rows of kGroup sub-batches of `chunk` rows, at most n
 static int group_rows(int chunk, int n) {
@@ -430,8 +468,8 @@ struct StepCall {
   void* workspace;
 };
 
-// enqueues Steps 1-3 on s and on the library's side streams (forked from s, joined back into it)
-static int enqueue_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
+// enqueues Steps 1-3 on s
+static int enqueue_step(const StepCall& c, hipStream_t s) {
   const void* x_q = c.x_q; const void* x_p = c.x_p; const int32_t* pos_idx = c.pos_idx;
   const int B = c.B, P = c.P, chunk_q = c.chunk_q, chunk_p = c.chunk_p;
   const gc_mlp_params* w = &c.w; const gc_mlp_grads* grads = &c.grads;
@@ -478,28 +516,33 @@ static int enqueue_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
                                base + sw.off_loss, sw.loss_bytes, (void*)s);
   if (rc != GC_OK) return rc;
   // Step 3: per sub-batch re-encode and backward of the cached rows; gradients accumulated in index order
-  hipStream_t enc = ss->side[1], wg = ss->side[0];
-  if (!ok(hipEventRecord(ss->fork, s)) || !ok(hipStreamWaitEvent(enc, ss->fork, 0))) return GC_ERR_HIP;  // Step 1 is over
-  for (int c = 0; c < nsub; c++) {
-    const int b = c % 3;
-    if (c >= 3 && !ok(hipStreamWaitEvent(enc, ss->wgrad_done[b], 0))) return GC_ERR_HIP;  // buffers b are free again
-    if (!ok(mlp_forward(subs[c].x, subs[c].rows, w, lane[b], true, nullptr, enc))) return GC_ERR_HIP;
-    if (!ok(hipEventRecord(ss->enc_done[b], enc)) || !ok(hipStreamWaitEvent(s, ss->enc_done[b], 0))) return GC_ERR_HIP;
-    if (!ok(mlp_backward_dh(subs[c].rows, w, subs[c].u, grads, lane[b], s))) return GC_ERR_HIP;
-    if (!ok(hipEventRecord(ss->dh_done[b], s)) || !ok(hipStreamWaitEvent(wg, ss->dh_done[b], 0))) return GC_ERR_HIP;
-    if (!ok(mlp_backward_wgrad(subs[c].x, subs[c].rows, w, subs[c].u, grads, lane[b], wg))) return GC_ERR_HIP;
-    if (!ok(hipEventRecord(ss->wgrad_done[b], wg))) return GC_ERR_HIP;
+  const int n2 = (w->dout / 128) * (w->dh / 32), n1 = (w->dh / 128) * (w->din / 32);
+  for (int i = 0; i < nsub + 2; i++) {
+    Step3Args a3{};
+    if (i >= 2) {                      // weight gradients of sub-batch i-2
+      const Sub& sb = subs[i - 2];
+      wgrad_args(sb.x, sb.rows, w, sb.u, grads, lane[(i - 2) % kLanes], a3.g2, a3.g1);
+      a3.n_wg2 = n2; a3.n_wg = n2 + n1;
+    }
+    if (i >= 1 && i - 1 < nsub) {      // dH, db1 of sub-batch i-1
+      const Sub& sb = subs[i - 1];
+      a3.dh = dh_args(sb.rows, w, sb.u, grads, lane[(i - 1) % kLanes]);
+      a3.n_dh = w->dh / 32;
+    }
+    if (i < nsub) {                    // re-encode of sub-batch i, keeping H and Act
+      const Sub& sb = subs[i];
+      a3.enc = layer1_args(sb.x, sb.rows, w, lane[i % kLanes], true);
+      a3.n_enc = (w->dh / 32) * ((sb.rows + 31) / 32);
+    }
+    mlp_step3_kernel<<<a3.n_wg + a3.n_dh + a3.n_enc, 256, 0, s>>>(a3);
   }
-  // the caller's stream ends after all of it (the weight-gradient stream is in order: its last event covers it;
-  // the re-encode stream's work is covered through dH)
-  if (!ok(hipStreamWaitEvent(s, ss->wgrad_done[(nsub - 1) % 3], 0))) return GC_ERR_HIP;
+  if (!ok(hipGetLastError())) return GC_ERR_HIP;
   return GC_OK;
 }
 
-// A step is some hundreds of small launches, and the host takes longer to enqueue them than the GPU to run
-// them.  The second time a call comes with exactly the same arguments, it is recorded into a HIP graph (on a
+// A step is some seventy small launches, and a host that enqueues them one by one can fall behind the GPU.  The second time a call comes with exactly the same arguments, it is recorded into a HIP graph (on a
 // stream of the library's: the caller's may be the null stream, which cannot be captured) and from then on
-// replayed with one launch.  The graph holds kernels and event dependencies only, no memset nodes.  Up to
+// replayed with one launch.  The graph holds kernel nodes only, no memset nodes.  Up to
 // kMaxGraphs argument sets are remembered per device (a graph in flight is never destroyed); others, calls
 // made while the measurement events of the loss path are on, and calls whose capture fails are enqueued directly.
 constexpr int kMaxGraphs = 8;
@@ -507,10 +550,10 @@ struct StepGraph { StepCall call; int seen; hipGraphExec_t exec; };
 struct StepGraphs { StepGraph g[kMaxGraphs]; int n = 0; hipStream_t cap = nullptr; };
 static StepGraphs g_step_graphs[64];
 
-static int run_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
+static int run_step(const StepCall& c, hipStream_t s) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
-  if (prof_active()) return enqueue_step(c, s, ss);
+  if (prof_active()) return enqueue_step(c, s);
   std::lock_guard<std::mutex> lock(g_step_mutex);
   StepGraphs& G = g_step_graphs[dev];
   StepGraph* e = nullptr;
@@ -518,13 +561,13 @@ static int run_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
     if (memcmp(&G.g[i].call, &c, sizeof(StepCall)) == 0) e = &G.g[i];
   if (!e) {
     if (G.n < kMaxGraphs) { G.g[G.n].call = c; G.g[G.n].seen = 1; G.g[G.n].exec = nullptr; G.n++; }
-    return enqueue_step(c, s, ss);
+    return enqueue_step(c, s);
   }
   if (!e->exec && e->seen == 1) {
     e->seen = 2;  // one attempt
     if (!G.cap && hipStreamCreateWithFlags(&G.cap, hipStreamNonBlocking) != hipSuccess) G.cap = nullptr;
     if (G.cap && hipStreamBeginCapture(G.cap, hipStreamCaptureModeThreadLocal) == hipSuccess) {
-      const int rc = enqueue_step(c, G.cap, ss);
+      const int rc = enqueue_step(c, G.cap);
       hipGraph_t graph = nullptr;
       const hipError_t ee = hipStreamEndCapture(G.cap, &graph);
       hipGraphExec_t exec = nullptr;
@@ -534,7 +577,7 @@ static int run_step(const StepCall& c, hipStream_t s, StepStreams* ss) {
     }
   }
   if (e->exec) return hipGraphLaunch(e->exec, s) == hipSuccess ? GC_OK : GC_ERR_HIP;
-  return enqueue_step(c, s, ss);
+  return enqueue_step(c, s);
 }
 
 }  // namespace gc
@@ -596,9 +639,7 @@ int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32
   c.x_q = x_q; c.x_p = x_p; c.pos_idx = pos_idx; c.B = B; c.P = P; c.chunk_q = chunk_q; c.chunk_p = chunk_p;
   c.w = *w; c.scale = scale; c.temp = temp; c.loss = loss; c.grads = *grads; c.q_rep = q_rep; c.p_rep = p_rep;
   c.dq = dq; c.dp = dp; c.workspace = workspace;
-  StepStreams* ss = step_streams();
-  if (!ss) return GC_ERR_HIP;
-  return run_step(c, (hipStream_t)stream, ss);
+  return run_step(c, (hipStream_t)stream);
 }
 
 }  // extern "C"
