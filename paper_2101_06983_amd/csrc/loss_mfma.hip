@@ -673,10 +673,15 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       p1_load(so2, 0, 1);
 #endif
     }
+    // the partial tile of the owner rows this wave finishes itself stays in registers (steady loop: the wave
+    // index is a compile-time constant there); the other three go through LDS
+    f32x4 own = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (STEADY) own = sacc[WAVE];
 #ifndef GC_EXP_NOX
     if (xw) {
 #pragma unroll
-      for (int dst = 0; dst < 4; dst++) *(f32x4*)(xwp + PAR1 * 16384 + dst * 1024) = sacc[dst];
+      for (int dst = 0; dst < 4; dst++)
+        if (!(STEADY && dst == WAVE)) *(f32x4*)(xwp + PAR1 * 16384 + dst * 1024) = sacc[dst];
     }
 #endif
     if (gw) *(bf16x4*)(gwp + PAR0 * 2048) = gq;
@@ -692,7 +697,10 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     if (xw) {
 #ifndef GC_EXP_NOX
 #pragma unroll
-      for (int src = 0; src < 4; src++) xr[src] = *(const f32x4*)(xrp + PAR1 * 16384 + src * 4096);
+      for (int src = 0; src < 4; src++) {
+        if (STEADY && src == WAVE) xr[src] = own;
+        else xr[src] = *(const f32x4*)(xrp + PAR1 * 16384 + src * 4096);
+      }
 #else
 #pragma unroll
       for (int src = 0; src < 4; src++) xr[src] = sacc[src];
