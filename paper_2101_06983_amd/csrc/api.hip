@@ -23,7 +23,8 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
     pl.stat_cols_per_split = ceil_div(tiles, splits) * 256;
     pl.stat_splits = ceil_div(P, pl.stat_cols_per_split);
     // gradient pass: one workgroup per CU, equal streamed length for both roles
-    const long long obQ = ceil_div(B, 64), obP = ceil_div(P, 64);
+    const int own = (d == 128) ? 256 : 64;   // owner rows per workgroup of the gradient kernel for this width
+    const long long obQ = ceil_div(B, own), obP = ceil_div(P, own);
     const long long W = obQ * P + obP * B;
     long long L = (W + kNumCU - 1) / kNumCU;
     if (L < 256) L = 256;

@@ -807,6 +807,246 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 #endif
 }
 
+
+// ===========================================================================
+// Gradient pass for d = 128 (the NT-Xent workload).  At this width a wave can hold whole owner rows, so
+// nothing is exchanged between waves: a workgroup (4 waves, one per SIMD) owns 256 rows, each wave 64 of
+// them with all 128 columns in registers (64 VGPRs as MFMA B fragments), and all four share the streamed
+// tiles (32 rows x 128 columns, 8 KB) through one LDS ring of four stages.  Per tile and wave:
+//   phase 1  S^T[32 streamed x 64 owner] = R_tile * O^T, 16 MFMAs 32x32x16.  Lane (n, h) then holds, for owner
+//            row n, the scores of streamed rows 8 j + 4 h + i (j, i = 0..3): registers 8 kk .. 8 kk + 7 are
+//            streamed rows 16 kk + {4 h .. 4 h + 3, 8 + 4 h .. 8 + 4 h + 3}.
+//   g        = 2^(t - lse2) - [j = r_i] in place, rounded to bf16: registers 8 kk .. 8 kk + 7 ARE the B
+//            fragment (k = those streamed rows, n = owner) of
+//   phase 2  dO^T[128 x 64 owner] += R_tile^T * g^T, 16 MFMAs 32x32x16, whose A fragments (columns of the tile,
+//            the same streamed rows in the same k order) come from two transposing LDS reads each.
+// The contraction order over the streamed rows is thus a permutation that both operands of phase 2 share.
+// LDS per tile: every wave reads the tile twice (8 KB + 8 KB), 72 KB per workgroup against 64 MFMAs per SIMD.
+// ===========================================================================
+constexpr int G1_OWN = 256, G1_OWN_W = 64, G1_T = 32, G1_STAGES = 4;
+constexpr int G1_STAT = 256;                      // a stage starts with lse2[32], then pos_idx[32] of the streamed rows
+constexpr int G1_STAGE = G1_STAT + G1_T * 256;    // bytes
+constexpr int G1_SMEM = G1_STAGES * G1_STAGE;
+// chunk c (16 bytes) of tile row r is stored at chunk position c ^ swz128(r): 8 consecutive rows of a
+// fragment read, and the 4 rows x 2 chunks of a transposing read, fall into different 16-byte bank groups
+__device__ __forceinline__ int swz128(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+// the first `LANES` lanes of the wave load 16 bytes each to lds_base + lane * 16 (EXEC narrowed inside)
+__device__ __forceinline__ void dma_lanes16(const void* gbase, unsigned voff, unsigned lds_base) {
+  unsigned long long keep;
+  asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffff\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+               : "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+}
+
+template <bool OWNER_IS_Q>
+__device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
+  constexpr int D = 128;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, ln = lane & 31;
+  const int l16 = lane & 15, g16 = lane >> 4;
+  const unsigned short* O = OWNER_IS_Q ? ga.Q : ga.P;
+  const unsigned short* R = OWNER_IS_Q ? ga.P : ga.Q;
+  const int No = OWNER_IS_Q ? ga.B : ga.Pn, Nr = OWNER_IS_Q ? ga.Pn : ga.B;
+  const int slen = OWNER_IS_Q ? ga.q_stream_len : ga.p_stream_len;
+  const int a0 = oblk * G1_OWN + w * G1_OWN_W;   // this wave's first owner row
+  const int sbeg = split * slen, send = min(Nr, sbeg + slen);
+  const int nt = (send - sbeg + G1_T - 1) / G1_T;   // >= 1
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)smem);
+  const int wu = __builtin_amdgcn_readfirstlane(w);   // the wave index as a scalar
+
+  // owner rows as phase-1 B fragments: lane (ln, h) holds owner row 32 n + ln, columns 16 ks + 8 h .. + 7
+  bf16x8 ofrag[2][8];
+  int own_idx[2];
+  float lse_o[2]; int r_o[2];
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+    own_idx[n] = a0 + 32 * n + ln;
+    const int row = min(own_idx[n], No - 1);
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) ofrag[n][ks] = *(const bf16x8*)(O + (size_t)row * D + 16 * ks + 8 * h);
+    lse_o[n] = INFINITY; r_o[n] = -1;            // a row past the end: g = 0
+    if (OWNER_IS_Q && own_idx[n] < No) { lse_o[n] = ga.lse2[own_idx[n]]; r_o[n] = ga.pos_pad[own_idx[n]]; }
+  }
+
+  // ---- loads of a streamed tile: 8 instructions of 4 rows, two per wave; lane -> (row, chunk position) ------
+  auto src_of = [&](int it, int max_row) __attribute__((always_inline)) -> unsigned {
+    const int row = 4 * it + (lane >> 4);
+    const int c = (lane & 15) ^ swz128(row);
+    return (unsigned)(min(row, max_row) * (D * 2) + c * 16);
+  };
+  const unsigned voff_full[2] = {src_of(2 * w, G1_T - 1), src_of(2 * w + 1, G1_T - 1)};
+  const unsigned stat_off = (lane & 8) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 7) : 16u * (lane & 7);
+  const bool stat_wave = !OWNER_IS_Q && wu == 0;
+  auto prefetch = [&](int u) __attribute__((always_inline)) {   // tile u -> stage u % 4
+    const int t0 = sbeg + u * G1_T;
+    const unsigned st = lds0 + (u & (G1_STAGES - 1)) * G1_STAGE;
+    const unsigned short* tile = R + (size_t)t0 * D;
+    if (stat_wave) dma_lanes16(ga.lse2 + t0, stat_off, st);
+    if (t0 + G1_T <= Nr) {
+      dma_group<1>(tile, &voff_full[0], st + G1_STAT + (2 * wu) * 1024);
+      dma_group<1>(tile, &voff_full[1], st + G1_STAT + (2 * wu + 1) * 1024);
+    } else {  // ragged last tile: rows past the end re-read the last valid row (their g is forced to 0)
+#pragma unroll
+      for (int k = 0; k < 2; k++) {
+        const unsigned off = src_of(2 * w + k, Nr - 1 - t0);
+        dma_group<1>(tile, &off, st + G1_STAT + (2 * wu + k) * 1024);
+      }
+    }
+  };
+
+  // per-lane LDS addresses inside a stage
+  const unsigned sw_ln = swz128(ln);
+  // transposing reads: rows 16 kk + 8 e + 4 h + (l16 >> 2), chunk 4 mt + 2 (g16 & 1) + ((l16 & 3) >> 1), half l16 & 1
+  const int tr_r = 4 * h + (l16 >> 2), tr_c = 2 * (g16 & 1) + ((l16 & 3) >> 1);
+  unsigned troff[2][2];  // [kk][e]: the swizzle depends on the row, so one base per (kk, e); + 64 * mt
+#pragma unroll
+  for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+    for (int e = 0; e < 2; e++) {
+      const int row = 16 * kk + 8 * e + tr_r;
+      troff[kk][e] = G1_STAT + row * 256 + 8 * (l16 & 1);   // chunk part added per mt (it is swizzled)
+    }
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+    for (int n = 0; n < 2; n++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[mt][n][r] = 0.f;
+
+#pragma unroll 1
+  for (int u = 0; u < min(nt, G1_STAGES - 1); u++) prefetch(u);
+
+#pragma unroll 1
+  for (int u = 0; u < nt; u++) {
+    // my loads of tile u have landed: at most the tiles u+1, u+2 that were started are still in flight
+    const int later = min(nt - 1 - u, G1_STAGES - 2);
+    if (later >= 2) { if (stat_wave) wait_vmem<6>(); else wait_vmem<4>(); }
+    else if (later == 1) { if (stat_wave) wait_vmem<3>(); else wait_vmem<2>(); }
+    else wait_vmem<0>();
+    __syncthreads();  // ... and everybody's; everybody is done with tile u-1, whose stage is loaded next
+    if (u + G1_STAGES - 1 < nt) prefetch(u + G1_STAGES - 1);
+    const unsigned char* st = smem + (u & (G1_STAGES - 1)) * G1_STAGE;
+    const int t0 = sbeg + u * G1_T;
+    __builtin_amdgcn_iglp_opt(0);
+
+    // ---- phase 1 ----
+    f32x16 sacc[2];
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      const int c = (2 * ks + h);
+      const bf16x8 a = *(const bf16x8*)(st + G1_STAT + ln * 256 + ((c ^ (int)sw_ln) * 16));
+#pragma unroll
+      for (int n = 0; n < 2; n++) {
+        if (ks == 0) {
+          f32x16 z;
+#pragma unroll
+          for (int r = 0; r < 16; r++) z[r] = 0.f;
+          sacc[n] = mfma32(a, ofrag[n][ks], z);
+        } else {
+          sacc[n] = mfma32(a, ofrag[n][ks], sacc[n]);
+        }
+      }
+    }
+    // transposing reads of phase 2 (issued before the softmax arithmetic so that they are back in time)
+    bf16x8 afr[4][2];
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+      for (int kk = 0; kk < 2; kk++) {
+        s16x4 q[2];
+#pragma unroll
+        for (int e = 0; e < 2; e++) {
+          const int row = 16 * kk + 8 * e + tr_r;
+          const int c = (4 * mt + tr_c) ^ swz128(row);
+          q[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + troff[kk][e] + c * 16));
+        }
+        s16x8 t = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
+        afr[mt][kk] = __builtin_bit_cast(bf16x8, t);
+      }
+
+    // ---- g ----
+    f32x4 lse_r[4]; i32x4 pos_r[4];
+    if (!OWNER_IS_Q) {
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        lse_r[j] = *(const f32x4*)(st + (8 * j + 4 * h) * 4);
+        pos_r[j] = *(const i32x4*)(st + 128 + (8 * j + 4 * h) * 4);
+      }
+    }
+    bool rare = (t0 + G1_T > send) || (ga.mask_self && (t0 < a0 + G1_OWN_W) && (t0 + G1_T > a0));
+    if (OWNER_IS_Q) {
+      rare = rare || (unsigned)(r_o[0] - t0) < (unsigned)G1_T || (unsigned)(r_o[1] - t0) < (unsigned)G1_T;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) rare = rare || (unsigned)(pos_r[j][i] - a0) < (unsigned)G1_OWN_W;
+    }
+    const bool any_rare = __builtin_amdgcn_ballot_w64(rare) != 0;
+    bf16x8 gfr[2][2];
+#pragma unroll
+    for (int n = 0; n < 2; n++) {
+      float gv[16];
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const float l = OWNER_IS_Q ? lse_o[n] : lse_r[r >> 2][r & 3];
+        gv[r] = fast_exp2(sacc[n][r] * ga.alpha2 - l);
+      }
+      if (any_rare) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int m = t0 + 8 * (r >> 2) + 4 * h + (r & 3);   // streamed row of this register
+          const bool hit = OWNER_IS_Q ? (r_o[n] == m) : (pos_r[r >> 2][r & 3] == own_idx[n]);
+          if (hit) gv[r] -= 1.f;
+          if (m >= send || (ga.mask_self && m == own_idx[n])) gv[r] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; kk++) {
+        typedef __attribute__((ext_vector_type(8))) float f32x8;
+        const f32x8 v = {gv[8 * kk], gv[8 * kk + 1], gv[8 * kk + 2], gv[8 * kk + 3], gv[8 * kk + 4], gv[8 * kk + 5], gv[8 * kk + 6], gv[8 * kk + 7]};
+        gfr[n][kk] = __builtin_convertvector(v, bf16x8);
+      }
+    }
+    // ---- phase 2 ----
+#pragma unroll
+    for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+      for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+        for (int n = 0; n < 2; n++) acc[mt][n] = mfma32(afr[mt][kk], gfr[n][kk], acc[mt][n]);
+  }
+
+  // ---- epilogue: lane (ln, h) holds owner row 32 n + ln, columns 32 mt + 8 (r / 4) + 4 h + r % 4 -----------------
+  float* out = OWNER_IS_Q ? (ga.dq_out + (size_t)split * ga.dq_split_stride) : (ga.dp_out + (size_t)split * ga.dp_split_stride);
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+    if (own_idx[n] < No) {
+#pragma unroll
+      for (int mt = 0; mt < 4; mt++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const f32x4 v = {acc[mt][n][4 * j] * ga.out_scale, acc[mt][n][4 * j + 1] * ga.out_scale,
+                           acc[mt][n][4 * j + 2] * ga.out_scale, acc[mt][n][4 * j + 3] * ga.out_scale};
+          *(f32x4*)(out + (size_t)own_idx[n] * D + 32 * mt + 8 * j + 4 * h) = v;
+        }
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) grad128_kernel(GradArgs ga) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
+  const int nQ = ga.obQ * ga.nsq;
+  const int id = xcd_task_id();
+  if (id < nQ) {
+    grad128_body<true>(ga, id % ga.obQ, id / ga.obQ, gsmem);
+  } else {
+    const int t = id - nQ;
+    grad128_body<false>(ga, t % ga.obP, t / ga.obP, gsmem);
+  }
+}
+
 template <int D>
 __global__ void __launch_bounds__(256) grad_mfma_kernel(GradArgs ga) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
@@ -839,8 +1079,9 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   ga.mask_self = (a.flags & GC_MASK_SELF) ? 1 : 0;
   const bool want_q = a.dq || a.dz, want_p = a.dp || a.dz;
   const size_t nq = (size_t)a.B * a.d, np = (size_t)a.P * a.d;
-  ga.obQ = want_q ? (a.B + GR_OWN - 1) / GR_OWN : 0; ga.nsq = pl.nsq; ga.q_stream_len = pl.q_stream_len;
-  ga.obP = want_p ? (a.P + GR_OWN - 1) / GR_OWN : 0; ga.nsp = pl.nsp; ga.p_stream_len = pl.p_stream_len;
+  const int own = (a.d == 128) ? G1_OWN : GR_OWN;   // owner rows per workgroup
+  ga.obQ = want_q ? (a.B + own - 1) / own : 0; ga.nsq = pl.nsq; ga.q_stream_len = pl.q_stream_len;
+  ga.obP = want_p ? (a.P + own - 1) / own : 0; ga.nsp = pl.nsp; ga.p_stream_len = pl.p_stream_len;
   const bool q_direct = (pl.nsq == 1 && !a.dz), p_direct = (pl.nsp == 1 && !a.dz);
   ga.dq_out = q_direct ? a.dq : (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
   ga.dp_out = p_direct ? a.dp : (float*)(ws + pl.off_dp_part); ga.dp_split_stride = np;
@@ -848,7 +1089,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   if (nwg == 0) { prof_mark_grad_kernel_done(a.stream); return hipSuccess; }
   hipError_t e;
   switch (a.d) {
-    case 128: e = grad_mfma_launch<128>(ga, nwg, a.stream); break;
+    case 128: grad128_kernel<<<nwg, 256, G1_SMEM, a.stream>>>(ga); e = hipGetLastError(); break;
     case 256: e = grad_mfma_launch<256>(ga, nwg, a.stream); break;
     case 384: e = grad_mfma_launch<384>(ga, nwg, a.stream); break;
     case 512: e = grad_mfma_launch<512>(ga, nwg, a.stream); break;
