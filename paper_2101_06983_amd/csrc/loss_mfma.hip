@@ -823,7 +823,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 // The contraction order over the streamed rows is thus a permutation that both operands of phase 2 share.
 // LDS per tile: every wave reads the tile twice (8 KB + 8 KB), 72 KB per workgroup against 64 MFMAs per SIMD.
 // ===========================================================================
-constexpr int G1_OWN = 256, G1_OWN_W = 64, G1_T = 32, G1_STAGES = 4;
+constexpr int G1_OWN = 256, G1_OWN_W = 64, G1_T = 32, G1_STAGES = 8, G1_AHEAD = 6;  // tiles u-1 .. u+1 alive, up to u+5 started
 constexpr int G1_STAT = 256;                      // a stage starts with lse2[32], then pos_idx[32] of the streamed rows
 constexpr int G1_STAGE = G1_STAT + G1_T * 256;    // bytes
 constexpr int G1_SMEM = G1_STAGES * G1_STAGE;
@@ -865,6 +865,14 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
     for (int ks = 0; ks < 8; ks++) ofrag[n][ks] = *(const bf16x8*)(O + (size_t)row * D + 16 * ks + 8 * h);
     lse_o[n] = INFINITY; r_o[n] = -1;            // a row past the end: g = 0
     if (OWNER_IS_Q && own_idx[n] < No) { lse_o[n] = ga.lse2[own_idx[n]]; r_o[n] = ga.pos_pad[own_idx[n]]; }
+  }
+  // The compiler's own loads end here: it does not see the direct-to-LDS loads below, and a wait of its own for
+  // these registers inside the loop would also wait for those.  An empty statement that "uses" every loaded register.
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) asm volatile("" : "+v"(ofrag[n][ks]));
+    asm volatile("" : "+v"(lse_o[n]), "+v"(r_o[n]));
   }
 
   // ---- loads of a streamed tile: 8 instructions of 4 rows, two per wave; lane -> (row, chunk position) ------
@@ -914,108 +922,153 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[mt][n][r] = 0.f;
 
-#pragma unroll 1
-  for (int u = 0; u < min(nt, G1_STAGES - 1); u++) prefetch(u);
+  // ---- software pipeline over the tiles: iteration u interleaves, MFMA by MFMA, phase 1 of tile u+1, the
+  // exp2 arithmetic of tile u (whose scores iteration u-1 left in registers) and phase 2 of tile u-1 (whose g the
+  // previous iteration left as fragments): a wave's VALU work hides behind its own MFMAs only when interleaved.
+  // Tiles u-1, u, u+1 are alive in the ring, u+2 .. u+5 in flight.
+  f32x16 sacc[2][2];     // [tile parity][owner half]
+  bf16x8 gfr[2][2];      // g of the tile last through the softmax: [owner half][kk]
+#pragma unroll
+  for (int n = 0; n < 2; n++)
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) gfr[n][kk][e] = 0;
 
 #pragma unroll 1
-  for (int u = 0; u < nt; u++) {
-    // my loads of tile u have landed: at most the tiles u+1, u+2 that were started are still in flight
-    const int later = min(nt - 1 - u, G1_STAGES - 2);
-    if (later >= 2) { if (stat_wave) wait_vmem<6>(); else wait_vmem<4>(); }
-    else if (later == 1) { if (stat_wave) wait_vmem<3>(); else wait_vmem<2>(); }
-    else wait_vmem<0>();
-    __syncthreads();  // ... and everybody's; everybody is done with tile u-1, whose stage is loaded next
-    if (u + G1_STAGES - 1 < nt) prefetch(u + G1_STAGES - 1);
-    const unsigned char* st = smem + (u & (G1_STAGES - 1)) * G1_STAGE;
-    const int t0 = sbeg + u * G1_T;
-    __builtin_amdgcn_iglp_opt(0);
+  for (int u = 0; u < min(nt, G1_AHEAD - 1); u++) prefetch(u);   // iteration -1 starts tile G1_AHEAD - 1
 
-    // ---- phase 1 ----
-    f32x16 sacc[2];
+  // PT: parity of tile u+1 (where phase 1 writes); the softmax reads parity PT ^ 1
+  // STEADY: all three parts are live (1 <= u, u + 1 < nt): no branches inside the MFMA stream
+  auto body = [&](int u, auto pt_tag, auto steady_tag) __attribute__((always_inline)) {
+    constexpr int PT = decltype(pt_tag)::value;
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const bool p1 = STEADY || (u + 1 < nt), sm = STEADY || (u >= 0 && u < nt), p2 = STEADY || (u >= 1);
+    // my loads of tile u+1 have landed (tiles up to u + G1_AHEAD - 1 have been started)
+    if (p1) {
+      const int later = min(nt - 1, u + G1_AHEAD - 1) - (u + 1);   // tiles started after u+1: 0 .. G1_AHEAD - 2
+      if (stat_wave) { if (later >= 4) wait_vmem<12>(); else if (later == 3) wait_vmem<9>(); else if (later == 2) wait_vmem<6>(); else if (later == 1) wait_vmem<3>(); else wait_vmem<0>(); }
+      else { if (later >= 4) wait_vmem<8>(); else if (later == 3) wait_vmem<6>(); else if (later == 2) wait_vmem<4>(); else if (later == 1) wait_vmem<2>(); else wait_vmem<0>(); }
+    }
+    __syncthreads();  // ... and everybody's; everybody is done with tile u-2, whose stage is loaded next
+    if (u + G1_AHEAD < nt) prefetch(u + G1_AHEAD);
+    const unsigned char* st_p1 = smem + ((u + 1) & (G1_STAGES - 1)) * G1_STAGE;
+    const unsigned char* st_sm = smem + (u & (G1_STAGES - 1)) * G1_STAGE;
+    const unsigned char* st_p2 = smem + ((u - 1) & (G1_STAGES - 1)) * G1_STAGE;
+    const int t0 = sbeg + u * G1_T;   // first streamed row of tile u
+
+    // fragments: row statistics of tile u, then tile u+1 for phase 1 and transposed tile u-1 for phase 2 in
+    // the order in which the rounds below consume them (LDS returns reads in order, and the 24 reads of the
+    // four waves keep the LDS busy for most of an iteration: the first MFMAs must not wait for the last read)
+    f32x4 lse_r[4]; i32x4 pos_r[4];
+    if (!OWNER_IS_Q && sm) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ks++) {
-      const int c = (2 * ks + h);
-      const bf16x8 a = *(const bf16x8*)(st + G1_STAT + ln * 256 + ((c ^ (int)sw_ln) * 16));
-#pragma unroll
-      for (int n = 0; n < 2; n++) {
-        if (ks == 0) {
-          f32x16 z;
-#pragma unroll
-          for (int r = 0; r < 16; r++) z[r] = 0.f;
-          sacc[n] = mfma32(a, ofrag[n][ks], z);
-        } else {
-          sacc[n] = mfma32(a, ofrag[n][ks], sacc[n]);
-        }
+      for (int j = 0; j < 4; j++) {
+        lse_r[j] = *(const f32x4*)(st_sm + (8 * j + 4 * h) * 4);
+        pos_r[j] = *(const i32x4*)(st_sm + 128 + (8 * j + 4 * h) * 4);
       }
     }
-    // transposing reads of phase 2 (issued before the softmax arithmetic so that they are back in time)
+    bf16x8 pfr[8];
     bf16x8 afr[4][2];
 #pragma unroll
-    for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-      for (int kk = 0; kk < 2; kk++) {
+    for (int k = 0; k < 8; k++) {   // round 2 k needs pfr[k] and afr[k / 2][k % 2]
+      if (p1) pfr[k] = *(const bf16x8*)(st_p1 + G1_STAT + ln * 256 + (((2 * k + h) ^ (int)sw_ln) * 16));
+      if (p2) {
+        const int mt = k / 2, kk = k % 2;
         s16x4 q[2];
 #pragma unroll
         for (int e = 0; e < 2; e++) {
           const int row = 16 * kk + 8 * e + tr_r;
           const int c = (4 * mt + tr_c) ^ swz128(row);
-          q[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st + troff[kk][e] + c * 16));
+          q[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(st_p2 + troff[kk][e] + c * 16));
         }
         s16x8 t = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
         afr[mt][kk] = __builtin_bit_cast(bf16x8, t);
       }
-
-    // ---- g ----
-    f32x4 lse_r[4]; i32x4 pos_r[4];
-    if (!OWNER_IS_Q) {
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        lse_r[j] = *(const f32x4*)(st + (8 * j + 4 * h) * 4);
-        pos_r[j] = *(const i32x4*)(st + 128 + (8 * j + 4 * h) * 4);
-      }
     }
-    bool rare = (t0 + G1_T > send) || (ga.mask_self && (t0 < a0 + G1_OWN_W) && (t0 + G1_T > a0));
-    if (OWNER_IS_Q) {
-      rare = rare || (unsigned)(r_o[0] - t0) < (unsigned)G1_T || (unsigned)(r_o[1] - t0) < (unsigned)G1_T;
-    } else {
+    // 16 rounds: one phase-1 MFMA pair position, one phase-2 MFMA, the exp2 of two scores
+    static_for<16>([&](auto i_tag) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_tag)::value;
+      if (p1) {
+        constexpr int ks = i / 2, n = i % 2;
+        if constexpr (ks == 0) {
+          f32x16 z;
 #pragma unroll
-      for (int j = 0; j < 4; j++)
-#pragma unroll
-        for (int i = 0; i < 4; i++) rare = rare || (unsigned)(pos_r[j][i] - a0) < (unsigned)G1_OWN_W;
-    }
-    const bool any_rare = __builtin_amdgcn_ballot_w64(rare) != 0;
-    bf16x8 gfr[2][2];
-#pragma unroll
-    for (int n = 0; n < 2; n++) {
-      float gv[16];
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const float l = OWNER_IS_Q ? lse_o[n] : lse_r[r >> 2][r & 3];
-        gv[r] = fast_exp2(sacc[n][r] * ga.alpha2 - l);
-      }
-      if (any_rare) {
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int m = t0 + 8 * (r >> 2) + 4 * h + (r & 3);   // streamed row of this register
-          const bool hit = OWNER_IS_Q ? (r_o[n] == m) : (pos_r[r >> 2][r & 3] == own_idx[n]);
-          if (hit) gv[r] -= 1.f;
-          if (m >= send || (ga.mask_self && m == own_idx[n])) gv[r] = 0.f;
+          for (int r = 0; r < 16; r++) z[r] = 0.f;
+          sacc[PT][n] = mfma32(pfr[ks], ofrag[n][ks], z);
+        } else {
+          sacc[PT][n] = mfma32(pfr[ks], ofrag[n][ks], sacc[PT][n]);
         }
       }
+      if (p2) {
+        constexpr int mt = i / 4, kk = (i / 2) % 2, n = i % 2;
+        acc[mt][n] = mfma32(afr[mt][kk], gfr[n][kk], acc[mt][n]);
+      }
+      if (sm) {
 #pragma unroll
-      for (int kk = 0; kk < 2; kk++) {
-        typedef __attribute__((ext_vector_type(8))) float f32x8;
-        const f32x8 v = {gv[8 * kk], gv[8 * kk + 1], gv[8 * kk + 2], gv[8 * kk + 3], gv[8 * kk + 4], gv[8 * kk + 5], gv[8 * kk + 6], gv[8 * kk + 7]};
-        gfr[n][kk] = __builtin_convertvector(v, bf16x8);
+        for (int n = 0; n < 2; n++) {
+          const float l = OWNER_IS_Q ? lse_o[n] : lse_r[i >> 2][i & 3];
+          float e = fast_exp2(sacc[PT ^ 1][n][i] * ga.alpha2 - l);
+          // an empty statement that "uses" the value: it keeps the arithmetic inside this round (pure
+          // arithmetic would otherwise be moved behind all the MFMAs and run exposed)
+          if constexpr (STEADY) asm volatile("" : "+v"(e));
+          sacc[PT ^ 1][n][i] = e;
+        }
+      }
+      if constexpr (STEADY) __builtin_amdgcn_sched_barrier(0);  // the rounds stay in order
+    });
+    if (sm) {
+      // -1 at the positive (j == r_i), zeros for rows past the end of the split and on the diagonal: few tiles
+      bool rare = (t0 + G1_T > send) || (ga.mask_self && (t0 < a0 + G1_OWN_W) && (t0 + G1_T > a0));
+      if (OWNER_IS_Q) {
+        rare = rare || (unsigned)(r_o[0] - t0) < (unsigned)G1_T || (unsigned)(r_o[1] - t0) < (unsigned)G1_T;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+          for (int e = 0; e < 4; e++) rare = rare || (unsigned)(pos_r[j][e] - a0) < (unsigned)G1_OWN_W;
+      }
+      if (__builtin_amdgcn_ballot_w64(rare) != 0) {
+#pragma unroll
+        for (int n = 0; n < 2; n++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int m = t0 + 8 * (r >> 2) + 4 * h + (r & 3);   // streamed row of this register
+            const bool hit = OWNER_IS_Q ? (r_o[n] == m) : (pos_r[r >> 2][r & 3] == own_idx[n]);
+            if (hit) sacc[PT ^ 1][n][r] -= 1.f;
+            if (m >= send || (ga.mask_self && m == own_idx[n])) sacc[PT ^ 1][n][r] = 0.f;
+          }
       }
     }
-    // ---- phase 2 ----
+    // the phase-2 MFMAs above have read the old fragments: now they take the g of tile u
+    if (sm) {
 #pragma unroll
-    for (int mt = 0; mt < 4; mt++)
+      for (int n = 0; n < 2; n++)
 #pragma unroll
-      for (int kk = 0; kk < 2; kk++)
-#pragma unroll
-        for (int n = 0; n < 2; n++) acc[mt][n] = mfma32(afr[mt][kk], gfr[n][kk], acc[mt][n]);
+        for (int kk = 0; kk < 2; kk++) {
+          typedef __attribute__((ext_vector_type(8))) float f32x8;
+          const f32x16& g = sacc[PT ^ 1][n];
+          const f32x8 v = {g[8 * kk], g[8 * kk + 1], g[8 * kk + 2], g[8 * kk + 3], g[8 * kk + 4], g[8 * kk + 5], g[8 * kk + 6], g[8 * kk + 7]};
+          gfr[n][kk] = __builtin_convertvector(v, bf16x8);
+        }
+    }
+  };
+  // iterations u = -1 .. nt (phase 1 of tile 0 first, phase 2 of tile nt-1 last), two per trip so that the
+  // parity of the score registers is a compile-time constant
+  constexpr std::integral_constant<int, 0> pt0{};   // u odd: tile u+1 has parity 0
+  constexpr std::integral_constant<int, 1> pt1{};
+  body(-1, pt0, std::false_type{});
+  body(0, pt1, std::false_type{});
+  int u = 1;
+#pragma unroll 1
+  for (; u + 2 < nt; u += 2) {
+    body(u, pt0, std::true_type{});
+    body(u + 1, pt1, std::true_type{});
+  }
+#pragma unroll 1
+  for (; u <= nt; u += 2) {
+    body(u, pt0, std::false_type{});
+    if (u + 1 <= nt) body(u + 1, pt1, std::false_type{});
   }
 
   // ---- epilogue: lane (ln, h) holds owner row 32 n + ln, columns 32 mt + 8 (r / 4) + 4 h + r % 4 -----------------
@@ -1089,7 +1142,17 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   if (nwg == 0) { prof_mark_grad_kernel_done(a.stream); return hipSuccess; }
   hipError_t e;
   switch (a.d) {
-    case 128: grad128_kernel<<<nwg, 256, G1_SMEM, a.stream>>>(ga); e = hipGetLastError(); break;
+    case 128: {
+      static bool attr_set = false;
+      if (!attr_set) {
+        e = hipFuncSetAttribute((const void*)grad128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, G1_SMEM);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+      }
+      grad128_kernel<<<nwg, 256, G1_SMEM, a.stream>>>(ga);
+      e = hipGetLastError();
+      break;
+    }
     case 256: e = grad_mfma_launch<256>(ga, nwg, a.stream); break;
     case 384: e = grad_mfma_launch<384>(ga, nwg, a.stream); break;
     case 512: e = grad_mfma_launch<512>(ga, nwg, a.stream); break;
