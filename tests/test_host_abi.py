@@ -75,3 +75,41 @@ def test_argument_errors_are_raised_on_the_host():
     assert nt(fake, 15, 128, 0.1, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
     assert nt(fake, 16, 128, -1.0, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
     assert nt(fake, 16, 128, 0.1, fake, fake, fake, 8, None) == gc.GC_ERR_WORKSPACE
+
+
+def test_mlp_argument_errors_are_raised_on_the_host():
+    lib = gc.load()
+    vp = ctypes.c_void_p
+    fake = 256  # never dereferenced
+    ok = gc.gc_mlp_params(fake, fake, fake, fake, 1024, 3072, 768)
+    grads = gc.gc_mlp_grads(fake, fake, fake, fake)
+    ref = ctypes.byref
+    # workspace sizes: 0 for bad shapes, linear in the rows of a sub-batch otherwise
+    assert lib.gc_mlp_workspace_bytes(32, ref(gc.gc_mlp_params(fake, fake, fake, fake, 1000, 3072, 768))) == 0
+    w32, w64 = lib.gc_mlp_workspace_bytes(32, ref(ok)), lib.gc_mlp_workspace_bytes(64, ref(ok))
+    assert 0 < w32 < w64 and w64 - w32 == 32 * 3072 * 4 * 3
+    assert lib.gc_step_mlp_workspace_bytes(512, 1024, 32, 32, ref(ok)) > w32
+    assert lib.gc_step_mlp_workspace_bytes(512, 1024, 0, 32, ref(ok)) == 0
+    fwd = lib.gc_mlp_forward_nograd_bf16
+    assert fwd(None, 32, ref(ok), vp(fake), vp(fake), 1 << 30, None) == gc.GC_ERR_NULL
+    assert fwd(vp(fake), 32, None, vp(fake), vp(fake), 1 << 30, None) == gc.GC_ERR_NULL
+    assert fwd(vp(fake), 0, ref(ok), vp(fake), vp(fake), 1 << 30, None) == gc.GC_ERR_SHAPE
+    assert fwd(vp(fake), 32, ref(ok), vp(fake), vp(fake), 64, None) == gc.GC_ERR_WORKSPACE
+    assert fwd(vp(fake), 32, ref(ok), vp(fake), vp(264), 1 << 30, None) == gc.GC_ERR_WORKSPACE
+    bad_dh = gc.gc_mlp_params(fake, fake, fake, fake, 1024, 3000, 768)
+    assert fwd(vp(fake), 32, ref(bad_dh), vp(fake), vp(fake), 1 << 30, None) == gc.GC_ERR_UNSUPPORTED
+    no_w2 = gc.gc_mlp_params(fake, fake, None, fake, 1024, 3072, 768)
+    assert fwd(vp(fake), 32, ref(no_w2), vp(fake), vp(fake), 1 << 30, None) == gc.GC_ERR_NULL
+    bwd = lib.gc_chunk_surrogate_backward_bf16
+    assert bwd(vp(fake), 32, ref(ok), None, ref(grads), vp(fake), 1 << 30, None) == gc.GC_ERR_NULL
+    assert bwd(vp(fake), 32, ref(ok), vp(fake), ref(gc.gc_mlp_grads(fake, None, fake, fake)), vp(fake), 1 << 30, None) == gc.GC_ERR_NULL
+    assert bwd(vp(fake), 32, ref(ok), vp(fake), ref(grads), vp(fake), 8, None) == gc.GC_ERR_WORKSPACE
+    step = lib.gc_step_mlp_bf16
+    sargs = lambda **k: [vp(fake), k.get("B", 512), vp(fake), 1024, vp(fake), k.get("cq", 32), 32, ref(ok), 1.0, k.get("temp", 1.0),
+                         k.get("loss", vp(fake)), ref(grads), None, None, None, None, k.get("ws", vp(fake)), k.get("wsb", 1 << 40), None]
+    assert step(*sargs(B=0)) == gc.GC_ERR_SHAPE
+    assert step(*sargs(cq=0)) == gc.GC_ERR_SHAPE
+    assert step(*sargs(temp=0.0)) == gc.GC_ERR_SHAPE
+    assert step(*sargs(loss=None)) == gc.GC_ERR_NULL
+    assert step(*sargs(ws=None)) == gc.GC_ERR_WORKSPACE
+    assert step(*sargs(wsb=1024)) == gc.GC_ERR_WORKSPACE
