@@ -75,6 +75,9 @@ def test_config2_dpr_shaped_bf16():
     (1, 1000, 384, 3.0, 1.0),
     (300, 31, 512, 1.0, 1.0),      # fewer targets than one stream tile
     (257, 513, 768, 1.0, 0.25),
+    (600, 1100, 128, 1.0, 0.2),    # d = 128 kernel: several 256-row owner blocks, ragged owner and stream ends
+    (257, 64, 128, 2.0, 1.0),      # d = 128: one row past an owner block, two stream tiles
+    (2048, 4096, 128, 1.0, 1.0),   # d = 128: long streams, split partials
     (64, 96, 96, 1.0, 1.0),        # d not a multiple of 128: general kernel on bf16 storage
     (20, 50, 8, 1.0, 1.0),
 ])
