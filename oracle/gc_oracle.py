@@ -25,7 +25,7 @@ import numpy as np
 from scipy.special import erf
 
 __all__ = [
-    "loss_and_rep_grad", "ntxent", "mlp_forward", "mlp_backward",
+    "loss_and_rep_grad", "ntxent", "bidirectional", "mlp_forward", "mlp_backward",
     "mlp_fullbatch_grad", "mlp_chunked_grad", "mlp_accumulation_grad", "round_to_bf16",
 ]
 
@@ -106,6 +106,26 @@ def ntxent(z, temp):
     r = np.arange(n) ^ 1
     out = loss_and_rep_grad(z, z, r, scale=1.0, temp=temp, mask_self=True)
     return dict(loss=out["loss"], dz=out["dq"] + out["dp"], lse=out["lse"])
+
+
+def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0):
+    """Symmetric in-batch-negative loss: anchors against targets and targets
+    against anchors (one of the loss variations Step 2 admits; the method only
+    needs dL/df(s_i) and dL/dg(t_j)).  B = P and r must be a bijection:
+      L = 1/2 [ L(F, G, r) + L(G, F, r^-1) ],
+    each term Eq. 1 with the roles of the two sides exchanged in the second.
+    Returns dict(loss, dq, dp): each gradient is the sum of Eq. 5 of one term
+    and Eq. 6 of the other, halved."""
+    q = _f64(q)
+    p = _f64(p)
+    r = np.asarray(pos_idx, dtype=np.int64)
+    n = q.shape[0]
+    assert p.shape[0] == n and sorted(r.tolist()) == list(range(n))
+    rinv = np.empty(n, dtype=np.int64)
+    rinv[r] = np.arange(n)
+    a = loss_and_rep_grad(q, p, r, scale, temp)
+    b = loss_and_rep_grad(p, q, rinv, scale, temp)
+    return dict(loss=0.5 * (a["loss"] + b["loss"]), dq=0.5 * (a["dq"] + b["dp"]), dp=0.5 * (a["dp"] + b["dq"]))
 
 
 # ---------------------------------------------------------------------------

@@ -199,6 +199,36 @@ def test_lib_ntxent_symmetric():
     np.testing.assert_allclose(out["dz"], tz.grad.numpy(), rtol=1e-9, atol=1e-14)
 
 
+def test_lib_and_fd_bidirectional():
+    # symmetric loss: cross-entropy of the rows and of the columns of one score matrix (library routine +
+    # autograd), and central differences of that definition written out by enumeration
+    n, d = 12, 5
+    q, p, _ = rand_problem(n, n, d, seed=41, std=1.0)
+    r = rng(42).permutation(n)
+    alpha = 1.7
+    out = O.bidirectional(q, p, r, scale=alpha, temp=1.0)
+    tq = torch.tensor(q, dtype=torch.float64, requires_grad=True)
+    tp = torch.tensor(p, dtype=torch.float64, requires_grad=True)
+    s = alpha * tq @ tp.T
+    rinv = np.argsort(r)
+    loss = 0.5 * (torch.nn.functional.cross_entropy(s, torch.tensor(r, dtype=torch.long)) +
+                  torch.nn.functional.cross_entropy(s.T, torch.tensor(rinv, dtype=torch.long)))
+    loss.backward()
+    assert out["loss"] == pytest.approx(loss.item(), rel=1e-12)
+    np.testing.assert_allclose(out["dq"], tq.grad.numpy(), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(out["dp"], tp.grad.numpy(), rtol=1e-9, atol=1e-14)
+    f = lambda: 0.5 * (brute_force_loss(q.tolist(), p.tolist(), r.tolist(), alpha) +
+                       brute_force_loss(p.tolist(), q.tolist(), rinv.tolist(), alpha))
+    assert out["loss"] == pytest.approx(f(), rel=1e-13)
+    assert_close_norm(out["dq"], fd_grad(f, q), 1e-7)
+    assert_close_norm(out["dp"], fd_grad(f, p), 1e-7)
+    # with q = p and the identity pairing the two directions coincide: same loss as one direction
+    one = O.loss_and_rep_grad(q, q, np.arange(n), alpha, 1.0)
+    both = O.bidirectional(q, q, np.arange(n), alpha, 1.0)
+    assert both["loss"] == pytest.approx(one["loss"], rel=1e-13)
+    np.testing.assert_allclose(both["dq"] + both["dp"], one["dq"] + one["dp"], rtol=1e-10, atol=1e-15)
+
+
 # ------------------------------------------------------------------ invariants
 def test_i1_i2_row_sums_and_euler_identity():
     q, p, r = rand_problem(17, 29, 24, seed=50)
