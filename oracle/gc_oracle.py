@@ -34,13 +34,19 @@ def _f64(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
 
 
-def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False):
+def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False, g_dtype=None):
     """Contrastive loss (Eq. 1) and its representation gradients (Eq. 4-7).
 
     q: [B, d] anchors f(s_i); p: [P, d] targets g(t_j); pos_idx: [B] ints r_i.
     Logits are s_ij = (scale / temp) * <q_i, p_j>  (Eq. 1 with the 1/tau kept;
     `scale` is an extra multiplier on the dot product, 1 in the paper).
     mask_self: s_ii = -inf (needs B == P), used by the NT-Xent variation.
+    g_dtype: None is the definition in fp64 throughout.  "bf16" rounds the
+    coefficients g_ij = p_ij - [j == r_i] to bf16 (nearest even) before the two
+    contractions of Eq. 5 and Eq. 6, which are still summed in fp64: the value
+    of a path that feeds those contractions bf16 operands.  Each g_ij then
+    carries a relative error of at most 2^-8, so dq and dp stay within 2^-8 of
+    sum_j |g_ij| |p_j| resp. sum_i |g_ij| |q_i| of the definition.
 
     Returns dict with
       loss      Eq. 1, mean over the B anchors
@@ -80,6 +86,9 @@ def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False):
     # g_ij = p_ij - [j == r_i]
     g = np.exp(s - lse[:, None])
     g[np.arange(B), r] -= 1.0
+    if g_dtype is not None:
+        assert g_dtype == "bf16"
+        g = round_to_bf16(g)
 
     # Eq. 5:  dL/df(s_i) = -(1/|S|) (g(t_{r_i}) - sum_j p_ij g(t_j))      (* alpha)
     dq = (alpha / B) * (g @ p)
@@ -89,7 +98,7 @@ def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False):
                 argmax=argmax.astype(np.int64), dq=dq, dp=dp)
 
 
-def ntxent(z, temp):
+def ntxent(z, temp, g_dtype=None):
     """NT-Xent over 2N views (the loss variation named in Sec. Related Work /
     Step 2's remark that other contrastive losses are supported).
 
@@ -104,11 +113,11 @@ def ntxent(z, temp):
     n = z.shape[0]
     assert n % 2 == 0 and n >= 2
     r = np.arange(n) ^ 1
-    out = loss_and_rep_grad(z, z, r, scale=1.0, temp=temp, mask_self=True)
+    out = loss_and_rep_grad(z, z, r, scale=1.0, temp=temp, mask_self=True, g_dtype=g_dtype)
     return dict(loss=out["loss"], dz=out["dq"] + out["dp"], lse=out["lse"])
 
 
-def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0):
+def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0, g_dtype=None):
     """Symmetric in-batch-negative loss: anchors against targets and targets
     against anchors (one of the loss variations Step 2 admits; the method only
     needs dL/df(s_i) and dL/dg(t_j)).  B = P and r must be a bijection:
@@ -123,8 +132,8 @@ def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0):
     assert p.shape[0] == n and sorted(r.tolist()) == list(range(n))
     rinv = np.empty(n, dtype=np.int64)
     rinv[r] = np.arange(n)
-    a = loss_and_rep_grad(q, p, r, scale, temp)
-    b = loss_and_rep_grad(p, q, rinv, scale, temp)
+    a = loss_and_rep_grad(q, p, r, scale, temp, g_dtype=g_dtype)
+    b = loss_and_rep_grad(p, q, rinv, scale, temp, g_dtype=g_dtype)
     return dict(loss=0.5 * (a["loss"] + b["loss"]), dq=0.5 * (a["dq"] + b["dp"]), dp=0.5 * (a["dp"] + b["dq"]))
 
 
@@ -186,8 +195,9 @@ def _zeros_like_params(params):
 
 def round_to_bf16(a):
     """Round-to-nearest-even of every entry to the bf16 grid (8 significant bits),
-    returned as float64.  Models ONE thing: a workload that says its stored
-    representations are bf16 (Step 1 "collect and store all representations").
+    returned as float64.  Used for two stated storage precisions: representations
+    that a workload keeps in bf16 (Step 1 stores all representations), and the
+    coefficients g_ij of Eq. 5-6 when g_dtype="bf16" is asked for.
     Pinned against torch's bfloat16 cast in the tests."""
     x = np.ascontiguousarray(np.asarray(a, dtype=np.float64).astype(np.float32))
     u = x.view(np.uint32).astype(np.uint64)
