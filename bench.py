@@ -68,6 +68,16 @@ def side_workload(args, gc, synth, dev):
         ws = gc.alloc_workspace(gc.load().gc_ntxent_workspace_bytes(16384, 128), dev)
         step = lambda: gc.gc_ntxent_loss_and_grad_bf16(z, 0.07, ws)
         flops, what = 6.0 * 16384 * 16384 * 128, "NT-Xent loss+grad, 2N=16384 d=128 bf16 tau=0.07"
+    elif args.workload == "bidir":
+        import numpy as np
+        n, d = 8192, 768
+        r = torch.from_numpy(np.random.default_rng(7).permutation(n).astype(np.int32))
+        q, p, r = synth.dpr_batch(n, n, d, seed=8, positive_mix=0.5, pos_idx=r)
+        qd, pd, rd = q.to(dev), p.to(dev), r.to(dev)
+        ws = gc.alloc_workspace(gc.load().gc_bidirectional_workspace_bytes(n, d), dev)
+        res = gc.gc_bidirectional_loss_and_rep_grad_bf16(qd, pd, rd, 1.0, 1.0, ws)
+        step = lambda: gc.gc_bidirectional_loss_and_rep_grad_bf16(qd, pd, rd, 1.0, 1.0, ws, out=res)
+        flops, what = 2 * 6.0 * n * n * d, "symmetric loss+rep-grad, n=8192 d=768 bf16 (two directions)"
     else:
         xq, xp, r, params = synth.mlp_problem()
         xq, xp, r = xq.to(dev), xp.to(dev), r.to(dev)
@@ -98,7 +108,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5"],
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5", "bidir"],
                     help="config3 (default) is the headline workload; the others print a shorter timing line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise kernel 4 times that reads 1 GiB and writes 1 GiB (known HBM "

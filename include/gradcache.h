@@ -130,6 +130,23 @@ int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, 
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Symmetric in-batch-negative loss (anchors against targets and targets against
+ * anchors), one of the loss variations Step 2 of Sec. "Gradient Cache Technique"
+ * admits: n anchors, n targets, pos_idx a bijection of 0..n-1,
+ *   L = 1/2 [ L(F, G, r) + L(G, F, r^-1) ]   with L as in Eq. 1,
+ * dq = dL/df(s_i), dp = dL/dg(t_j) (Eq. 5 of one direction + Eq. 6 of the
+ * other, halved).  q, p [n,d] bf16, pos_idx [n] int32, loss [1], dq, dp [n,d]
+ * float, all device memory, all overwritten.  A pos_idx that is no bijection is
+ * reported like a positive out of range (loss = NaN, GC_ERR_POS_IDX from
+ * gc_check_async_error(workspace)).
+ * workspace: gc_bidirectional_workspace_bytes(n, d).
+ */
+size_t gc_bidirectional_workspace_bytes(int n, int d);
+int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const int32_t* pos_idx, int n, int d,
+                                            float scale, float temp, float* loss, float* dq, float* dp,
+                                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Stand-in encoder  y = GELU(x W1 + b1) W2 + b2  (exact erf GELU), bf16 storage,
  * fp32 accumulation.  W1[din,dh], b1[dh], W2[dh,dout], b2[dout], all device bf16.
  * din must be a multiple of 64, dh and dout multiples of 128 (else

@@ -20,7 +20,8 @@ GC_MASK_SELF = 1
 EXPORTS = [
     "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",
     "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
-    "gc_ntxent_loss_and_grad_bf16", "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
+    "gc_ntxent_loss_and_grad_bf16", "gc_bidirectional_workspace_bytes",
+    "gc_bidirectional_loss_and_rep_grad_bf16", "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
     "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
     "gc_profile_begin", "gc_profile_end",
 ]
@@ -70,6 +71,10 @@ def load():
     lib.gc_ntxent_workspace_bytes.argtypes = [ci, ci]
     lib.gc_ntxent_loss_and_grad_bf16.restype = ci
     lib.gc_ntxent_loss_and_grad_bf16.argtypes = [vp, ci, ci, cf, vp, vp, vp, sz, vp]
+    lib.gc_bidirectional_workspace_bytes.restype = sz
+    lib.gc_bidirectional_workspace_bytes.argtypes = [ci, ci]
+    lib.gc_bidirectional_loss_and_rep_grad_bf16.restype = ci
+    lib.gc_bidirectional_loss_and_rep_grad_bf16.argtypes = [vp, vp, vp, ci, ci, cf, cf, vp, vp, vp, vp, sz, vp]
     pp, pg = ctypes.POINTER(gc_mlp_params), ctypes.POINTER(gc_mlp_grads)
     lib.gc_mlp_workspace_bytes.restype = sz
     lib.gc_mlp_workspace_bytes.argtypes = [ci, pp]
@@ -215,6 +220,28 @@ def gc_ntxent_loss_and_grad_bf16(z, temp, workspace=None, stream=None):
     rc = lib.gc_ntxent_loss_and_grad_bf16(_ptr(z), n, d, temp, _ptr(loss), _ptr(dz), wp, wn, _stream(stream))
     _check(rc, "gc_ntxent_loss_and_grad_bf16")
     return loss, dz
+
+
+def gc_bidirectional_loss_and_rep_grad_bf16(q, p, pos_idx, scale=1.0, temp=1.0, workspace=None, out=None, stream=None):
+    """Symmetric loss; returns dict(loss, dq, dp).  `out` may carry the three buffers to reuse."""
+    lib = load()
+    _dev_contig(q, torch.bfloat16, "q")
+    _dev_contig(p, torch.bfloat16, "p")
+    _dev_contig(pos_idx, torch.int32, "pos_idx")
+    n, d = q.shape
+    if tuple(p.shape) != (n, d) or tuple(pos_idx.shape) != (n,):
+        raise GradCacheError(GC_ERR_SHAPE, "gc_bidirectional_loss_and_rep_grad_bf16")
+    if out is None:
+        out = dict(loss=torch.empty(1, dtype=torch.float32, device=q.device),
+                   dq=torch.empty(n, d, dtype=torch.float32, device=q.device),
+                   dp=torch.empty(n, d, dtype=torch.float32, device=q.device))
+    if workspace is None:
+        workspace = alloc_workspace(lib.gc_bidirectional_workspace_bytes(n, d), q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_bidirectional_loss_and_rep_grad_bf16(_ptr(q), _ptr(p), _ptr(pos_idx), n, d, scale, temp, _ptr(out["loss"]),
+                                                     _ptr(out["dq"]), _ptr(out["dp"]), wp, wn, _stream(stream))
+    _check(rc, "gc_bidirectional_loss_and_rep_grad_bf16")
+    return out
 
 
 # ----------------------------------------------------------------------------- stand-in encoder

@@ -147,6 +147,27 @@ __global__ void pair_index_kernel(int32_t* r, int n) {
   if (i < n) r[i] = i ^ 1;
 }
 
+// rinv[r[i]] = i; entries that no r[i] points at keep -1 (then r is no bijection, and the second direction of the
+// symmetric loss reports them as positives out of range)
+__global__ void fill_i32_kernel(int32_t* x, int n, int v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) x[i] = v;
+}
+__global__ void invert_perm_kernel(const int32_t* r, int32_t* rinv, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const int j = r[i];
+    if (j >= 0 && j < n) rinv[j] = i;
+  }
+}
+// loss = (l1 + l2) / 2; the error word of the first direction also takes the second's
+__global__ void combine_sym_kernel(const float* l1, const float* l2, float* loss, int* err1, const int* err2) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    if (loss) *loss = 0.5f * (*l1 + *l2);
+    if (*err2) *err1 = *err2;
+  }
+}
+
 }  // namespace gc
 
 using namespace gc;
@@ -284,6 +305,62 @@ int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, 
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
   a.pos_idx = r;
   return run_loss(a, pl);
+}
+
+// Workspace of the symmetric loss: [plan of direction 1][plan of direction 2][rinv][l1, l2][dq1][dp1][dq2][dp2]
+struct SymPlan { LossPlan pl; size_t off2, off_rinv, off_l, off_g, total; };
+static SymPlan make_sym_plan(int n, int d) {
+  SymPlan sp{};
+  sp.pl = make_loss_plan(n, n, d, GC_BF16, false);
+  size_t off = align_up(sp.pl.total, 256);
+  sp.off2 = off; off = align_up(off + sp.pl.total, 256);
+  sp.off_rinv = off; off = align_up(off + (size_t)n * 4, 256);
+  sp.off_l = off; off += 256;
+  sp.off_g = off; off += 4 * align_up((size_t)n * d * 4, 256);
+  sp.total = off;
+  return sp;
+}
+
+size_t gc_bidirectional_workspace_bytes(int n, int d) {
+  if (n < 1 || !shape_ok(n, n, d)) return 0;
+  return make_sym_plan(n, d).total;
+}
+
+int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const int32_t* pos_idx, int n, int d, float scale,
+                                            float temp, float* loss, float* dq, float* dp, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+  int rc = check_loss_args(GC_BF16, q, p, pos_idx, n, n, d, scale, temp, 0);
+  if (rc != GC_OK) return rc;
+  if (!loss || !dq || !dp) return GC_ERR_NULL;
+  const SymPlan sp = make_sym_plan(n, d);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sp.total) return GC_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* rinv = (int32_t*)(ws + sp.off_rinv);
+  float* l = (float*)(ws + sp.off_l);
+  const size_t gsz = align_up((size_t)n * d * 4, 256);
+  float* g[4];
+  for (int i = 0; i < 4; i++) g[i] = (float*)(ws + sp.off_g + i * gsz);
+  fill_i32_kernel<<<(n + 255) / 256, 256, 0, s>>>(rinv, n, -1);
+  invert_perm_kernel<<<(n + 255) / 256, 256, 0, s>>>(pos_idx, rinv, n);
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  LossArgs a{};
+  a.dt = GC_BF16; a.B = n; a.P = n; a.d = d; a.alpha = scale / temp; a.grad_mul = 0.5f; a.stream = s;
+  // direction 1: anchors against targets (Eq. 1); direction 2: the same with the two sides exchanged
+  a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = l; a.dq = g[0]; a.dp = g[1]; a.ws = ws;
+  rc = run_loss(a, sp.pl);
+  if (rc != GC_OK) return rc;
+  a.q = p; a.p = q; a.pos_idx = rinv; a.loss = l + 1; a.dq = g[2]; a.dp = g[3]; a.ws = ws + sp.off2;
+  rc = run_loss(a, sp.pl);
+  if (rc != GC_OK) return rc;
+  // dL/df = Eq. 5 of direction 1 + Eq. 6 of direction 2, dL/dg the other two; fixed order
+  const size_t ne = (size_t)n * d;
+  { const float* srcs[2] = {g[0], g[3]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
+    if (launch_partial_reduce(dq, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
+  { const float* srcs[2] = {g[1], g[2]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
+    if (launch_partial_reduce(dp, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
+  combine_sym_kernel<<<1, 64, 0, s>>>(l, l + 1, loss, (int*)(ws + sp.pl.off_err), (const int*)(ws + sp.off2 + sp.pl.off_err));
+  return hipGetLastError() == hipSuccess ? GC_OK : GC_ERR_HIP;
 }
 
 }  // extern "C"

@@ -68,6 +68,7 @@ struct LossArgs {
   float* lse;
   int32_t* argmax;
   float* dz;         // NT-Xent: dq + dp summed into one buffer (dq, dp then unused)
+  float grad_mul;    // extra factor on the gradients (0 = 1; the symmetric loss halves both terms)
   char* ws;
   hipStream_t stream;
 };

@@ -279,7 +279,7 @@ template <typename T>
 static hipError_t grad_generic_t(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
   const float* lse2 = (const float*)(ws + pl.off_lse2);
-  const float alpha2 = a.alpha * kLog2e, osc = a.alpha / (float)a.B;
+  const float alpha2 = a.alpha * kLog2e, osc = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
   const int ms = (a.flags & GC_MASK_SELF) ? 1 : 0;
   float* dq = a.dz ? (float*)(ws + pl.off_dq_part) : a.dq;
   float* dp = a.dz ? (float*)(ws + pl.off_dp_part) : a.dp;

@@ -1128,7 +1128,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   ga.Q = (const unsigned short*)a.q; ga.P = (const unsigned short*)a.p;
   ga.pos_pad = (const int32_t*)(ws + pl.off_pos_pad); ga.lse2 = (const float*)(ws + pl.off_lse2);
   ga.B = a.B; ga.Pn = a.P;
-  ga.alpha2 = a.alpha * kLog2e; ga.out_scale = a.alpha / (float)a.B;
+  ga.alpha2 = a.alpha * kLog2e; ga.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
   ga.mask_self = (a.flags & GC_MASK_SELF) ? 1 : 0;
   const bool want_q = a.dq || a.dz, want_p = a.dp || a.dz;
   const size_t nq = (size_t)a.B * a.d, np = (size_t)a.P * a.d;

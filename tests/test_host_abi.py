@@ -75,6 +75,18 @@ def test_argument_errors_are_raised_on_the_host():
     assert nt(fake, 15, 128, 0.1, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
     assert nt(fake, 16, 128, -1.0, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
     assert nt(fake, 16, 128, 0.1, fake, fake, fake, 8, None) == gc.GC_ERR_WORKSPACE
+    bd = lib.gc_bidirectional_loss_and_rep_grad_bf16
+    assert bd(fake, None, fake, 16, 128, 1.0, 1.0, fake, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_NULL
+    assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, None, fake, fake, 1 << 30, None) == gc.GC_ERR_NULL
+    assert bd(fake, fake, fake, 0, 128, 1.0, 1.0, fake, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
+    assert bd(fake, fake, fake, 16, 128, 1.0, 0.0, fake, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
+    assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, fake, fake, None, 1 << 30, None) == gc.GC_ERR_WORKSPACE
+    assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, fake, fake, fake, 64, None) == gc.GC_ERR_WORKSPACE
+    # four gradient buffers + two loss workspaces (split partials included): never the n x n scores
+    for n in (4096, 8192, 65536):
+        w = lib.gc_bidirectional_workspace_bytes(n, 768)
+        assert 4 * n * 768 * 4 < w < 16 * n * 768 * 4
+    assert lib.gc_bidirectional_workspace_bytes(0, 768) == 0
 
 
 def test_mlp_argument_errors_are_raised_on_the_host():
