@@ -195,15 +195,10 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
     __syncthreads();
     bf16x8 af[2][4], bfg[2][2];
     for (int kc = 0; kc < nk; kc++) {
-#ifndef GC_EXP_ST_NODMA
       if (kc + 1 < nk) prefetch(tile_row0, kc + 1, (kc + 1) & 1);
-#endif
       const int so = (kc & 1) * ST_STAGE_BYTES;
       __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the fragment reads with the MFMA stream
       auto load_frags = [&](int ks, int buf) __attribute__((always_inline)) {
-#ifdef GC_EXP_ST_NOLDSREAD
-        if (kc > 0) return;
-#endif
 #pragma unroll
         for (int mt = 0; mt < 4; mt++) af[buf][mt] = *(const bf16x8*)(a_base + so + mt * 32 * ST_ROWB + koff[ks]);
 #pragma unroll
@@ -218,17 +213,10 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 #pragma unroll
           for (int nt = 0; nt < 2; nt++) acc[mt][nt] = mfma32(af[ks & 1][mt], bfg[ks & 1][nt], acc[mt][nt]);
       }
-#ifndef GC_EXP_ST_NOWAIT
       wait_vmem<0>();   // this wave's part of the next stage has landed
-#endif
-#ifndef GC_EXP_ST_NOBAR
       __syncthreads();  // ... and everybody's; nobody still reads the stage that is overwritten next
-#endif
     }
 
-#ifdef GC_EXP_ST_NOEPI
-    if (alpha2 != 12345.f) { rl[0] += acc[0][0][0] + acc[1][1][3] + acc[2][0][5] + acc[3][1][7]; continue; }
-#endif
     // ---- tile epilogue: online softmax statistics, all in registers -----------------------------
     const int brow0 = b0 + wm * 128 + 4 * (lane >> 5);  // + mt*32 + 8*(r/4) + r%4
     const bool edge = (b0 + ST_TM > cend);
@@ -280,12 +268,6 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
     }
   }
 
-#if defined(GC_EXP_ST_NOWAIT)
-  wait_vmem<0>();
-#endif
-#ifdef GC_EXP_ST_NOEPI
-  if (alpha2 != 12345.f) return;
-#endif
   // ---- combine the two half-waves (same anchor column, different target rows) -------------------
 #pragma unroll
   for (int nt = 0; nt < 2; nt++) {
@@ -557,11 +539,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   u32x4 afr[C::KS];  // phase-1 A fragments of the tile being started (bf16x8 each)
   auto p1_load = [&](unsigned so, int ks0, int ks1) __attribute__((always_inline)) {
 #pragma unroll
-#ifndef GC_EXP_NOP1READ
     for (int ks = ks0; ks < ks1; ks++) afr[ks] = *(const u32x4*)(p1p[ks & 1] + so + 64 * ks);
-#else
-    for (int ks = ks0; ks < ks1; ks++) afr[ks] = __builtin_bit_cast(u32x4, ofrag[ks & 3][ks]);
-#endif
   };
   auto p1_mfma = [&](int ks0, int ks1) __attribute__((always_inline)) {
 #pragma unroll
@@ -592,13 +570,11 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   // next MFMA reads (TWO: they differ)
   auto spread = [&](auto wave_tag, auto sec_tag, auto idx_tag, auto two_tag, int t_pf, unsigned so_pf, u32x4& pin_a, u32x4& pin_b) __attribute__((always_inline)) {
     constexpr int WAVE = decltype(wave_tag)::value, SEC = decltype(sec_tag)::value, IDX = decltype(idx_tag)::value;
-#ifndef GC_EXP_NODMA
     if constexpr (WAVE >= 0) {
       static_for<NI>([&](auto k_tag) __attribute__((always_inline)) {
         if constexpr (slot_of(WAVE, decltype(k_tag)::value, SEC) == IDX) prefetch_piece(k_tag, two_tag, t_pf, so_pf, pin_a, pin_b);
       });
     }
-#endif
   };
   auto p1_mfma_spread = [&](auto wave_tag, auto sec_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
     constexpr int SEC = decltype(sec_tag)::value;
@@ -617,12 +593,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   auto p2_load = [&](unsigned so) __attribute__((always_inline)) {
 #pragma unroll
     for (int ct = 0; ct < C::CT; ct++) {
-#ifndef GC_EXP_NOTR
       s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2lo[ct & 1] + so + 64 * ct));
       s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2hi[ct & 1] + so + 64 * ct));
-#else
-      s16x4 lo = {(short)ct, 1, 2, (short)so}, hi = {4, 5, 6, (short)lane};
-#endif
       s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       bfr[ct] = __builtin_bit_cast(u32x4, bb);
     }
@@ -637,9 +609,6 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     });
   };
 
-#ifdef GC_EXP_TIMING
-  long long tacc[4] = {0, 0, 0, 0}, tq1 = 0;
-#endif
   bf16x4 gq = {0, 0, 0, 0};  // g of the tile whose scores were finished last (4 streamed rows of owner row a_q)
 
   // One pipeline iteration (see the header comment); so0 = ring offset of the stage of tile u.  STEADY:
@@ -657,54 +626,31 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     const bool p1 = STEADY || (u + 2 < nt);            // tile u+2: phase 1
     const bool pf = STEADY || (u >= 0 && u + 4 < nt);  // tile u+4: start its loads
     __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the LDS reads with the MFMA stream
-#ifdef GC_EXP_TIMING
-    const long long tq0 = clock64();
-#endif
     if (p1) {
       // tile u+2 has landed (in a steady iteration the loads of tile u+3 may still be in flight).  Its
       // fragment reads are issued ahead of the writes below, so they come back first.
       if (STEADY) wait_vmem<NI>(); else wait_vmem<0>();
-#ifdef GC_EXP_TIMING
-      tq1 = clock64();
-#endif
-#ifndef GC_EXP_WRFIRST
       p1_load(so2, 0, C::KS);
-#else
-      p1_load(so2, 0, 1);
-#endif
     }
     // the partial tile of the owner rows this wave finishes itself stays in registers (steady loop: the wave
     // index is a compile-time constant there); the other three go through LDS
     f32x4 own = {0.f, 0.f, 0.f, 0.f};
     if constexpr (STEADY) own = sacc[WAVE];
-#ifndef GC_EXP_NOX
     if (xw) {
 #pragma unroll
       for (int dst = 0; dst < 4; dst++)
         if (!(STEADY && dst == WAVE)) *(f32x4*)(xwp + PAR1 * 16384 + dst * 1024) = sacc[dst];
     }
-#endif
     if (gw) *(bf16x4*)(gwp + PAR0 * 2048) = gq;
-#ifdef GC_EXP_WRFIRST
-    __builtin_amdgcn_sched_barrier(0);
-    if (p1) p1_load(so2, 1, C::KS);
-#endif
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 0>{}, t_pf, so4);  // while the writes drain and the barrier gathers the waves
-#ifndef GC_EXP_NOBAR
     __syncthreads();
-#endif
     f32x4 xr[4];
     if (xw) {
-#ifndef GC_EXP_NOX
 #pragma unroll
       for (int src = 0; src < 4; src++) {
         if (STEADY && src == WAVE) xr[src] = own;
         else xr[src] = *(const f32x4*)(xrp + PAR1 * 16384 + src * 4096);
       }
-#else
-#pragma unroll
-      for (int src = 0; src < 4; src++) xr[src] = sacc[src];
-#endif
     }
     bf16x8 gf[2];
     if (gw) {
@@ -716,23 +662,11 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       lse_r = *(const f32x4*)(rip + so1);
       pos_r = *(const i32x4*)(rip + so1 + 64);
     }
-#ifdef GC_EXP_TRFIRST
-    if (gw) p2_load(so0);
-#endif
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
-#ifdef GC_EXP_TIMING
-    const long long tq2 = clock64();
-#endif
     if (gw) {
-#ifndef GC_EXP_TRFIRST
       p2_load(so0);
-#endif
       phase2(gf, wave_tag, t_pf, so4);
     }
-#ifdef GC_EXP_TIMING
-    const long long tq3 = clock64();
-    if (STEADY) { tacc[0] += tq1 - tq0; tacc[1] += tq2 - tq1; tacc[2] += tq3 - tq2; tacc[3] += 1; }
-#endif
     if (xw) {
       const f32x4 sv = ((xr[0] + xr[1]) + xr[2]) + xr[3];  // fixed order: bit-identical whichever wave sums
       const int b0 = sbeg + (u + 1) * GR_T + 4 * g16;      // first of this lane's 4 streamed rows
@@ -757,9 +691,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       }
       gq = __builtin_convertvector(gv, bf16x4);
     }
-#ifndef GC_EXP_NODMA
     if (!STEADY && pf) prefetch(u + 4, so4);  // in a steady iteration phase 2 has issued these loads
-#endif
   };
   // ---- prologue: start the first tiles, phase 1 of tile 0 ------------------------------------------------------
 #pragma unroll 1
@@ -797,14 +729,6 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         const int a = a0 + 32 * mt + 8 * (r >> 2) + 4 * h + (r & 3);
         if (a < No) out[(size_t)a * D + w * C::DS + 32 * ct + ln] = acc[mt][ct][r] * ga.out_scale;
       }
-#ifdef GC_EXP_TIMING
-  __threadfence();
-  __syncthreads();
-  if (oblk == 0 && split == 0 && lane == 0) {
-    long long* tp = (long long*)out + 4 * w;
-    for (int i = 0; i < 4; i++) tp[i] = tacc[i];
-  }
-#endif
 }
 
 
