@@ -120,21 +120,35 @@ def ntxent(z, temp, g_dtype=None):
 def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0, g_dtype=None):
     """Symmetric in-batch-negative loss: anchors against targets and targets
     against anchors (one of the loss variations Step 2 admits; the method only
-    needs dL/df(s_i) and dL/dg(t_j)).  B = P and r must be a bijection:
+    needs dL/df(s_i) and dL/dg(t_j)).  B = P = n and r must be a bijection:
       L = 1/2 [ L(F, G, r) + L(G, F, r^-1) ],
-    each term Eq. 1 with the roles of the two sides exchanged in the second.
-    Returns dict(loss, dq, dp): each gradient is the sum of Eq. 5 of one term
-    and Eq. 6 of the other, halved."""
+    each term Eq. 1, the second with the roles of the two sides exchanged.
+    Both terms are functions of the same scores s_ij: the first normalises
+    every row (Eq. 4), the second every column, and both have their positive at
+    (i, r_i).  So dL/ds_ij = g_ij / n with
+      g_ij = 1/2 (p^row_ij + p^col_ij) - [j == r_i],
+    and dL/df(s_i) = (alpha/n) sum_j g_ij g(t_j), dL/dg(t_j) = (alpha/n) sum_i g_ij f(s_i)
+    (Eq. 5 of one term plus Eq. 6 of the other, halved).
+    g_dtype="bf16" rounds g_ij before the two contractions, as in loss_and_rep_grad.
+    Returns dict(loss, dq, dp)."""
     q = _f64(q)
     p = _f64(p)
     r = np.asarray(pos_idx, dtype=np.int64)
     n = q.shape[0]
-    assert p.shape[0] == n and sorted(r.tolist()) == list(range(n))
-    rinv = np.empty(n, dtype=np.int64)
-    rinv[r] = np.arange(n)
-    a = loss_and_rep_grad(q, p, r, scale, temp, g_dtype=g_dtype)
-    b = loss_and_rep_grad(p, q, rinv, scale, temp, g_dtype=g_dtype)
-    return dict(loss=0.5 * (a["loss"] + b["loss"]), dq=0.5 * (a["dq"] + b["dp"]), dp=0.5 * (a["dp"] + b["dq"]))
+    assert p.shape == q.shape and sorted(r.tolist()) == list(range(n))
+    alpha = float(scale) / float(temp)
+    s = alpha * (q @ p.T)
+    pos = s[np.arange(n), r]
+    lse_row = loss_and_rep_grad(q, p, r, scale, temp)["lse"]          # over the targets, per anchor
+    m = s.max(axis=0)
+    lse_col = m + np.log(np.exp(s - m[None, :]).sum(axis=0))          # over the anchors, per target
+    loss = 0.5 * (np.sum(lse_row - pos) + np.sum(lse_col[r] - pos)) / n
+    g = 0.5 * (np.exp(s - lse_row[:, None]) + np.exp(s - lse_col[None, :]))
+    g[np.arange(n), r] -= 1.0
+    if g_dtype is not None:
+        assert g_dtype == "bf16"
+        g = round_to_bf16(g)
+    return dict(loss=float(loss), dq=(alpha / n) * (g @ p), dp=(alpha / n) * (g.T @ q))
 
 
 # ---------------------------------------------------------------------------
