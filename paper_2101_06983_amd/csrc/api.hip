@@ -113,11 +113,16 @@ bool prof_active() { return g_prof.on; }
 static int run_loss(const LossArgs& a, const LossPlan& pl) {
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
-  hipError_t e = pl.use_mfma ? launch_stats_mfma(a, pl) : launch_stats_generic(a, pl);
-  if (e != hipSuccess) return GC_ERR_HIP;
+  hipError_t e;
+  if (!a.lse2_t) {
+    e = pl.use_mfma ? launch_stats_mfma(a, pl) : launch_stats_generic(a, pl);
+    if (e != hipSuccess) return GC_ERR_HIP;
+  }
   prof_mark(call, 1, a.stream);
-  e = launch_stats_merge(a, pl);
-  if (e != hipSuccess) return GC_ERR_HIP;
+  if (!a.lse2_t) {
+    e = launch_stats_merge(a, pl);
+    if (e != hipSuccess) return GC_ERR_HIP;
+  }
   prof_mark(call, 2, a.stream);
   if (a.dq || a.dp || a.dz) {
     e = pl.use_mfma ? launch_grad_mfma(a, pl) : launch_grad_generic(a, pl);  // records mark 3 after its main kernel(s)
@@ -308,15 +313,18 @@ int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, 
 }
 
 // Workspace of the symmetric loss: [plan of direction 1][plan of direction 2][rinv][l1, l2][dq1][dp1][dq2][dp2]
+// Workspace of the symmetric loss: [loss workspace, direction 1][direction 2][r^-1][two losses][4 gradient buffers].
+// With the MFMA kernels one gradient pass serves both directions: the second workspace then holds statistics only
+// and there are no gradient buffers.
 struct SymPlan { LossPlan pl; size_t off2, off_rinv, off_l, off_g, total; };
 static SymPlan make_sym_plan(int n, int d) {
   SymPlan sp{};
   sp.pl = make_loss_plan(n, n, d, GC_BF16, false);
   size_t off = align_up(sp.pl.total, 256);
-  sp.off2 = off; off = align_up(off + sp.pl.total, 256);
+  sp.off2 = off; off = align_up(off + (sp.pl.use_mfma ? sp.pl.off_dq_part : sp.pl.total), 256);
   sp.off_rinv = off; off = align_up(off + (size_t)n * 4, 256);
   sp.off_l = off; off += 256;
-  sp.off_g = off; off += 4 * align_up((size_t)n * d * 4, 256);
+  sp.off_g = off; off += sp.pl.use_mfma ? 0 : 4 * align_up((size_t)n * d * 4, 256);
   sp.total = off;
   return sp;
 }
@@ -338,27 +346,43 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
   hipStream_t s = (hipStream_t)stream;
   int32_t* rinv = (int32_t*)(ws + sp.off_rinv);
   float* l = (float*)(ws + sp.off_l);
-  const size_t gsz = align_up((size_t)n * d * 4, 256);
-  float* g[4];
-  for (int i = 0; i < 4; i++) g[i] = (float*)(ws + sp.off_g + i * gsz);
   fill_i32_kernel<<<(n + 255) / 256, 256, 0, s>>>(rinv, n, -1);
   invert_perm_kernel<<<(n + 255) / 256, 256, 0, s>>>(pos_idx, rinv, n);
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
   LossArgs a{};
-  a.dt = GC_BF16; a.B = n; a.P = n; a.d = d; a.alpha = scale / temp; a.grad_mul = 0.5f; a.stream = s;
-  // direction 1: anchors against targets (Eq. 1); direction 2: the same with the two sides exchanged
-  a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = l; a.dq = g[0]; a.dp = g[1]; a.ws = ws;
-  rc = run_loss(a, sp.pl);
-  if (rc != GC_OK) return rc;
-  a.q = p; a.p = q; a.pos_idx = rinv; a.loss = l + 1; a.dq = g[2]; a.dp = g[3]; a.ws = ws + sp.off2;
-  rc = run_loss(a, sp.pl);
-  if (rc != GC_OK) return rc;
-  // dL/df = Eq. 5 of direction 1 + Eq. 6 of direction 2, dL/dg the other two; fixed order
-  const size_t ne = (size_t)n * d;
-  { const float* srcs[2] = {g[0], g[3]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
-    if (launch_partial_reduce(dq, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
-  { const float* srcs[2] = {g[1], g[2]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
-    if (launch_partial_reduce(dp, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
+  a.dt = GC_BF16; a.B = n; a.P = n; a.d = d; a.alpha = scale / temp; a.stream = s;
+  if (sp.pl.use_mfma) {
+    // statistics of both directions (Eq. 1 as it stands, then with the two sides exchanged) ...
+    a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = l; a.ws = ws;
+    rc = run_loss(a, sp.pl);
+    if (rc != GC_OK) return rc;
+    a.q = p; a.p = q; a.pos_idx = rinv; a.loss = l + 1; a.ws = ws + sp.off2;
+    rc = run_loss(a, sp.pl);
+    if (rc != GC_OK) return rc;
+    // ... and one gradient pass with the mean of the two softmaxes as coefficients
+    a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = nullptr; a.ws = ws; a.dq = dq; a.dp = dp;
+    a.lse2_t = (const float*)(ws + sp.off2 + sp.pl.off_lse2);
+    rc = run_loss(a, sp.pl);
+    if (rc != GC_OK) return rc;
+  } else {
+    const size_t gsz = align_up((size_t)n * d * 4, 256);
+    float* g[4];
+    for (int i = 0; i < 4; i++) g[i] = (float*)(ws + sp.off_g + i * gsz);
+    a.grad_mul = 0.5f;
+    // direction 1: anchors against targets (Eq. 1); direction 2: the same with the two sides exchanged
+    a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = l; a.dq = g[0]; a.dp = g[1]; a.ws = ws;
+    rc = run_loss(a, sp.pl);
+    if (rc != GC_OK) return rc;
+    a.q = p; a.p = q; a.pos_idx = rinv; a.loss = l + 1; a.dq = g[2]; a.dp = g[3]; a.ws = ws + sp.off2;
+    rc = run_loss(a, sp.pl);
+    if (rc != GC_OK) return rc;
+    // dL/df = Eq. 5 of direction 1 + Eq. 6 of direction 2, dL/dg the other two; fixed order
+    const size_t ne = (size_t)n * d;
+    { const float* srcs[2] = {g[0], g[3]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
+      if (launch_partial_reduce(dq, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
+    { const float* srcs[2] = {g[1], g[2]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
+      if (launch_partial_reduce(dp, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
+  }
   combine_sym_kernel<<<1, 64, 0, s>>>(l, l + 1, loss, (int*)(ws + sp.pl.off_err), (const int*)(ws + sp.off2 + sp.pl.off_err));
   return hipGetLastError() == hipSuccess ? GC_OK : GC_ERR_HIP;
 }

@@ -69,6 +69,9 @@ struct LossArgs {
   int32_t* argmax;
   float* dz;         // NT-Xent: dq + dp summed into one buffer (dq, dp then unused)
   float grad_mul;    // extra factor on the gradients (0 = 1; the symmetric loss halves both terms)
+  // symmetric loss in one gradient pass (MFMA kernels only): log2-domain log-sum-exp per target over the anchors,
+  // padded like the per-anchor one; with it set the statistics of this call are taken as already in `ws`
+  const float* lse2_t;
   char* ws;
   hipStream_t stream;
 };

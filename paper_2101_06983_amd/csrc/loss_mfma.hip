@@ -392,6 +392,7 @@ struct GradArgs {
   const unsigned short* P;
   const int32_t* pos_pad;   // pos_idx copied and padded with -1 to a multiple of 64 rows
   const float* lse2;        // log2-domain log-sum-exp per anchor, padded with +inf
+  const float* lse2_t;      // symmetric loss only: the same per target (over the anchors), padded alike
   int B, Pn;
   float alpha2, out_scale;
   int mask_self;
@@ -421,9 +422,16 @@ constexpr bool grad_offsets_fit() {  // voff[k] - 1024 (k % 4) must stay >= 0 fo
   return true;
 }
 
-template <int D, bool OWNER_IS_Q>
+// SYM: the symmetric loss 1/2 [L(F, G, r) + L(G, F, r^-1)].  Its coefficient matrix is
+//   g_ij = 1/2 (2^(t_ij - lse2[i]) + 2^(t_ij - lse2_t[j])) - [j = r_i]
+// (row softmax and column softmax of the same scores), and dQ = g P, dP = g^T Q as before: one walk per side,
+// in which the streamed rows always bring their statistic along.
+template <int D, bool OWNER_IS_Q, bool SYM>
 __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
   using C = GradCfg<D>;
+  constexpr bool STR_STATS = SYM || !OWNER_IS_Q;   // the streamed rows' statistics ride in the LDS stage
+  const float* lse_own = (SYM && !OWNER_IS_Q) ? ga.lse2_t : ga.lse2;
+  const float* lse_str = (SYM && OWNER_IS_Q) ? ga.lse2_t : ga.lse2;
   static_assert(grad_offsets_fit<D>(), "direct-to-LDS load offsets");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, ln = lane & 31;
   const int l16 = lane & 15, g16 = lane >> 4;
@@ -474,10 +482,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   // this wave finishes the scores of owner rows 16 w .. 16 w + 15; a lane holds streamed rows 4 * g16 + 0..3
   const int a_q = a0 + 16 * w + l16;
   float lse_a = 0.f; int r_a = -1;
-  if (OWNER_IS_Q) {
-    lse_a = ga.lse2[a_q];      // padded: +inf past the end, so g = 0 there
-    r_a = ga.pos_pad[a_q];
-  }
+  if (OWNER_IS_Q || SYM) lse_a = lse_own[a_q];   // padded: +inf past the end, so g = 0 there
+  if (OWNER_IS_Q) r_a = ga.pos_pad[a_q];
 
   // ---- direct-to-LDS loads of a streamed tile: slot q = it * 64 + lane -> (row, chunk) -------------------------
   auto slot_src = [&](int q, int max_row) __attribute__((always_inline)) -> unsigned {
@@ -489,17 +495,18 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   unsigned src_off[NT];  // full tile, with the instruction offset 1024 (it % 4) pre-subtracted
 #pragma unroll
   for (int it = 0; it < NT; it++) src_off[it] = slot_src(it * 64 + lane, GR_T - 1) - 1024u * (it & 3);
-  // row statistics of the streamed rows (dP role): lanes 0-3 load lse2[t0 + 4 l ..], lanes 4-7 pos_pad
-  const unsigned ri_off = (lane & 4) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 3) : 16u * (lane & 3);
-  constexpr int NI = OWNER_IS_Q ? NT : NT + 1;  // load instructions per tile
+  // row statistics of the streamed rows: lanes 0-3 load lse_str[t0 + 4 l ..], lanes 4-7 pos_pad (dP role; in
+  // the dQ role of the symmetric loss they load the same as lanes 0-3 and nobody reads it)
+  const unsigned ri_off = ((lane & 4) && !OWNER_IS_Q) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 3) : 16u * (lane & 3);
+  constexpr int NI = STR_STATS ? NT + 1 : NT;  // load instructions per tile
   // piece k (0 .. NI-1) of the loads of a full tile that starts at row t0, into the stage at byte offset so
   auto prefetch_piece = [&](auto k_tag, auto two_tag, int t0, unsigned so, u32x4& pin_a, u32x4& pin_b) __attribute__((always_inline)) {
     constexpr int K = decltype(k_tag)::value;
     constexpr bool TWO = decltype(two_tag)::value;
-    if constexpr (!OWNER_IS_Q && K == 0) {
-      dma_piece_pinned<0, true, TWO>(ga.lse2 + t0, ri_off, ring_m0 + so, pin_a, pin_b);
+    if constexpr (STR_STATS && K == 0) {
+      dma_piece_pinned<0, true, TWO>(lse_str + t0, ri_off, ring_m0 + so, pin_a, pin_b);
     } else {
-      constexpr int IT = OWNER_IS_Q ? K : K - 1;
+      constexpr int IT = STR_STATS ? K - 1 : K;
       dma_piece_pinned<1024 * (IT & 3), false, TWO>(R + (size_t)t0 * D, src_off[IT], ring_m0 + so + C::TOFF + 4096 * (IT >> 2), pin_a, pin_b);
     }
   };
@@ -507,8 +514,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     const int t0 = sbeg + u * GR_T;
     const unsigned short* tile = R + (size_t)t0 * D;  // wave-uniform
     const unsigned lds0 = ring_m0 + so + C::TOFF;
-    if (!OWNER_IS_Q) {
-      if (lane < 8) dma_piece<0>(ga.lse2 + t0, ri_off, ring_m0 + so);
+    if (STR_STATS) {
+      if (lane < 8) dma_piece<0>(lse_str + t0, ri_off, ring_m0 + so);
     }
     if (t0 + GR_T <= Nr) {
 #pragma unroll
@@ -658,9 +665,9 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       for (int mt = 0; mt < 2; mt++) gf[mt] = *(const bf16x8*)(grp + PAR0 * 2048 + mt * 1024);
     }
     f32x4 lse_r = {0.f, 0.f, 0.f, 0.f}; i32x4 pos_r = {0, 0, 0, 0};
-    if (!OWNER_IS_Q && xw) {  // row statistics of tile u+1 ride in its LDS stage
+    if (STR_STATS && xw) {  // row statistics of tile u+1 ride in its LDS stage
       lse_r = *(const f32x4*)(rip + so1);
-      pos_r = *(const i32x4*)(rip + so1 + 64);
+      if (!OWNER_IS_Q) pos_r = *(const i32x4*)(rip + so1 + 64);
     }
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
     if (gw) {
@@ -672,7 +679,14 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       const int b0 = sbeg + (u + 1) * GR_T + 4 * g16;      // first of this lane's 4 streamed rows
       f32x4 gv;
 #pragma unroll
-      for (int e = 0; e < 4; e++) gv[e] = fast_exp2(sv[e] * ga.alpha2 - (OWNER_IS_Q ? lse_a : lse_r[e]));  // softmax
+      for (int e = 0; e < 4; e++) {
+        if constexpr (SYM) {  // mean of the row softmax and the column softmax
+          const float t = sv[e] * ga.alpha2;
+          gv[e] = 0.5f * fast_exp2(t - lse_a) + 0.5f * fast_exp2(t - lse_r[e]);
+        } else {
+          gv[e] = fast_exp2(sv[e] * ga.alpha2 - (OWNER_IS_Q ? lse_a : lse_r[e]));  // softmax
+        }
+      }
       // the rest touches few tiles and is decided per wave: -1 at the positive (j == r_i), zeros for rows
       // past the end of the split and on the diagonal (i == j)
       bool hit_any;
@@ -762,9 +776,12 @@ __device__ __forceinline__ void dma_lanes16(const void* gbase, unsigned voff, un
                : "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase) : "memory");
 }
 
-template <bool OWNER_IS_Q>
+template <bool OWNER_IS_Q, bool SYM>
 __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
   constexpr int D = 128;
+  constexpr bool STR_STATS = SYM || !OWNER_IS_Q;   // as in grad_body
+  const float* lse_own = (SYM && !OWNER_IS_Q) ? ga.lse2_t : ga.lse2;
+  const float* lse_str = (SYM && OWNER_IS_Q) ? ga.lse2_t : ga.lse2;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, ln = lane & 31;
   const int l16 = lane & 15, g16 = lane >> 4;
   const unsigned short* O = OWNER_IS_Q ? ga.Q : ga.P;
@@ -788,7 +805,8 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
 #pragma unroll
     for (int ks = 0; ks < 8; ks++) ofrag[n][ks] = *(const bf16x8*)(O + (size_t)row * D + 16 * ks + 8 * h);
     lse_o[n] = INFINITY; r_o[n] = -1;            // a row past the end: g = 0
-    if (OWNER_IS_Q && own_idx[n] < No) { lse_o[n] = ga.lse2[own_idx[n]]; r_o[n] = ga.pos_pad[own_idx[n]]; }
+    if ((OWNER_IS_Q || SYM) && own_idx[n] < No) lse_o[n] = lse_own[own_idx[n]];
+    if (OWNER_IS_Q && own_idx[n] < No) r_o[n] = ga.pos_pad[own_idx[n]];
   }
   // The compiler's own loads end here: it does not see the direct-to-LDS loads below, and a wait of its own for
   // these registers inside the loop would also wait for those.  An empty statement that "uses" every loaded register.
@@ -806,13 +824,13 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
     return (unsigned)(min(row, max_row) * (D * 2) + c * 16);
   };
   const unsigned voff_full[2] = {src_of(2 * w, G1_T - 1), src_of(2 * w + 1, G1_T - 1)};
-  const unsigned stat_off = (lane & 8) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 7) : 16u * (lane & 7);
-  const bool stat_wave = !OWNER_IS_Q && wu == 0;
+  const unsigned stat_off = ((lane & 8) && !OWNER_IS_Q) ? (unsigned)((const char*)ga.pos_pad - (const char*)ga.lse2) + 16u * (lane & 7) : 16u * (lane & 7);
+  const bool stat_wave = STR_STATS && wu == 0;
   auto prefetch = [&](int u) __attribute__((always_inline)) {   // tile u -> stage u % 4
     const int t0 = sbeg + u * G1_T;
     const unsigned st = lds0 + (u & (G1_STAGES - 1)) * G1_STAGE;
     const unsigned short* tile = R + (size_t)t0 * D;
-    if (stat_wave) dma_lanes16(ga.lse2 + t0, stat_off, st);
+    if (stat_wave) dma_lanes16(lse_str + t0, stat_off, st);
     if (t0 + G1_T <= Nr) {
       dma_group<1>(tile, &voff_full[0], st + G1_STAT + (2 * wu) * 1024);
       dma_group<1>(tile, &voff_full[1], st + G1_STAT + (2 * wu + 1) * 1024);
@@ -885,11 +903,11 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
     // the order in which the rounds below consume them (LDS returns reads in order, and the 24 reads of the
     // four waves keep the LDS busy for most of an iteration: the first MFMAs must not wait for the last read)
     f32x4 lse_r[4]; i32x4 pos_r[4];
-    if (!OWNER_IS_Q && sm) {
+    if (STR_STATS && sm) {
 #pragma unroll
       for (int j = 0; j < 4; j++) {
         lse_r[j] = *(const f32x4*)(st_sm + (8 * j + 4 * h) * 4);
-        pos_r[j] = *(const i32x4*)(st_sm + 128 + (8 * j + 4 * h) * 4);
+        if (!OWNER_IS_Q) pos_r[j] = *(const i32x4*)(st_sm + 128 + (8 * j + 4 * h) * 4);
       }
     }
     bf16x8 pfr[8];
@@ -931,8 +949,14 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
       if (sm) {
 #pragma unroll
         for (int n = 0; n < 2; n++) {
-          const float l = OWNER_IS_Q ? lse_o[n] : lse_r[i >> 2][i & 3];
-          float e = fast_exp2(sacc[PT ^ 1][n][i] * ga.alpha2 - l);
+          float e;
+          if constexpr (SYM) {  // mean of the row softmax and the column softmax
+            const float t = sacc[PT ^ 1][n][i] * ga.alpha2;
+            e = 0.5f * fast_exp2(t - lse_o[n]) + 0.5f * fast_exp2(t - lse_r[i >> 2][i & 3]);
+          } else {
+            const float l = OWNER_IS_Q ? lse_o[n] : lse_r[i >> 2][i & 3];
+            e = fast_exp2(sacc[PT ^ 1][n][i] * ga.alpha2 - l);
+          }
           // an empty statement that "uses" the value: it keeps the arithmetic inside this round (pure
           // arithmetic would otherwise be moved behind all the MFMAs and run exposed)
           if constexpr (STEADY) asm volatile("" : "+v"(e));
@@ -1012,37 +1036,53 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
   }
 }
 
+template <bool SYM>
 __global__ void __launch_bounds__(256) grad128_kernel(GradArgs ga) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
   const int nQ = ga.obQ * ga.nsq;
   const int id = xcd_task_id();
   if (id < nQ) {
-    grad128_body<true>(ga, id % ga.obQ, id / ga.obQ, gsmem);
+    grad128_body<true, SYM>(ga, id % ga.obQ, id / ga.obQ, gsmem);
   } else {
     const int t = id - nQ;
-    grad128_body<false>(ga, t % ga.obP, t / ga.obP, gsmem);
+    grad128_body<false, SYM>(ga, t % ga.obP, t / ga.obP, gsmem);
   }
 }
 
-template <int D>
+template <int D, bool SYM>
 __global__ void __launch_bounds__(256) grad_mfma_kernel(GradArgs ga) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
   const int nQ = ga.obQ * ga.nsq;
   const int id = xcd_task_id();
   if (id < nQ) {
-    grad_body<D, true>(ga, id % ga.obQ, id / ga.obQ, gsmem);
+    grad_body<D, true, SYM>(ga, id % ga.obQ, id / ga.obQ, gsmem);
   } else {
     const int t = id - nQ;
-    grad_body<D, false>(ga, t % ga.obP, t / ga.obP, gsmem);
+    grad_body<D, false, SYM>(ga, t % ga.obP, t / ga.obP, gsmem);
   }
 }
 
+template <int D, bool SYM>
+static hipError_t grad_mfma_launch_as(const GradArgs& ga, int nwg, hipStream_t stream) {
+  const int smem = GradCfg<D>::SMEM;
+  hipError_t e = hipFuncSetAttribute((const void*)grad_mfma_kernel<D, SYM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (e != hipSuccess) return e;
+  grad_mfma_kernel<D, SYM><<<nwg, 256, smem, stream>>>(ga);
+  return hipGetLastError();
+}
 template <int D>
 static hipError_t grad_mfma_launch(const GradArgs& ga, int nwg, hipStream_t stream) {
-  const int smem = GradCfg<D>::SMEM;
-  hipError_t e = hipFuncSetAttribute((const void*)grad_mfma_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (e != hipSuccess) return e;
-  grad_mfma_kernel<D><<<nwg, 256, smem, stream>>>(ga);
+  return ga.lse2_t ? grad_mfma_launch_as<D, true>(ga, nwg, stream) : grad_mfma_launch_as<D, false>(ga, nwg, stream);
+}
+template <bool SYM>
+static hipError_t grad128_launch(const GradArgs& ga, int nwg, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)grad128_kernel<SYM>, hipFuncAttributeMaxDynamicSharedMemorySize, G1_SMEM);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  grad128_kernel<SYM><<<nwg, 256, G1_SMEM, stream>>>(ga);
   return hipGetLastError();
 }
 
@@ -1051,6 +1091,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   GradArgs ga{};
   ga.Q = (const unsigned short*)a.q; ga.P = (const unsigned short*)a.p;
   ga.pos_pad = (const int32_t*)(ws + pl.off_pos_pad); ga.lse2 = (const float*)(ws + pl.off_lse2);
+  ga.lse2_t = a.lse2_t;
   ga.B = a.B; ga.Pn = a.P;
   ga.alpha2 = a.alpha * kLog2e; ga.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
   ga.mask_self = (a.flags & GC_MASK_SELF) ? 1 : 0;
@@ -1066,17 +1107,7 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   if (nwg == 0) { prof_mark_grad_kernel_done(a.stream); return hipSuccess; }
   hipError_t e;
   switch (a.d) {
-    case 128: {
-      static bool attr_set = false;
-      if (!attr_set) {
-        e = hipFuncSetAttribute((const void*)grad128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, G1_SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-      }
-      grad128_kernel<<<nwg, 256, G1_SMEM, a.stream>>>(ga);
-      e = hipGetLastError();
-      break;
-    }
+    case 128: e = ga.lse2_t ? grad128_launch<true>(ga, nwg, a.stream) : grad128_launch<false>(ga, nwg, a.stream); break;
     case 256: e = grad_mfma_launch<256>(ga, nwg, a.stream); break;
     case 384: e = grad_mfma_launch<384>(ga, nwg, a.stream); break;
     case 512: e = grad_mfma_launch<512>(ga, nwg, a.stream); break;

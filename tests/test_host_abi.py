@@ -82,10 +82,11 @@ def test_argument_errors_are_raised_on_the_host():
     assert bd(fake, fake, fake, 16, 128, 1.0, 0.0, fake, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
     assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, fake, fake, None, 1 << 30, None) == gc.GC_ERR_WORKSPACE
     assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, fake, fake, fake, 64, None) == gc.GC_ERR_WORKSPACE
-    # four gradient buffers + two loss workspaces (split partials included): never the n x n scores
+    # loss workspaces (split partials included; four gradient buffers for widths the MFMA kernels do not take):
+    # never the n x n scores
     for n in (4096, 8192, 65536):
-        w = lib.gc_bidirectional_workspace_bytes(n, 768)
-        assert 4 * n * 768 * 4 < w < 16 * n * 768 * 4
+        assert 0 < lib.gc_bidirectional_workspace_bytes(n, 768) < 16 * n * 768 * 4
+        assert 4 * n * 96 * 4 < lib.gc_bidirectional_workspace_bytes(n, 96) < 16 * n * 96 * 4
     assert lib.gc_bidirectional_workspace_bytes(0, 768) == 0
 
 
