@@ -110,7 +110,10 @@ static void prof_mark(int call, int mark, hipStream_t s) {
 void prof_mark_grad_kernel_done(hipStream_t s) { prof_mark(g_prof.calls, 3, s); }
 bool prof_active() { return g_prof.on; }
 
-static int run_loss(const LossArgs& a, const LossPlan& pl) {
+static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
+  LossArgs a = a_in;
+  // does the gradient pass of this call end in a sum of split partials (launch_grad_mfma)?
+  a.loss_with_partials = pl.use_mfma && !a.lse2_t && (a.dz || (a.dq && pl.nsq > 1) || (a.dp && pl.nsp > 1));
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
   hipError_t e;

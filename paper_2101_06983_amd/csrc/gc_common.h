@@ -72,6 +72,9 @@ struct LossArgs {
   // symmetric loss in one gradient pass (MFMA kernels only): log2-domain log-sum-exp per target over the anchors,
   // padded like the per-anchor one; with it set the statistics of this call are taken as already in `ws`
   const float* lse2_t;
+  // set by run_loss when the gradient pass ends in a sum of split partials: that launch then also sums the row
+  // losses (one launch less); the statistics merge leaves the sum to it
+  bool loss_with_partials;
   char* ws;
   hipStream_t stream;
 };
@@ -84,7 +87,9 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl);
 void prof_mark_grad_kernel_done(hipStream_t s);  // measurement aid: event after the main gradient kernel(s)
 bool prof_active();  // the measurement events of the loss path are being recorded
+// loss_of / pl: also carry the sum of the row losses of that call (see LossArgs::loss_with_partials)
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
-                                 int nsrc, size_t n, hipStream_t stream);
+                                 int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of = nullptr,
+                                 const LossPlan* pl = nullptr);
 
 }  // namespace gc

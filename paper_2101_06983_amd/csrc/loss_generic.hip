@@ -139,28 +139,62 @@ __global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restric
   if (argmax_out) argmax_out[i] = bi;
 }
 
-// loss = (1/B) sum_i rowloss_i in a fixed order (single workgroup); raises the error word when a
-// row was flagged (NaN marker) because its pos_idx was out of range.
-__global__ void __launch_bounds__(1024) loss_reduce_kernel(const float* __restrict__ rowloss, const int32_t* __restrict__ pos_idx,
-                                                          int B, int P, float* __restrict__ loss, int* __restrict__ err) {
-  __shared__ float red[1024];
-  __shared__ int bad[1024];
-  float s = 0.f; int b = 0;
-  for (int i = threadIdx.x; i < B; i += 1024) {
-    s += rowloss[i];
-    int r = pos_idx[i];
-    b |= (r < 0 || r >= P);
+// loss = (1/B) sum_i rowloss_i by one workgroup; raises the error word when a row was flagged because its
+// pos_idx was out of range.  The order is fixed and does not depend on the size of the workgroup: 1024 strided
+// partial sums, then a binary tree over them (so the value has the same bits whichever kernel carries the sum).
+struct LossSum {
+  const float* rowloss;      // nullptr: nothing to do
+  const int32_t* pos_idx;
+  int B, P;
+  float* loss;               // may be nullptr
+  int* err;
+};
+template <int NT>  // threads of the workgroup
+__device__ __forceinline__ void loss_sum_block(const LossSum& ls, float* red /* [1024] in LDS */) {
+  constexpr int SL = 1024 / NT;   // partial sums per thread: slots threadIdx.x + NT * j
+  float s[SL];
+  int b = 0;
+#pragma unroll
+  for (int j = 0; j < SL; j++) s[j] = 0.f;
+  // rows i0 + slot, i0 = 0, 1024, ...: the loads of four such steps are issued together, then summed in order
+  for (int i0 = 0; i0 < ls.B; i0 += 4096) {
+    float v[4][SL];
+    int r[4][SL];
+#pragma unroll
+    for (int k = 0; k < 4; k++)
+#pragma unroll
+      for (int j = 0; j < SL; j++) {
+        const int i = i0 + 1024 * k + (int)threadIdx.x + NT * j;
+        const int ic = min(i, ls.B - 1);
+        v[k][j] = ls.rowloss[ic];
+        r[k][j] = ls.pos_idx[ic];
+      }
+#pragma unroll
+    for (int k = 0; k < 4; k++)
+#pragma unroll
+      for (int j = 0; j < SL; j++) {
+        const int i = i0 + 1024 * k + (int)threadIdx.x + NT * j;
+        if (i < ls.B) {
+          s[j] += v[k][j];
+          b |= (r[k][j] < 0 || r[k][j] >= ls.P);
+        }
+      }
   }
-  red[threadIdx.x] = s; bad[threadIdx.x] = b;
-  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < SL; j++) red[threadIdx.x + NT * j] = s[j];
+  const int bad = __syncthreads_or(b);
   for (int w = 512; w > 0; w >>= 1) {
-    if ((int)threadIdx.x < w) { red[threadIdx.x] += red[threadIdx.x + w]; bad[threadIdx.x] |= bad[threadIdx.x + w]; }
+    for (int x = threadIdx.x; x < w; x += NT) red[x] += red[x + w];
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    if (loss) *loss = bad[0] ? NAN : red[0] / (float)B;
-    *err = bad[0] ? 1 : 0;
+    if (ls.loss) *ls.loss = bad ? NAN : red[0] / (float)ls.B;
+    *ls.err = bad ? 1 : 0;
   }
+}
+__global__ void __launch_bounds__(1024) loss_reduce_kernel(LossSum ls) {
+  __shared__ float red[1024];
+  loss_sum_block<1024>(ls, red);
 }
 
 // Gradient pass, general form.  owner = the matrix whose gradient rows this workgroup owns
@@ -213,8 +247,15 @@ struct ReduceSrc {
   size_t stride[4];
   int nsrc;
 };
-__global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__ out, ReduceSrc rs, size_t n4) {
-  size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+// With a loss sum attached the grid has one more workgroup, the first (so that it runs beside the others), which carries it (it has nothing to do with
+// the partial sums; it only saves a launch on the path that needs both).
+__global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__ out, ReduceSrc rs, size_t n4, LossSum ls) {
+  __shared__ float red[1024];
+  if (ls.rowloss && blockIdx.x == 0) {
+    loss_sum_block<256>(ls, red);
+    return;
+  }
+  size_t e = (size_t)(blockIdx.x - (ls.rowloss ? 1 : 0)) * blockDim.x + threadIdx.x;
   if (e >= n4) return;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < rs.nsrc; s++)
@@ -230,13 +271,23 @@ __global__ void __launch_bounds__(256) partial_reduce_tail_kernel(float* __restr
   out[e] = acc;
 }
 
+static LossSum loss_sum_of(const LossArgs& a, const LossPlan& pl) {
+  LossSum ls{};
+  ls.rowloss = (const float*)(a.ws + pl.off_rowloss); ls.pos_idx = a.pos_idx; ls.B = a.B; ls.P = a.P;
+  ls.loss = a.loss; ls.err = (int*)(a.ws + pl.off_err);
+  return ls;
+}
+
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
-                                 int nsrc, size_t n, hipStream_t stream) {
+                                 int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of, const LossPlan* pl) {
   ReduceSrc rs{};
   rs.nsrc = nsrc;
   for (int s = 0; s < nsrc; s++) { rs.ptr[s] = srcs[s]; rs.count[s] = counts[s]; rs.stride[s] = strides[s]; }
+  LossSum ls{};
+  if (loss_of) ls = loss_sum_of(*loss_of, *pl);
   size_t n4 = n / 4;
-  if (n4) partial_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256)), 256, 0, stream>>>(out, rs, n4);
+  if (n4 || loss_of)
+    partial_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256 + (loss_of ? 1 : 0))), 256, 0, stream>>>(out, rs, n4, ls);
   if (n4 * 4 < n) partial_reduce_tail_kernel<<<1, 256, 0, stream>>>(out, rs, n4 * 4, n);
   return hipGetLastError();
 }
@@ -270,8 +321,8 @@ hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
   else if (pl.stat_splits <= 4) merge(std::integral_constant<int, 4>{});
   else if (pl.stat_splits <= 16) merge(std::integral_constant<int, 16>{});
   else merge(std::integral_constant<int, 64>{});
-  loss_reduce_kernel<<<1, 1024, 0, a.stream>>>((const float*)(ws + pl.off_rowloss), a.pos_idx, a.B, a.P, a.loss,
-                                               (int*)(ws + pl.off_err));
+  // the sum of the row losses: by a launch of its own, unless a sum of gradient partials follows that carries it
+  if (!a.loss_with_partials) loss_reduce_kernel<<<1, 1024, 0, a.stream>>>(loss_sum_of(a, pl));
   return hipGetLastError();
 }
 

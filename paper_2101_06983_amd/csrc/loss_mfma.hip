@@ -1117,21 +1117,23 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   }
   if (e != hipSuccess) return e;
   prof_mark_grad_kernel_done(a.stream);
-  // fixed-order sums of the split partials
+  // fixed-order sums of the split partials; the first of these launches also sums the row losses if asked to
+  const LossArgs* loss_of = a.loss_with_partials ? &a : nullptr;
   if (a.dz) {
     const float* srcs[2] = {ga.dq_out, ga.dp_out};
     int counts[2] = {pl.nsq, pl.nsp};
     size_t strides[2] = {nq, np};
-    return launch_partial_reduce(a.dz, srcs, counts, strides, 2, nq, a.stream);
+    return launch_partial_reduce(a.dz, srcs, counts, strides, 2, nq, a.stream, loss_of, &pl);
   }
   if (want_q && !q_direct) {
     const float* srcs[1] = {ga.dq_out}; int counts[1] = {pl.nsq}; size_t strides[1] = {nq};
-    e = launch_partial_reduce(a.dq, srcs, counts, strides, 1, nq, a.stream);
+    e = launch_partial_reduce(a.dq, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl);
     if (e != hipSuccess) return e;
+    loss_of = nullptr;
   }
   if (want_p && !p_direct) {
     const float* srcs[1] = {ga.dp_out}; int counts[1] = {pl.nsp}; size_t strides[1] = {np};
-    e = launch_partial_reduce(a.dp, srcs, counts, strides, 1, np, a.stream);
+    e = launch_partial_reduce(a.dp, srcs, counts, strides, 1, np, a.stream, loss_of, &pl);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
