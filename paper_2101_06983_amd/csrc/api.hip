@@ -25,7 +25,9 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
     // gradient pass: one workgroup per CU, equal streamed length for both roles
     const int own = (d == 128) ? 256 : 64;   // owner rows per workgroup of the gradient kernel for this width
     const long long obQ = ceil_div(B, own), obP = ceil_div(P, own);
-    const long long W = obQ * P + obP * B;
+    // NT-Xent on these kernels is one walk (the score matrix is symmetric: see launch_grad_mfma)
+    pl.one_walk = ntxent ? 1 : 0;
+    const long long W = pl.one_walk ? obQ * P : obQ * P + obP * B;
     long long L = (W + kNumCU - 1) / kNumCU;
     if (L < 256) L = 256;
     L = (L + 31) / 32 * 32;
@@ -38,6 +40,7 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
     };
     split_of(P, pl.nsq, pl.q_stream_len);
     split_of(B, pl.nsp, pl.p_stream_len);
+    if (pl.one_walk) { pl.nsp = 1; pl.p_stream_len = B; }
   } else {
     const int blocks = ceil_div(B, 16), tiles = ceil_div(P, 16);
     int splits = ceil_div(4 * kNumCU, blocks);
@@ -62,7 +65,7 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   pl.off_pos_pad = take((size_t)pl.b_pad * 4);
   pl.off_rowloss = take((size_t)B * 4);
   pl.off_dq_part = take((pl.nsq > 1 || ntxent) ? (size_t)pl.nsq * B * d * 4 : 0);
-  pl.off_dp_part = take((pl.nsp > 1 || ntxent) ? (size_t)pl.nsp * P * d * 4 : 0);
+  pl.off_dp_part = take(((pl.nsp > 1 || ntxent) && !pl.one_walk) ? (size_t)pl.nsp * P * d * 4 : 0);
   pl.off_pos_idx = take(ntxent ? (size_t)B * 4 : 0);
   pl.total = off;
   return pl;
@@ -113,7 +116,8 @@ bool prof_active() { return g_prof.on; }
 static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   LossArgs a = a_in;
   // does the gradient pass of this call end in a sum of split partials (launch_grad_mfma)?
-  a.loss_with_partials = pl.use_mfma && !a.lse2_t && (a.dz || (a.dq && pl.nsq > 1) || (a.dp && pl.nsp > 1));
+  a.loss_with_partials = pl.use_mfma && !a.lse2_t &&
+                         (a.dz ? (!pl.one_walk || pl.nsq > 1) : ((a.dq && pl.nsq > 1) || (a.dp && pl.nsp > 1)));
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
   hipError_t e;
@@ -315,7 +319,6 @@ int gc_ntxent_loss_and_grad_bf16(const void* z, int n_views, int d, float temp, 
   return run_loss(a, pl);
 }
 
-// Workspace of the symmetric loss: [plan of direction 1][plan of direction 2][rinv][l1, l2][dq1][dp1][dq2][dp2]
 // Workspace of the symmetric loss: [loss workspace, direction 1][direction 2][r^-1][two losses][4 gradient buffers].
 // With the MFMA kernels one gradient pass serves both directions: the second workspace then holds statistics only
 // and there are no gradient buffers.

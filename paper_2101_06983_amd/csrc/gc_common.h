@@ -43,6 +43,7 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 // ---------------------------------------------------------------------------
 struct LossPlan {
   int use_mfma;          // 1: bf16 MFMA kernels, 0: general fp32-FMA kernels
+  int one_walk;          // NT-Xent on the MFMA kernels: dz from a single walk (no dP role, no dP partials)
   int stat_splits;       // column (target) ranges of the statistics pass
   int stat_cols_per_split;
   int nsq, nsp;          // stream splits of the dQ-role / dP-role workgroups of the gradient pass

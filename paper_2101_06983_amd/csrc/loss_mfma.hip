@@ -1095,13 +1095,18 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   ga.B = a.B; ga.Pn = a.P;
   ga.alpha2 = a.alpha * kLog2e; ga.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
   ga.mask_self = (a.flags & GC_MASK_SELF) ? 1 : 0;
-  const bool want_q = a.dq || a.dz, want_p = a.dp || a.dz;
+  // NT-Xent in one walk: q = p = z, so the score matrix is symmetric, target j's log-sum-exp is anchor j's, and
+  //   dz_i = (alpha/n) sum_j (g_ij + g_ji) z_j,   g_ij + g_ji = 2^(t_ij - lse2_i) + 2^(t_ij - lse2_j) - 2 [j = pair(i)]:
+  // twice the coefficient of the symmetric loss with both statistics taken from the one array.  Only the dQ role runs.
+  const bool one_walk = pl.one_walk && a.dz;
+  if (one_walk) { ga.lse2_t = ga.lse2; ga.out_scale *= 2.f; }
+  const bool want_q = a.dq || a.dz, want_p = (a.dp || a.dz) && !one_walk;
   const size_t nq = (size_t)a.B * a.d, np = (size_t)a.P * a.d;
   const int own = (a.d == 128) ? G1_OWN : GR_OWN;   // owner rows per workgroup
   ga.obQ = want_q ? (a.B + own - 1) / own : 0; ga.nsq = pl.nsq; ga.q_stream_len = pl.q_stream_len;
   ga.obP = want_p ? (a.P + own - 1) / own : 0; ga.nsp = pl.nsp; ga.p_stream_len = pl.p_stream_len;
-  const bool q_direct = (pl.nsq == 1 && !a.dz), p_direct = (pl.nsp == 1 && !a.dz);
-  ga.dq_out = q_direct ? a.dq : (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
+  const bool q_direct = (pl.nsq == 1 && (!a.dz || one_walk)), p_direct = (pl.nsp == 1 && !a.dz);
+  ga.dq_out = q_direct ? (one_walk ? a.dz : a.dq) : (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
   ga.dp_out = p_direct ? a.dp : (float*)(ws + pl.off_dp_part); ga.dp_split_stride = np;
   const int nwg = ga.obQ * ga.nsq + ga.obP * ga.nsp;
   if (nwg == 0) { prof_mark_grad_kernel_done(a.stream); return hipSuccess; }
@@ -1119,6 +1124,11 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   prof_mark_grad_kernel_done(a.stream);
   // fixed-order sums of the split partials; the first of these launches also sums the row losses if asked to
   const LossArgs* loss_of = a.loss_with_partials ? &a : nullptr;
+  if (one_walk) {
+    if (q_direct) return hipSuccess;
+    const float* srcs[1] = {ga.dq_out}; int counts[1] = {pl.nsq}; size_t strides[1] = {nq};
+    return launch_partial_reduce(a.dz, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl);
+  }
   if (a.dz) {
     const float* srcs[2] = {ga.dq_out, ga.dp_out};
     int counts[2] = {pl.nsq, pl.nsp};
