@@ -127,11 +127,12 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 
   // ---- direct global->LDS loads: wave w fills rows 64 w .. 64 w + 63 of a stage (waves 0-3 the target
   // rows, waves 4-7 the anchor rows), 8 instructions of 8 rows x 8 chunks each -------------------------
-  const bool loads_q = wave >= 4;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // as a scalar: what follows from it stays uniform
+  const bool loads_q = wave_u >= 4;
   const unsigned short* lmat = loads_q ? Q : Pm;
   const int lrows = loads_q ? B : P;
-  const int lrow_in = (wave & 3) * 64 + (lane >> 3);  // + 8 j: row inside the 256-row tile
-  const unsigned stage_m0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)smem_b + wave * 64 * ST_ROWB);
+  const int lrow_in = (wave_u & 3) * 64 + (lane >> 3);  // + 8 j: row inside the 256-row tile
+  const unsigned stage_m0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)smem_b + wave_u * 64 * ST_ROWB);
   auto src_of = [&](int j, int tile_row0, bool clamp) -> unsigned {  // byte offset from the tile's first row, chunk kc = 0
     int r = lrow_in + 8 * j;
     const int c = (lane & 7) ^ ((r >> 1) & 7);
@@ -179,6 +180,10 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
     r_of[nt] = (a_col[nt] < B) ? pos_idx[a_col[nt]] : -1;
   }
 
+  // The k-chunks of all the tiles of this workgroup form one sequence of steps; step st lives in stage st & 1 and
+  // its loads are issued one step ahead inside a tile.  (Loading the first chunk of the next tile under the last
+  // MFMAs of this one was measured too: no gain at 2 tiles of 12 chunks, a loss at 16 tiles of 2 chunks.)
+  int st = 0;
   for (int b0 = cbeg; b0 < cend; b0 += ST_TM) {
     f32x16 acc[4][2];
 #pragma unroll
@@ -188,15 +193,15 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
 
-    const int tile_row0 = loads_q ? a0 : b0;
-    __syncthreads();  // the previous tile's readers (and the epilogue's LDS use) are done with both stages
-    prefetch(tile_row0, 0, 0);
+    const int row0 = loads_q ? a0 : b0;
+    // nothing is in flight and every reader is past the last barrier: both stages are free
+    prefetch(row0, 0, st & 1);
     wait_vmem<0>();
     __syncthreads();
     bf16x8 af[2][4], bfg[2][2];
-    for (int kc = 0; kc < nk; kc++) {
-      if (kc + 1 < nk) prefetch(tile_row0, kc + 1, (kc + 1) & 1);
-      const int so = (kc & 1) * ST_STAGE_BYTES;
+    for (int kc = 0; kc < nk; kc++, st++) {
+      if (kc + 1 < nk) prefetch(row0, kc + 1, (st + 1) & 1);
+      const int so = (st & 1) * ST_STAGE_BYTES;
       __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the fragment reads with the MFMA stream
       auto load_frags = [&](int ks, int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -217,52 +222,48 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
       __syncthreads();  // ... and everybody's; nobody still reads the stage that is overwritten next
     }
 
-    // ---- tile epilogue: online softmax statistics, all in registers -----------------------------
+    // ---- tile epilogue: online softmax statistics, all in registers; acc holds the raw dot products, the
+    // base-2 logit is t = alpha2 * acc (alpha2 > 0: the order of the raw values is the order of the logits) -------
     const int brow0 = b0 + wm * 128 + 4 * (lane >> 5);  // + mt*32 + 8*(r/4) + r%4
     const bool edge = (b0 + ST_TM > cend);
 #pragma unroll
     for (int nt = 0; nt < 2; nt++) {
       const int a = a_col[nt];
-      // scale to base-2 logits, apply the masks that can touch this tile
+      // the masks that can touch this tile
       const bool diag = mask_self && (a >= b0 && a < b0 + ST_TM);
       const bool haspos = (unsigned)(r_of[nt] - b0) < (unsigned)ST_TM;
-#pragma unroll
-      for (int mt = 0; mt < 4; mt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[mt][nt][r] *= alpha2;
       if (edge || diag || haspos) {  // rare: the general slow walk
 #pragma unroll
         for (int mt = 0; mt < 4; mt++)
 #pragma unroll
           for (int r = 0; r < 16; r++) {
             int j = brow0 + mt * 32 + 8 * (r >> 2) + (r & 3);
-            float t = acc[mt][nt][r];
-            if (j == r_of[nt]) rpos[nt] = t;
+            if (j == r_of[nt]) rpos[nt] = acc[mt][nt][r] * alpha2;
             if (j >= cend || (mask_self && j == a)) acc[mt][nt][r] = -INFINITY;
           }
       }
       // tile max + first index attaining it (rows are visited in increasing j within mt; across
       // register order j is increasing too, so a strict > keeps the smallest index)
-      float tm = -INFINITY; int ti = 0x7fffffff;
+      float tmr = -INFINITY; int tc = 0;
 #pragma unroll
       for (int mt = 0; mt < 4; mt++)
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-          float t = acc[mt][nt][r];
-          int j = brow0 + mt * 32 + 8 * (r >> 2) + (r & 3);
-          bool gt = t > tm;
-          tm = gt ? t : tm;
-          ti = gt ? j : ti;
+          const float t = acc[mt][nt][r];
+          const bool le = t <= tmr;
+          tmr = le ? tmr : t;
+          tc = le ? tc : (mt * 32 + 8 * (r >> 2) + (r & 3));
         }
-      if (tm > -INFINITY) {
-        float mn = fmaxf(rm[nt], tm);
+      if (tmr > -INFINITY) {
+        const float tm = tmr * alpha2;
+        const float mn = fmaxf(rm[nt], tm);
         float s = 0.f;
 #pragma unroll
         for (int mt = 0; mt < 4; mt++)
 #pragma unroll
-          for (int r = 0; r < 16; r++) s += fast_exp2(acc[mt][nt][r] - mn);
+          for (int r = 0; r < 16; r++) s += fast_exp2(__builtin_fmaf(acc[mt][nt][r], alpha2, -mn));
         rl[nt] = rl[nt] * fast_exp2(rm[nt] - mn) + s;
-        if (tm > rm[nt]) ridx[nt] = ti;  // later tiles have larger j: strict >
+        if (tm > rm[nt]) ridx[nt] = brow0 + tc;  // later tiles have larger j: strict >
         rm[nt] = mn;
       }
     }
