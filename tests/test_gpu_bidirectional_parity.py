@@ -31,7 +31,9 @@ def run(q, p, r, scale, temp):
 @pytest.mark.parametrize("n,d,scale,temp,tol", [(96, 128, 1.0, 0.5, TOL_BF16), (300, 256, 2.0, 1.0, TOL_BF16),
                                                 (257, 64, 1.0, 0.1, TOL_BF16_PEAKED), (1024, 768, 1.0, 1.0, TOL_BF16),
                                                 (1500, 128, 1.0, 0.07, TOL_BF16_PEAKED),
-                                                (1500, 256, 1.0, 0.07, TOL_BF16_PEAKED)])
+                                                (1500, 256, 1.0, 0.07, TOL_BF16_PEAKED),
+                                                (200, 384, 1.0, 1.0, TOL_BF16), (333, 512, 1.5, 0.5, TOL_BF16),
+                                                (130, 640, 1.0, 0.2, TOL_BF16_PEAKED), (64, 96, 1.0, 1.0, TOL_BF16)])
 def test_bidirectional_matches_the_oracle(n, d, scale, temp, tol):
     q, p, r = problem(n, d, 6000 + n)
     q64, p64 = synth.widen(q), synth.widen(p)
@@ -45,6 +47,20 @@ def test_bidirectional_matches_the_oracle(n, d, scale, temp, tol):
             assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
         else:                # fp32-FMA kernels: nothing is rounded to bf16
             assert relerr(to_np(out[k]), want[k]) <= 1e-5
+
+
+def test_bidirectional_at_the_benchmark_size():
+    """n = 8192, d = 768 (the shape `bench.py --workload bidir` times): every output against the oracle."""
+    n, d = 8192, 768
+    q, p, r = problem(n, d, 6400)
+    want = O.bidirectional(synth.widen(q), synth.widen(p), r.numpy(), 1.0, 1.0)
+    out = run(q, p, r, 1.0, 1.0)
+    assert abs(out["loss"].item() - want["loss"]) <= 1e-5 * abs(want["loss"])
+    for k in ("dq", "dp"):
+        assert relerr(to_np(out[k]), want[k]) <= TOL_BF16
+    # Euler identity: sum_i <q_i, dq_i> = sum_j <p_j, dp_j> (both are (alpha/n) sum_ij g_ij <q_i, p_j>)
+    a = float((synth.widen(q) * to_np(out["dq"])).sum()), float((synth.widen(p) * to_np(out["dp"])).sum())
+    assert abs(a[0] - a[1]) <= 1e-3 * max(abs(a[0]), abs(a[1]), 1e-6)
 
 
 def test_bidirectional_with_equal_sides_is_twice_symmetric():

@@ -13,7 +13,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("n,d,tau", [(512, 128, 0.07), (130, 128, 0.5), (66, 64, 0.2), (1000, 256, 0.1)])
+@pytest.mark.parametrize("n,d,tau", [(512, 128, 0.07), (130, 128, 0.5), (66, 64, 0.2), (1000, 256, 0.1),
+                                     (300, 384, 0.2), (258, 512, 0.1), (192, 640, 0.5), (700, 768, 0.07),
+                                     (2, 128, 0.5), (4100, 128, 0.1)])
 def test_ntxent_small(n, d, tau):
     z = synth.ntxent_views(n, d, seed=4000 + n)
     want = O.ntxent(synth.widen(z), tau)
