@@ -25,7 +25,7 @@ import numpy as np
 from scipy.special import erf
 
 __all__ = [
-    "loss_and_rep_grad", "ntxent", "bidirectional", "mlp_forward", "mlp_backward",
+    "loss_and_rep_grad", "ntxent", "bidirectional", "bilinear_distance", "mlp_forward", "mlp_backward",
     "mlp_fullbatch_grad", "mlp_chunked_grad", "mlp_accumulation_grad", "round_to_bf16",
 ]
 
@@ -149,6 +149,45 @@ def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0, g_dtype=None):
         assert g_dtype == "bf16"
         g = round_to_bf16(g)
     return dict(loss=float(loss), dq=(alpha / n) * (g @ p), dp=(alpha / n) * (g.T @ q))
+
+
+def bilinear_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, rep_dtype=None, g_dtype=None):
+    """Loss with a parameterised distance function (Sec. "Extend to Deep Distance
+    Function"), for the bilinear form Phi_Omega(f, g) = f^T Omega g, Omega [d, d]:
+      d_ij = f(s_i)^T Omega g(t_j)                     (the section's first equation)
+      logits alpha * d_ij, loss as Eq. 1
+      w_ij = dL/dd_ij = (alpha/B) (p_ij - [j == r_i])  (the Distance Gradient Cache)
+      dOmega = sum_ij w_ij f(s_i) g(t_j)^T             (its gradient of Omega: d Phi / d Omega = f g^T)
+      u_i = sum_j w_ij Omega g(t_j)                    (d d_ij / d f(s_i) = Omega g(t_j))
+      v_j = sum_i w_ij Omega^T f(s_i)                  (d d_ij / d g(t_j) = Omega^T f(s_i))
+    The B x P matrix w is materialised here, as the paper's description stores it.
+    rep_dtype="bf16": the products h_i = Omega^T f(s_i) are stored in bf16 before
+    they meet the targets (scores d_ij = <h_i, g(t_j)> and v_j = sum_i w_ij h_i use
+    the stored values); u and dOmega flow through the unrounded bilinear form.
+    g_dtype="bf16": w is rounded to bf16 (in units of alpha/B) before it is contracted.
+    Returns dict(loss, w, u, v, domega)."""
+    q = _f64(q)
+    p = _f64(p)
+    om = _f64(omega)
+    r = np.asarray(pos_idx, dtype=np.int64)
+    B, d = q.shape
+    P = p.shape[0]
+    assert om.shape == (d, d) and p.shape[1] == d and r.shape == (B,)
+    assert np.all((r >= 0) & (r < P))
+    alpha = float(scale) / float(temp)
+    h = _store(q @ om, rep_dtype)                # h_i^T = f(s_i)^T Omega
+    s = alpha * (h @ p.T)
+    m = s.max(axis=1)
+    lse = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    loss = np.sum(lse - s[np.arange(B), r]) / B
+    g = np.exp(s - lse[:, None])
+    g[np.arange(B), r] -= 1.0
+    if g_dtype is not None:
+        assert g_dtype == "bf16"
+        g = round_to_bf16(g)
+    w = (alpha / B) * g
+    a = w @ p                                    # sum_j w_ij g(t_j)
+    return dict(loss=float(loss), w=w, u=a @ om.T, v=w.T @ h, domega=q.T @ a)
 
 
 # ---------------------------------------------------------------------------

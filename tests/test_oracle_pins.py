@@ -229,6 +229,46 @@ def test_lib_and_fd_bidirectional():
     np.testing.assert_allclose(both["dq"] + both["dp"], one["dq"] + one["dp"], rtol=1e-10, atol=1e-15)
 
 
+def test_bilinear_distance_against_autograd_enumeration_and_the_dot_product_case():
+    """Parameterised distance (Sec. "Extend to Deep Distance Function") with Phi = f^T Omega g."""
+    B, P, d = 6, 9, 4
+    q, p, r = rand_problem(B, P, d, seed=45, std=1.0)
+    om = rng(46).standard_normal((d, d))
+    alpha = 1.3
+    out = O.bilinear_distance(q, p, r, om, scale=alpha, temp=1.0)
+    # library routine + autograd: cross-entropy of alpha * d_ij, gradients of f, g, Omega and of the distances
+    tq = torch.tensor(q, requires_grad=True)
+    tp = torch.tensor(p, requires_grad=True)
+    to = torch.tensor(om, requires_grad=True)
+    dist = tq @ to @ tp.T
+    dist.retain_grad()
+    loss = torch.nn.functional.cross_entropy(alpha * dist, torch.tensor(r, dtype=torch.long))
+    loss.backward()
+    assert out["loss"] == pytest.approx(loss.item(), rel=1e-12)
+    np.testing.assert_allclose(out["w"], dist.grad.numpy(), rtol=1e-9, atol=1e-15)       # the distance gradient cache
+    np.testing.assert_allclose(out["u"], tq.grad.numpy(), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(out["v"], tp.grad.numpy(), rtol=1e-9, atol=1e-14)
+    np.testing.assert_allclose(out["domega"], to.grad.numpy(), rtol=1e-9, atol=1e-14)
+    # central differences of the loss written out by enumeration, on Omega (h_i = Omega^T f_i takes the anchor's place)
+    f = lambda: brute_force_loss((q @ om).tolist(), p.tolist(), r.tolist(), alpha)
+    assert_close_norm(out["domega"], fd_grad(f, om), 1e-7)
+    # Omega = I is the dot product of the main text: u = Eq. 5, v = Eq. 6
+    eye = O.bilinear_distance(q, p, r, np.eye(d), scale=alpha)
+    one = O.loss_and_rep_grad(q, p, r, scale=alpha)
+    assert eye["loss"] == pytest.approx(one["loss"], rel=1e-14)
+    np.testing.assert_allclose(eye["u"], one["dq"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(eye["v"], one["dp"], rtol=1e-12, atol=1e-16)
+    # ... and its Omega gradient is sum_i f_i (dL/df_i)^T-like: dOmega = F^T (W G), checked as an explicit double sum
+    dom = np.zeros((d, d))
+    for i in range(B):
+        for j in range(P):
+            dom += out["w"][i, j] * np.outer(q[i], p[j])
+    np.testing.assert_allclose(out["domega"], dom, rtol=1e-10, atol=1e-15)
+    # stored-in-bf16 products: the scores change by at most the rounding of h, the rest follows
+    st = O.bilinear_distance(q, p, r, om, scale=alpha, rep_dtype="bf16")
+    assert 0 < abs(st["loss"] - out["loss"]) < 2e-2 and np.abs(st["u"] - out["u"]).max() < 5e-2
+
+
 # ------------------------------------------------------------------ invariants
 def test_i1_i2_row_sums_and_euler_identity():
     q, p, r = rand_problem(17, 29, 24, seed=50)
