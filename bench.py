@@ -78,6 +78,14 @@ def side_workload(args, gc, synth, dev):
         res = gc.gc_bidirectional_loss_and_rep_grad_bf16(qd, pd, rd, 1.0, 1.0, ws)
         step = lambda: gc.gc_bidirectional_loss_and_rep_grad_bf16(qd, pd, rd, 1.0, 1.0, ws, out=res)
         flops, what = 2 * 6.0 * n * n * d, "symmetric loss+rep-grad, n=8192 d=768 bf16 (two directions)"
+    elif args.workload == "bilinear":
+        q, p, r = synth.config3()
+        om = synth.bilinear_omega(768).to(dev)
+        qd, pd, rd = q.to(dev), p.to(dev), r.to(dev)
+        res = gc.gc_bilinear_loss_and_grads_bf16(qd, pd, rd, om)
+        step = lambda: gc.gc_bilinear_loss_and_grads_bf16(qd, pd, rd, om, workspace=res["workspace"], out=res)
+        flops = 6.0 * 4096 * 8192 * 768 + 3 * 2.0 * 4096 * 768 * 768
+        what = "bilinear distance f^T Omega g: loss, u, v, dOmega at B=4096 P=8192 d=768 bf16"
     else:
         xq, xp, r, params = synth.mlp_problem()
         xq, xp, r = xq.to(dev), xp.to(dev), r.to(dev)
@@ -108,7 +116,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5", "bidir"],
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5", "bidir", "bilinear"],
                     help="config3 (default) is the headline workload; the others print a shorter timing line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise kernel 4 times that reads 1 GiB and writes 1 GiB (known HBM "

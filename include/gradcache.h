@@ -147,6 +147,28 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
                                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Loss with a parameterised distance function (Sec. "Extend to Deep Distance
+ * Function"), for the bilinear form Phi_Omega(f, g) = f^T Omega g:
+ *   d_ij = f(s_i)^T Omega g(t_j), logits scale * d_ij / temp, loss as Eq. 1.
+ * With w_ij = dL/dd_ij (the section's Distance Gradient Cache) the outputs are
+ *   u[B,d]      = dL/df(s_i) = sum_j w_ij Omega g(t_j)
+ *   v[P,d]      = dL/dg(t_j) = sum_i w_ij Omega^T f(s_i)
+ *   domega[d,d] = dL/dOmega  = sum_ij w_ij f(s_i) g(t_j)^T
+ * (the section's last three equations); u and v are what Step 3 takes as the
+ * Representation Gradient Cache.  w is never stored: it exists tile by tile inside
+ * the loss kernels, which run on h_i = Omega^T f(s_i) (kept in bf16) against the
+ * targets.  q[B,d], p[P,d], omega[d,d] (row-major) bf16, pos_idx[B] int32; loss[1],
+ * u, v, domega float, overwritten; all device memory.  d must be a multiple of 128
+ * up to 768 (else GC_ERR_UNSUPPORTED).  Errors as gc_loss_and_rep_grad_ex; the
+ * asynchronous pos_idx error is read with gc_check_async_error(workspace).
+ * workspace: gc_bilinear_workspace_bytes(B, P, d) (0 for an unsupported shape).
+ */
+size_t gc_bilinear_workspace_bytes(int B, int P, int d);
+int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                                    const void* omega, float scale, float temp, float* loss, float* u, float* v,
+                                    float* domega, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Stand-in encoder  y = GELU(x W1 + b1) W2 + b2  (exact erf GELU), bf16 storage,
  * fp32 accumulation.  W1[din,dh], b1[dh], W2[dh,dout], b2[dout], all device bf16.
  * din must be a multiple of 64, dh and dout multiples of 128 (else

@@ -21,7 +21,8 @@ EXPORTS = [
     "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",
     "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
     "gc_ntxent_loss_and_grad_bf16", "gc_bidirectional_workspace_bytes",
-    "gc_bidirectional_loss_and_rep_grad_bf16", "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
+    "gc_bidirectional_loss_and_rep_grad_bf16", "gc_bilinear_workspace_bytes", "gc_bilinear_loss_and_grads_bf16",
+    "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
     "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
     "gc_profile_begin", "gc_profile_end",
 ]
@@ -75,6 +76,10 @@ def load():
     lib.gc_bidirectional_workspace_bytes.argtypes = [ci, ci]
     lib.gc_bidirectional_loss_and_rep_grad_bf16.restype = ci
     lib.gc_bidirectional_loss_and_rep_grad_bf16.argtypes = [vp, vp, vp, ci, ci, cf, cf, vp, vp, vp, vp, sz, vp]
+    lib.gc_bilinear_workspace_bytes.restype = sz
+    lib.gc_bilinear_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.gc_bilinear_loss_and_grads_bf16.restype = ci
+    lib.gc_bilinear_loss_and_grads_bf16.argtypes = [vp, vp, vp, ci, ci, ci, vp, cf, cf, vp, vp, vp, vp, vp, sz, vp]
     pp, pg = ctypes.POINTER(gc_mlp_params), ctypes.POINTER(gc_mlp_grads)
     lib.gc_mlp_workspace_bytes.restype = sz
     lib.gc_mlp_workspace_bytes.argtypes = [ci, pp]
@@ -241,6 +246,34 @@ def gc_bidirectional_loss_and_rep_grad_bf16(q, p, pos_idx, scale=1.0, temp=1.0, 
     rc = lib.gc_bidirectional_loss_and_rep_grad_bf16(_ptr(q), _ptr(p), _ptr(pos_idx), n, d, scale, temp, _ptr(out["loss"]),
                                                      _ptr(out["dq"]), _ptr(out["dp"]), wp, wn, _stream(stream))
     _check(rc, "gc_bidirectional_loss_and_rep_grad_bf16")
+    return out
+
+
+def gc_bilinear_loss_and_grads_bf16(q, p, pos_idx, omega, scale=1.0, temp=1.0, workspace=None, out=None, stream=None):
+    """Bilinear distance f^T Omega g; returns dict(loss, u, v, domega, workspace)."""
+    lib = load()
+    for t, name in ((q, "q"), (p, "p"), (omega, "omega")):
+        _dev_contig(t, torch.bfloat16, name)
+    _dev_contig(pos_idx, torch.int32, "pos_idx")
+    B, d = q.shape
+    P = p.shape[0]
+    if p.shape[1] != d or tuple(omega.shape) != (d, d) or tuple(pos_idx.shape) != (B,):
+        raise GradCacheError(GC_ERR_SHAPE, "gc_bilinear_loss_and_grads_bf16")
+    if out is None:
+        f32 = dict(dtype=torch.float32, device=q.device)
+        out = dict(loss=torch.empty(1, **f32), u=torch.empty(B, d, **f32), v=torch.empty(P, d, **f32),
+                   domega=torch.empty(d, d, **f32))
+    if workspace is None:
+        need = lib.gc_bilinear_workspace_bytes(B, P, d)
+        if need == 0:
+            raise GradCacheError(GC_ERR_UNSUPPORTED, "gc_bilinear_workspace_bytes")
+        workspace = alloc_workspace(need, q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_bilinear_loss_and_grads_bf16(_ptr(q), _ptr(p), _ptr(pos_idx), B, P, d, _ptr(omega), scale, temp,
+                                             _ptr(out["loss"]), _ptr(out["u"]), _ptr(out["v"]), _ptr(out["domega"]),
+                                             wp, wn, _stream(stream))
+    _check(rc, "gc_bilinear_loss_and_grads_bf16")
+    out["workspace"] = workspace
     return out
 
 

@@ -29,7 +29,7 @@ namespace gc {
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4m;
 
-enum Epilogue { EP_GELU = 0, EP_BIAS = 1, EP_DH = 2 };
+enum Epilogue { EP_GELU = 0, EP_BIAS = 1, EP_DH = 2, EP_PLAIN = 3 };
 
 __device__ __forceinline__ float gelu_f(float h) { return 0.5f * h * (1.f + erff(h * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_prime_f(float h) {
@@ -145,6 +145,28 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g2, WgradArgs 
   }
 }
 
+// C = A^T B with the rows (K) cut into slices: workgroup (tile, slice) adds its slice's product to partial s of C
+// (g.C + s * M * ldc, zeroed by the caller), which a fixed-order sum combines afterwards.  A bf16.
+__global__ void __launch_bounds__(256) wgrad_splitk_kernel(WgradArgs g, int rows_per_slice) {
+  __shared__ __attribute__((aligned(16))) unsigned short As[2 * WG_KCH * WG_A_LD];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * WG_KCH * WG_B_LD];
+  const int nb = g.N / 128, tiles = nb * (g.M / 32);
+  const int tile = blockIdx.x % tiles, slice = blockIdx.x / tiles;
+  const int k0 = slice * rows_per_slice;
+  WgradArgs s = g;
+  s.A = (const unsigned short*)g.A + (size_t)k0 * g.lda;
+  s.B = g.B + (size_t)k0 * g.ldb;
+  s.K = min(rows_per_slice, g.K - k0);
+  s.C = g.C + (size_t)slice * g.M * g.ldc;
+  s.colsum = nullptr;
+  wgrad_tile<false>(s, tile % nb, tile / nb, As, Bs);
+}
+
+__global__ void __launch_bounds__(256) fill_f32_kernel(float* x, size_t n, float v) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) x[i] = v;
+}
+
 // ---------------------------------------------------------------------------------------------------
 struct SkinnyArgs {
   const void* A; int lda;            // [M][K], bf16 or fp32
@@ -153,8 +175,8 @@ struct SkinnyArgs {
   const unsigned short* bias;        // EP_GELU / EP_BIAS: [N] bf16
   float* H; int ldh;                 // EP_GELU: optional fp32 pre-activation out; EP_DH: fp32 pre-activation in
   float* ActF;                       // EP_GELU: fp32 activation out (ldh)
-  unsigned short* Cb; int ldc;       // EP_BIAS: bf16 output
-  float* Cf;                         // EP_DH: dH out (fp32, ldc)
+  unsigned short* Cb; int ldc;       // EP_BIAS: bf16 output; EP_PLAIN: bf16 output if set
+  float* Cf;                         // EP_DH: dH out (fp32, ldc); EP_PLAIN: fp32 output if Cb is not set
   float* colsum;                     // EP_DH: db1 [N] += column sums (one m-tile per launch: single writer)
 };
 
@@ -229,6 +251,11 @@ __device__ __forceinline__ void skinny_tile(const SkinnyArgs& g, int bx, int by,
       }
     } else if (EP == EP_BIAS) {
       if (mm < g.M) g.Cb[(size_t)mm * g.ldc + n] = f2bf(sum + bf2f(g.bias[n]));
+    } else if (EP == EP_PLAIN) {  // the product itself
+      if (mm < g.M) {
+        if (g.Cb) g.Cb[(size_t)mm * g.ldc + n] = f2bf(sum);
+        else g.Cf[(size_t)mm * g.ldc + n] = sum;
+      }
     } else {  // EP_DH
       float v = 0.f;
       if (mm < g.M) {
@@ -640,6 +667,89 @@ int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32
   c.w = *w; c.scale = scale; c.temp = temp; c.loss = loss; c.grads = *grads; c.q_rep = q_rep; c.p_rep = p_rep;
   c.dq = dq; c.dp = dp; c.workspace = workspace;
   return run_step(c, (hipStream_t)stream);
+}
+
+
+// ---- parameterised distance function (Sec. "Extend to Deep Distance Function"), bilinear form ---------------
+// d_ij = f_i^T Omega g_j = <h_i, g_j> with h_i = Omega^T f_i: the loss path on (H, G) gives the loss, A = dL/dH
+// (rows a_i = sum_j w_ij g_j) and v = dL/dG (rows sum_i w_ij h_i); then u = A Omega^T and dOmega = F^T A.
+// The weights w_ij live only inside the tiles of the loss kernels.
+struct BilinearWs { size_t off_loss, loss_bytes, off_omT, off_H, off_A, off_part, total; int slices, rows_per_slice; };
+static BilinearWs plan_bilinear(int B, int P, int d) {
+  BilinearWs w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = up256(off + bytes); return o; };
+  w.loss_bytes = gc_workspace_bytes(B, P, d, GC_BF16);
+  w.off_loss = take(w.loss_bytes);
+  w.off_omT = take((size_t)d * d * 2);
+  w.off_H = take((size_t)B * d * 2);
+  w.off_A = take((size_t)B * d * 4);
+  const int tiles = (d / 128) * (d / 32);
+  int slices = (4 * kNumCU + tiles - 1) / tiles;           // about four workgroups per CU
+  const int max_slices = (B + 127) / 128;                   // at least 128 rows per slice
+  if (slices > max_slices) slices = max_slices;
+  if (slices > 64) slices = 64;
+  if (slices < 1) slices = 1;
+  w.rows_per_slice = ((B + slices - 1) / slices + 31) / 32 * 32;
+  w.slices = (B + w.rows_per_slice - 1) / w.rows_per_slice;
+  w.off_part = take((size_t)w.slices * d * d * 4);
+  w.total = off;
+  return w;
+}
+static bool bilinear_shape_ok(int B, int P, int d) {
+  return B >= 1 && P >= 1 && d >= 1 && (long long)B * d <= (1ll << 40) && (long long)P * d <= (1ll << 40);
+}
+
+size_t gc_bilinear_workspace_bytes(int B, int P, int d) {
+  if (!bilinear_shape_ok(B, P, d) || d % 128 || d > 768) return 0;
+  return plan_bilinear(B, P, d).total;
+}
+
+int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                                    const void* omega, float scale, float temp, float* loss, float* u, float* v,
+                                    float* domega, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !p || !pos_idx || !omega || !loss || !u || !v || !domega) return GC_ERR_NULL;
+  if (!bilinear_shape_ok(B, P, d)) return GC_ERR_SHAPE;
+  if (!(scale > 0.f) || !(temp > 0.f) || !std::isfinite(scale) || !std::isfinite(temp) || !std::isfinite(scale / temp) ||
+      !(scale / temp > 0.f))
+    return GC_ERR_SHAPE;
+  if (d % 128 || d > 768) return GC_ERR_UNSUPPORTED;
+  const BilinearWs w = plan_bilinear(B, P, d);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return GC_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t s = (hipStream_t)stream;
+  unsigned short* omT = (unsigned short*)(ws + w.off_omT);
+  unsigned short* H = (unsigned short*)(ws + w.off_H);
+  float* A = (float*)(ws + w.off_A);
+  float* part = (float*)(ws + w.off_part);
+  // H = F Omega (bf16): Bt[n][k] = Omega[k][n]
+  transpose_bf16_kernel<<<dim3(d / 32, d / 32), 256, 0, s>>>((const unsigned short*)omega, d, d, omT);
+  {
+    SkinnyArgs g{};
+    g.A = q; g.lda = d; g.Bt = omT; g.ldb = d; g.M = B; g.N = d; g.K = d; g.Cb = H; g.ldc = d;
+    mlp_skinny_kernel<false, EP_PLAIN><<<dim3(d / 32, (B + 31) / 32), 256, 0, s>>>(g);
+  }
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  // loss, A = dL/dH, v = dL/dG
+  int rc = gc_loss_and_rep_grad_ex(GC_BF16, H, p, pos_idx, B, P, d, scale, temp, 0, loss, A, v, nullptr, nullptr,
+                                   ws + w.off_loss, w.loss_bytes, stream);
+  if (rc != GC_OK) return rc;
+  {  // u = A Omega^T: Bt[n][k] = Omega[n][k]
+    SkinnyArgs g{};
+    g.A = A; g.lda = d; g.Bt = (const unsigned short*)omega; g.ldb = d; g.M = B; g.N = d; g.K = d; g.Cf = u; g.ldc = d;
+    mlp_skinny_kernel<true, EP_PLAIN><<<dim3(d / 32, (B + 31) / 32), 256, 0, s>>>(g);
+  }
+  {  // dOmega = F^T A, the rows cut into slices, partial sums in a fixed order
+    const size_t n = (size_t)w.slices * d * d;
+    fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, n, 0.f);
+    WgradArgs g{};
+    g.A = q; g.lda = d; g.B = A; g.ldb = d; g.M = d; g.N = d; g.K = B; g.C = part; g.ldc = d;
+    wgrad_splitk_kernel<<<(d / 128) * (d / 32) * w.slices, 256, 0, s>>>(g, w.rows_per_slice);
+    if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+    const float* srcs[1] = {part}; int counts[1] = {w.slices}; size_t strides[1] = {(size_t)d * d};
+    if (launch_partial_reduce(domega, srcs, counts, strides, 1, (size_t)d * d, s) != hipSuccess) return GC_ERR_HIP;
+  }
+  return GC_OK;
 }
 
 }  // extern "C"

@@ -89,3 +89,10 @@ def mlp_problem(B=512, P=1024, din=1024, dh=3072, dout=768, dtype=torch.bfloat16
     k = max(P // B, 1)
     pos_idx = torch.clamp(torch.arange(B, dtype=torch.int32) * k, max=P - 1)
     return xq, xp, pos_idx, params
+
+
+def bilinear_omega(d, dtype=torch.bfloat16, seed=SEED0 + 6, noise=0.5):
+    """Parameter matrix of the bilinear distance: the identity (the dot product of the main text) plus
+    `noise` times an iid N(0, 1/d) matrix, rounded to the storage type."""
+    rng = np.random.default_rng(seed)
+    return (torch.eye(d) + noise * _normal(rng, (d, d), d ** -0.5)).to(dtype)

@@ -82,6 +82,19 @@ def test_argument_errors_are_raised_on_the_host():
     assert bd(fake, fake, fake, 16, 128, 1.0, 0.0, fake, fake, fake, fake, 1 << 30, None) == gc.GC_ERR_SHAPE
     assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, fake, fake, None, 1 << 30, None) == gc.GC_ERR_WORKSPACE
     assert bd(fake, fake, fake, 16, 128, 1.0, 1.0, fake, fake, fake, fake, 64, None) == gc.GC_ERR_WORKSPACE
+    bl = lib.gc_bilinear_loss_and_grads_bf16
+    bargs = lambda **k: [k.get("q", fake), fake, fake, k.get("B", 8), 16, k.get("d", 128), k.get("om", fake), 1.0,
+                         k.get("temp", 1.0), fake, fake, fake, k.get("dom", fake), k.get("ws", fake), k.get("wsb", 1 << 30), None]
+    assert bl(*bargs(q=None)) == gc.GC_ERR_NULL
+    assert bl(*bargs(om=None)) == gc.GC_ERR_NULL
+    assert bl(*bargs(dom=None)) == gc.GC_ERR_NULL
+    assert bl(*bargs(B=0)) == gc.GC_ERR_SHAPE
+    assert bl(*bargs(temp=0.0)) == gc.GC_ERR_SHAPE
+    assert bl(*bargs(d=96)) == gc.GC_ERR_UNSUPPORTED
+    assert bl(*bargs(d=1024)) == gc.GC_ERR_UNSUPPORTED
+    assert bl(*bargs(ws=None)) == gc.GC_ERR_WORKSPACE
+    assert bl(*bargs(wsb=1024)) == gc.GC_ERR_WORKSPACE
+    assert lib.gc_bilinear_workspace_bytes(8, 16, 96) == 0 and lib.gc_bilinear_workspace_bytes(8, 16, 128) > 0
     # loss workspaces (split partials included; four gradient buffers for widths the MFMA kernels do not take):
     # never the n x n scores
     for n in (4096, 8192, 65536):
