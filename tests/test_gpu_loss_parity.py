@@ -117,6 +117,32 @@ def test_peaked_softmax_at_low_temperature(B, P, d, temp):
         assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
 
 
+@pytest.mark.parametrize("B,P,d,dtype", [(200, 700, 256, torch.bfloat16), (90, 300, 768, torch.bfloat16),
+                                         (64, 200, 128, torch.bfloat16), (40, 90, 48, torch.float32)])
+def test_very_large_logits_neither_overflow_nor_vanish(B, P, d, dtype):
+    """Logits of 200 to 400 (scale 400 on unit-norm rows): every exponent the kernels form is <= 0, so nothing
+    overflows, and each row's largest term is 1, so no row sum vanishes; the softmax is one-hot up to fp32."""
+    q, p, r = synth.dpr_batch(B, P, d, dtype, seed=2700 + B, positive_mix=0.6)
+    scale = 400.0
+    q64, p64 = synth.widen(q), synth.widen(p)
+    want = O.loss_and_rep_grad(q64, p64, r.numpy(), scale, 1.0)
+    assert np.abs(scale * q64 @ p64.T).max() > 200.0
+    out = run_ex(q, p, r, scale, 1.0)
+    for k in ("loss", "dq", "dp", "lse"):
+        assert torch.isfinite(out[k]).all(), k
+    assert abs(out["loss"].item() - want["loss"]) <= 1e-4 * abs(want["loss"])
+    assert relerr(to_np(out["lse"]), want["lse"]) <= 1e-5
+    # The softmax is saturated here (g_ij is 0 or -1 + 1 up to 1e-40), so the true gradients are next to nothing and
+    # a relative error says nothing.  What the arithmetic fixes is the absolute error of a coefficient: t and lse2
+    # are fp32 numbers of size |logit| log2(e), so 2^(t - lse2) near 1 is off by about ln2 (ulp(t) + ulp(lse2)) <=
+    # 4 * 2^-24 |t|, on top of the bf16 rounding of g; a gradient row is (alpha/B) sum_j g_ij p_j.
+    t_max = np.abs(scale * q64 @ p64.T).max() * math.log2(math.e)
+    g_err = (2.0 ** -8 if dtype == torch.bfloat16 else 0.0) * 1e-3 + 4 * 2.0 ** -24 * t_max
+    assert np.abs(to_np(out["dq"]) - want["dq"]).max() <= scale / B * np.abs(p64).max() * g_err * 4
+    assert np.abs(to_np(out["dp"]) - want["dp"]).max() <= scale / B * np.abs(q64).max() * g_err * 4
+    assert np.array_equal(to_np(out["argmax"]), want["argmax"])
+
+
 @pytest.mark.parametrize("n,d,dtype", [(96, 128, torch.bfloat16), (70, 24, torch.float32), (322, 256, torch.bfloat16)])
 def test_mask_self(n, d, dtype):
     q, p, _ = synth.dpr_batch(n, n, d, dtype, seed=3000 + n)
