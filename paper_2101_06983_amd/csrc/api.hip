@@ -41,6 +41,21 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
     split_of(P, pl.nsq, pl.q_stream_len);
     split_of(B, pl.nsp, pl.p_stream_len);
     if (pl.one_walk) { pl.nsp = 1; pl.p_stream_len = B; }
+    // fused mode: each walk is a launch of its own and has to fill the GPU alone
+    pl.fused = (d >= 256 && !ntxent) ? 1 : 0;
+    if (pl.fused) {
+      auto split_alone = [&](long long own_blocks, int n, int& ns, int& len) {
+        long long La = (own_blocks * n + kNumCU - 1) / kNumCU;
+        if (La < 256) La = 256;
+        ns = (int)((n + La - 1) / La);
+        if (ns > 16) ns = 16;
+        if (ns < 1) ns = 1;
+        len = (ceil_div(n, ns) + 31) / 32 * 32;
+        ns = ceil_div(n, len);
+      };
+      split_alone(obQ, P, pl.fz_nsq, pl.fz_q_stream_len);
+      split_alone(obP, B, pl.fz_nsp, pl.fz_p_stream_len);
+    }
   } else {
     const int blocks = ceil_div(B, 16), tiles = ceil_div(P, 16);
     int splits = ceil_div(4 * kNumCU, blocks);
@@ -56,16 +71,23 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   pl.off_err = take(256);
-  pl.off_part_m = take((size_t)pl.stat_splits * B * 4);
-  pl.off_part_l = take((size_t)pl.stat_splits * B * 4);
-  pl.off_part_idx = take((size_t)pl.stat_splits * B * 4);
+  const int stat_parts = pl.stat_splits > pl.fz_nsq ? pl.stat_splits : pl.fz_nsq;   // fz_* are 0 outside fused mode
+  pl.off_part_m = take((size_t)stat_parts * B * 4);
+  pl.off_part_l = take((size_t)stat_parts * B * 4);
+  pl.off_part_idx = take((size_t)stat_parts * B * 4);
   pl.off_pos = take((size_t)B * 4);
   pl.b_pad = (B + 63) / 64 * 64;
   pl.off_lse2 = take((size_t)pl.b_pad * 4);
   pl.off_pos_pad = take((size_t)pl.b_pad * 4);
   pl.off_rowloss = take((size_t)B * 4);
-  pl.off_dq_part = take((pl.nsq > 1 || ntxent) ? (size_t)pl.nsq * B * d * 4 : 0);
-  pl.off_dp_part = take(((pl.nsp > 1 || ntxent) && !pl.one_walk) ? (size_t)pl.nsp * P * d * 4 : 0);
+  int dq_parts = (pl.nsq > 1 || ntxent) ? pl.nsq : 0, dp_parts = ((pl.nsp > 1 || ntxent) && !pl.one_walk) ? pl.nsp : 0;
+  if (pl.fused) {
+    if (pl.fz_nsq > dq_parts) dq_parts = pl.fz_nsq;            // the online walk always writes partials
+    if (pl.fz_nsp > 1 && pl.fz_nsp > dp_parts) dp_parts = pl.fz_nsp;
+  }
+  pl.off_dq_part = take((size_t)dq_parts * B * d * 4);
+  pl.off_dp_part = take((size_t)dp_parts * P * d * 4);
+  pl.off_on_ref = take((size_t)pl.fz_nsq * B * 4);
   pl.off_pos_idx = take(ntxent ? (size_t)B * 4 : 0);
   pl.total = off;
   return pl;
@@ -113,6 +135,9 @@ static void prof_mark(int call, int mark, hipStream_t s) {
 void prof_mark_grad_kernel_done(hipStream_t s) { prof_mark(g_prof.calls, 3, s); }
 bool prof_active() { return g_prof.on; }
 
+// GC_NO_FUSED=1 in the environment keeps the statistics-pass path for every call (measurement aid)
+static const bool g_no_fused = [] { const char* e = getenv("GC_NO_FUSED"); return e && e[0] == '1'; }();
+
 static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   LossArgs a = a_in;
   // does the gradient pass of this call end in a sum of split partials (launch_grad_mfma)?
@@ -121,6 +146,32 @@ static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
   hipError_t e;
+  if (pl.fused && a.dq && !a.dz && !a.lse2_t && !g_no_fused) {
+    // fused mode: online-statistics dQ walk | merge of its splits (lse2, row losses, dQ) | dP walk | partial sums
+    e = launch_grad_online(a, pl);
+    if (e != hipSuccess) return GC_ERR_HIP;
+    prof_mark(call, 1, a.stream);
+    e = launch_online_finish(a, pl);
+    if (e != hipSuccess) return GC_ERR_HIP;
+    prof_mark(call, 2, a.stream);
+    bool loss_done = false;
+    if (a.dp) {
+      LossArgs b = a;
+      LossPlan pb = pl;
+      b.dq = nullptr;
+      pb.nsp = pl.fz_nsp; pb.p_stream_len = pl.fz_p_stream_len;
+      b.loss_with_partials = pb.nsp > 1;
+      loss_done = b.loss_with_partials;
+      e = launch_grad_mfma(b, pb);   // records mark 3 after the walk
+      if (e != hipSuccess) return GC_ERR_HIP;
+    } else {
+      prof_mark(call, 3, a.stream);
+    }
+    if (!loss_done && launch_loss_sum(a, pl) != hipSuccess) return GC_ERR_HIP;
+    prof_mark(call, 4, a.stream);
+    if (g_prof.on) g_prof.calls++;
+    return GC_OK;
+  }
   if (!a.lse2_t) {
     e = pl.use_mfma ? launch_stats_mfma(a, pl) : launch_stats_generic(a, pl);
     if (e != hipSuccess) return GC_ERR_HIP;

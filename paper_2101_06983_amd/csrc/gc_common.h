@@ -49,8 +49,11 @@ struct LossPlan {
   int nsq, nsp;          // stream splits of the dQ-role / dP-role workgroups of the gradient pass
   int q_stream_len, p_stream_len;  // stream rows per split (multiple of the stream tile)
   int b_pad;             // B rounded up to 64: length of the padded lse2 / pos_pad arrays
+  // fused mode (MFMA kernels, d >= 256, dQ wanted): no statistics pass; an online-statistics dQ walk, a kernel that
+  // merges its splits into lse2 and dQ, then the dP walk.  Each walk fills the GPU alone, so they have splits of their own
+  int fused, fz_nsq, fz_nsp, fz_q_stream_len, fz_p_stream_len;
   size_t off_err, off_part_m, off_part_l, off_part_idx, off_pos, off_lse2, off_pos_pad, off_rowloss, off_dq_part,
-      off_dp_part, off_pos_idx, total;
+      off_dp_part, off_pos_idx, off_on_ref, total;
 };
 
 LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent);
@@ -85,6 +88,9 @@ hipError_t launch_stats_generic(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_grad_generic(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl);
+hipError_t launch_grad_online(const LossArgs& a, const LossPlan& pl);    // fused mode: dQ walk with online statistics
+hipError_t launch_online_finish(const LossArgs& a, const LossPlan& pl);  // ... its splits -> lse2, row losses, dQ
+hipError_t launch_loss_sum(const LossArgs& a, const LossPlan& pl);       // the fixed-order sum of the row losses alone
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl);
 void prof_mark_grad_kernel_done(hipStream_t s);  // measurement aid: event after the main gradient kernel(s)
 bool prof_active();  // the measurement events of the loss path are being recorded

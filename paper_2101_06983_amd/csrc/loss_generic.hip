@@ -271,6 +271,96 @@ __global__ void __launch_bounds__(256) partial_reduce_tail_kernel(float* __restr
   out[e] = acc;
 }
 
+// Fused mode: merge of what the splits of the online dQ walk left per anchor (reference, sum 2^(t - reference), and
+// when the arg-max is asked for the true maximum with its first index) into lse2_i, the row loss and the arg-max, and
+//   dQ_i = sum_s 2^(ref_s,i - lse2_i) part_s,i + (alpha / B) (p_{i r_i} - 1) p_{r_i}
+// where part_s,i = (alpha / B) sum_{j in split s, j != r_i} 2^(t_ij - ref_s,i) p_j (Eq. 5; the positive's own term is
+// formed here in fp32, so a softmax that has converged on the positive does not cancel in bf16).  Splits are
+// combined in index order.  64 threads per anchor, 4 anchors per workgroup.
+struct FinishArgs {
+  const float* on_ref; const float* on_l; const float* on_best; const int* on_idx; const float* on_pos;
+  const int32_t* pos_idx; const unsigned short* P;
+  const float* part; size_t part_stride;
+  int nsq, B, Pn, d, b_pad;
+  float out_scale;
+  float* lse2; int32_t* pos_pad; float* rowloss; float* lse_out; int32_t* argmax_out; float* dq;
+};
+__global__ void __launch_bounds__(256) online_finish_kernel(FinishArgs f) {
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (i >= f.b_pad) return;
+  if (i >= f.B) {
+    if (lane == 0) { f.lse2[i] = INFINITY; f.pos_pad[i] = -1; }
+    return;
+  }
+  // every load of the row's statistics is issued before the first result is needed
+  float sl[16], sr[16];
+#pragma unroll
+  for (int s = 0; s < 16; s++) {
+    const bool live = s < f.nsq;
+    const size_t o = (size_t)(live ? s : 0) * f.B + i;
+    sl[s] = live ? f.on_l[o] : 0.f; sr[s] = live ? f.on_ref[o] : -INFINITY;
+  }
+  const int r = f.pos_idx[i];
+  const bool ok = (r >= 0 && r < f.Pn);
+  const int r_safe = ok ? r : 0;
+  const float pos = f.on_pos[i];
+  float M = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < 16; s++) M = fmaxf(M, sr[s]);
+  float L = 0.f;
+  if (M > -INFINITY) {
+#pragma unroll
+    for (int s = 0; s < 16; s++) L += sl[s] * exp2f(sr[s] - M);   // dead splits: 0 * 2^-inf = 0
+  }
+  const float l2 = M + log2f(L);
+  if (lane == 0) {
+    f.lse2[i] = l2;
+    f.pos_pad[i] = r;
+    f.rowloss[i] = ok ? (l2 - pos) * kLn2 : NAN;
+    if (f.lse_out) f.lse_out[i] = l2 * kLn2;
+    if (f.argmax_out) {
+      float bv = -INFINITY; int bi = 0x7fffffff;
+      for (int s = 0; s < f.nsq; s++) {
+        const float v = f.on_best[(size_t)s * f.B + i];
+        const int idx = f.on_idx[(size_t)s * f.B + i];
+        if (v > bv || (v == bv && idx < bi)) { bv = v; bi = idx; }
+      }
+      f.argmax_out[i] = bi;
+    }
+  }
+  if (!f.dq) return;
+  float w[16];
+#pragma unroll
+  for (int s = 0; s < 16; s++) w[s] = exp2f(sr[s] - l2);
+  // coefficient of the positive: p_{i r_i} - 1
+  const float cpos = ok ? f.out_scale * (exp2f(pos - l2) - 1.f) : 0.f;
+  for (int c = lane; c < f.d / 4; c += 64) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 16; s++)
+      if (s < f.nsq) acc += w[s] * ((const f32x4*)(f.part + (size_t)s * f.part_stride + (size_t)i * f.d))[c];
+    const s16x4 pv = ((const s16x4*)(f.P + (size_t)r_safe * f.d))[c];
+#pragma unroll
+    for (int e = 0; e < 4; e++) acc[e] += cpos * bf2f((unsigned short)pv[e]);
+    ((f32x4*)(f.dq + (size_t)i * f.d))[c] = acc;
+  }
+}
+
+hipError_t launch_online_finish(const LossArgs& a, const LossPlan& pl) {
+  char* ws = a.ws;
+  FinishArgs f{};
+  f.on_ref = (const float*)(ws + pl.off_on_ref); f.on_best = (const float*)(ws + pl.off_part_m);
+  f.on_l = (const float*)(ws + pl.off_part_l); f.on_idx = (const int*)(ws + pl.off_part_idx);
+  f.on_pos = (const float*)(ws + pl.off_pos); f.pos_idx = a.pos_idx; f.P = (const unsigned short*)a.p;
+  f.part = (const float*)(ws + pl.off_dq_part); f.part_stride = (size_t)a.B * a.d;
+  f.nsq = pl.fz_nsq; f.B = a.B; f.Pn = a.P; f.d = a.d; f.b_pad = pl.b_pad;
+  f.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
+  f.lse2 = (float*)(ws + pl.off_lse2); f.pos_pad = (int32_t*)(ws + pl.off_pos_pad); f.rowloss = (float*)(ws + pl.off_rowloss);
+  f.lse_out = a.lse; f.argmax_out = a.argmax; f.dq = a.dq;
+  online_finish_kernel<<<(pl.b_pad + 3) / 4, 256, 0, a.stream>>>(f);
+  return hipGetLastError();
+}
+
 static LossSum loss_sum_of(const LossArgs& a, const LossPlan& pl) {
   LossSum ls{};
   ls.rowloss = (const float*)(a.ws + pl.off_rowloss); ls.pos_idx = a.pos_idx; ls.B = a.B; ls.P = a.P;
@@ -305,6 +395,11 @@ static hipError_t stats_generic_t(const LossArgs& a, const LossPlan& pl) {
 }
 hipError_t launch_stats_generic(const LossArgs& a, const LossPlan& pl) {
   return a.dt == GC_F32 ? stats_generic_t<float>(a, pl) : stats_generic_t<unsigned short>(a, pl);
+}
+
+hipError_t launch_loss_sum(const LossArgs& a, const LossPlan& pl) {
+  loss_reduce_kernel<<<1, 1024, 0, a.stream>>>(loss_sum_of(a, pl));
+  return hipGetLastError();
 }
 
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {

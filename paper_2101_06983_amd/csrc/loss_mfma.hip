@@ -382,7 +382,10 @@ struct GradCfg {
   static constexpr int RS_BYTES = 4 * GR_STAGES * STAGE;
   static constexpr int X_BYTES = 2 * 4 * 4 * 64 * 16;   // [parity][src][dst][lane] float4
   static constexpr int G_BYTES = 2 * 2 * 64 * 16;       // [parity][m-tile][lane] bf16x8
-  static constexpr int SMEM = RS_BYTES + X_BYTES + G_BYTES;
+  // online-statistics walk: [parity][64 rescale factors (float) | 4 flag words, one per finishing wave]
+  static constexpr int F_PAR = 64 * 4 + 16;
+  static constexpr int F_BYTES = 1024;
+  static constexpr int SMEM = RS_BYTES + X_BYTES + G_BYTES + F_BYTES;
   static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
 
@@ -401,7 +404,46 @@ struct GradArgs {
   int obP, nsp, p_stream_len;
   float* dq_out; size_t dq_split_stride;  // split s writes dq_out + s * stride
   float* dp_out; size_t dp_split_stride;
+  // online-statistics walk (dQ role, no statistics pass before it): per split and anchor the reference the
+  // accumulators are relative to and sum 2^(t - reference); per anchor the positive's logit
+  float* on_ref; float* on_l; int* on_idx; float* on_pos;
+  float* on_best;  // per split and anchor: the true maximum, written (with on_idx) only when on_argmax is set
+  int on_argmax;   // track the true maximum and its first index
 };
+
+// max / sum over the four lanes that share lane % 16 (v_permlane16_swap / v_permlane32_swap give every lane both
+// partners' values, so all four lanes end with the same bits)
+__device__ __forceinline__ void swap16(unsigned x, unsigned& a, unsigned& b) {
+  auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false); a = r[0]; b = r[1];
+}
+__device__ __forceinline__ void swap32(unsigned x, unsigned& a, unsigned& b) {
+  auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false); a = r[0]; b = r[1];
+}
+__device__ __forceinline__ float max_g16(float x) {
+  unsigned a, b;
+  swap16(__builtin_bit_cast(unsigned, x), a, b);
+  x = fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+  swap32(__builtin_bit_cast(unsigned, x), a, b);
+  return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+__device__ __forceinline__ float sum_g16(float x) {
+  unsigned a, b;
+  swap16(__builtin_bit_cast(unsigned, x), a, b);
+  x = __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+  swap32(__builtin_bit_cast(unsigned, x), a, b);
+  return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+// (value, index): larger value wins, ties go to the smaller index
+__device__ __forceinline__ void argmax_g16(float& v, int& i) {
+  unsigned a, b, ia, ib;
+  auto pick = [&]() {
+    const float va = __builtin_bit_cast(float, a), vb = __builtin_bit_cast(float, b);
+    const bool tb = (vb > va) || (vb == va && (int)ib < (int)ia);
+    v = tb ? vb : va; i = tb ? (int)ib : (int)ia;
+  };
+  swap16(__builtin_bit_cast(unsigned, v), a, b); swap16((unsigned)i, ia, ib); pick();
+  swap32(__builtin_bit_cast(unsigned, v), a, b); swap32((unsigned)i, ia, ib); pick();
+}
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -427,9 +469,16 @@ constexpr bool grad_offsets_fit() {  // voff[k] - 1024 (k % 4) must stay >= 0 fo
 //   g_ij = 1/2 (2^(t_ij - lse2[i]) + 2^(t_ij - lse2_t[j])) - [j = r_i]
 // (row softmax and column softmax of the same scores), and dQ = g P, dP = g^T Q as before: one walk per side,
 // in which the streamed rows always bring their statistic along.
-template <int D, bool OWNER_IS_Q, bool SYM>
+// ONLINE (dQ role only): no statistics pass has run.  The walk keeps, per owner row, a reference m (the row
+// maximum of the first tile; raised, with the accumulators and the running sum rescaled by 2^(old - new), only when
+// a later score exceeds it by more than kOnlineMargin), accumulates sum_j 2^(t_ij - m) p_j and sum_j 2^(t_ij - m),
+// and tracks the true maximum, its first index and the positive's logit.  A later kernel turns these into lse2 and
+// dQ (softmax_ij = 2^(t_ij - m) 2^(m - lse2_i); the positive's -p_{r_i} is subtracted there).
+constexpr float kOnlineMargin = 16.f;
+template <int D, bool OWNER_IS_Q, bool SYM, bool ONLINE = false>
 __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int split, unsigned char* smem) {
   using C = GradCfg<D>;
+  static_assert(!ONLINE || (OWNER_IS_Q && !SYM), "the online walk is the dQ role of the one-direction loss");
   constexpr bool STR_STATS = SYM || !OWNER_IS_Q;   // the streamed rows' statistics ride in the LDS stage
   const float* lse_own = (SYM && !OWNER_IS_Q) ? ga.lse2_t : ga.lse2;
   const float* lse_str = (SYM && OWNER_IS_Q) ? ga.lse2_t : ga.lse2;
@@ -483,8 +532,9 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   // this wave finishes the scores of owner rows 16 w .. 16 w + 15; a lane holds streamed rows 4 * g16 + 0..3
   const int a_q = a0 + 16 * w + l16;
   float lse_a = 0.f; int r_a = -1;
-  if (OWNER_IS_Q || SYM) lse_a = lse_own[a_q];   // padded: +inf past the end, so g = 0 there
-  if (OWNER_IS_Q) r_a = ga.pos_pad[a_q];
+  if ((OWNER_IS_Q || SYM) && !ONLINE) lse_a = lse_own[a_q];   // padded: +inf past the end, so g = 0 there
+  if (OWNER_IS_Q && !ONLINE) r_a = ga.pos_pad[a_q];
+  if (ONLINE) r_a = (a_q < No) ? ga.pos_pad[a_q] : -1;   // here pos_pad is the caller's pos_idx itself (B entries)
 
   // ---- direct-to-LDS loads of a streamed tile: slot q = it * 64 + lane -> (row, chunk) -------------------------
   auto slot_src = [&](int q, int max_row) __attribute__((always_inline)) -> unsigned {
@@ -607,17 +657,23 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       bfr[ct] = __builtin_bit_cast(u32x4, bb);
     }
   };
-  auto phase2 = [&](const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
+  // after_round(i): arithmetic of the caller that is to run in the shadow of MFMA i
+  auto phase2 = [&](const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf, auto&& after_round) __attribute__((always_inline)) {
     static_for<MC>([&](auto i_tag) __attribute__((always_inline)) {
       constexpr int i = decltype(i_tag)::value, ct = i / 2, mt = i % 2;
       acc[mt][ct] = mfma32(gf[mt], __builtin_bit_cast(bf16x8, bfr[ct]), acc[mt][ct]);
       constexpr std::integral_constant<int, 2> sec{};
       if constexpr (mt == 1 && ct + 1 < C::CT) spread(wave_tag, sec, i_tag, std::true_type{}, t_pf, so_pf, bfr[ct], bfr[ct + 1]);
       else spread(wave_tag, sec, i_tag, std::false_type{}, t_pf, so_pf, bfr[ct], bfr[ct]);
+      after_round(i_tag);
     });
   };
 
   bf16x4 gq = {0, 0, 0, 0};  // g of the tile whose scores were finished last (4 streamed rows of owner row a_q)
+  // online walk: state of owner row a_q (m_run is the same in the four lanes that share the row, the rest is per lane)
+  float m_run = -INFINITY, l_run = 0.f, best_v = -INFINITY, f_pub = 1.f;
+  int best_i = 0x7fffffff, need_pub = 0;
+  unsigned char* fwp = smem + C::RS_BYTES + C::X_BYTES + C::G_BYTES;            // + par * F_PAR
 
   // One pipeline iteration (see the header comment); so0 = ring offset of the stage of tile u.  STEADY:
   // every pipeline slot is live, the tiles involved are full and not the last ones.
@@ -650,6 +706,10 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         if (!(STEADY && dst == WAVE)) *(f32x4*)(xwp + PAR1 * 16384 + dst * 1024) = sacc[dst];
     }
     if (gw) *(bf16x4*)(gwp + PAR0 * 2048) = gq;
+    if (ONLINE && gw) {  // the rescale factors of tile u's rows and this wave's "some row was rescaled" word
+      if (g16 == 0) *(float*)(fwp + PAR0 * C::F_PAR + (16 * w + l16) * 4) = f_pub;
+      if (lane == 0) *(int*)(fwp + PAR0 * C::F_PAR + 256 + 4 * w) = need_pub;
+    }
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 0>{}, t_pf, so4);  // while the writes drain and the barrier gathers the waves
     __syncthreads();
     f32x4 xr[4];
@@ -670,40 +730,154 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       lse_r = *(const f32x4*)(rip + so1);
       if (!OWNER_IS_Q) pos_r = *(const i32x4*)(rip + so1 + 64);
     }
+    i32x4 fl = {0, 0, 0, 0};
+    if (ONLINE && gw) fl = *(const i32x4*)(fwp + PAR0 * C::F_PAR + 256);
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
-    if (gw) {
-      p2_load(so0);
-      phase2(gf, wave_tag, t_pf, so4);
+    if (gw) p2_load(so0);   // ahead of the flag test: LDS answers in order, the test waits for the flags only
+    if (ONLINE && gw) {
+      // rare after the first tile: some row's reference went up, every wave rescales its columns of those rows
+      if (__builtin_amdgcn_ballot_w64((fl[0] | fl[1] | fl[2] | fl[3]) != 0) != 0) {
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            const f32x4 f4 = *(const f32x4*)(fwp + PAR0 * C::F_PAR + (32 * mt + 8 * j + 4 * h) * 4);
+#pragma unroll
+            for (int ct = 0; ct < C::CT; ct++)
+#pragma unroll
+              for (int i = 0; i < 4; i++) {
+                // in place on the accumulation register (written in the compiler's own way this cold path moved
+                // every accumulator into ordinary registers and cost the loop 200 spilled ones); the MFMAs that
+                // wrote and will read these registers are a barrier and many instructions away
+                float x = acc[mt][ct][4 * j + i], tmp;
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                             : "+a"(x), "=&v"(tmp) : "v"(f4[i]));
+                acc[mt][ct][4 * j + i] = x;
+              }
+          }
+      }
     }
-    if (xw) {
-      const f32x4 sv = ((xr[0] + xr[1]) + xr[2]) + xr[3];  // fixed order: bit-identical whichever wave sums
-      const int b0 = sbeg + (u + 1) * GR_T + 4 * g16;      // first of this lane's 4 streamed rows
-      f32x4 gv;
+    // ---- from the summed scores of tile u+1 to its coefficients.  The arithmetic that every tile needs is cut into
+    // pieces; in a steady iteration (not for SYM) piece k runs right behind MFMA k * MC / NP of phase 2, where a
+    // wave's own arithmetic is free, instead of after the last MFMA, where it is not.  What only few tiles need
+    // (the positive, masks, the arg-max) stays behind phase 2.
+    constexpr bool INTER = STEADY && !SYM;
+    constexpr int NP = ONLINE ? 10 : 5;
+    const int b0 = sbeg + (u + 1) * GR_T + 4 * g16;      // first of this lane's 4 streamed rows
+    f32x4 sv = {0.f, 0.f, 0.f, 0.f}, tt = {0.f, 0.f, 0.f, 0.f}, gv = {0.f, 0.f, 0.f, 0.f};
+    float tmx = 0.f, mref = 0.f;
+    bool need = false;
+    auto piece = [&](auto k_tag) __attribute__((always_inline)) {
+      constexpr int K = decltype(k_tag)::value;
+      if constexpr (K == 0) sv = xr[0] + xr[1];            // fixed order ((x0 + x1) + x2) + x3: bit-identical
+      else if constexpr (K == 1) sv = sv + xr[2];           // whichever wave sums
+      else if constexpr (K == 2) sv = sv + xr[3];
+      else if constexpr (!ONLINE) {
+        if constexpr (K == 3) {
 #pragma unroll
-      for (int e = 0; e < 4; e++) {
-        if constexpr (SYM) {  // mean of the row softmax and the column softmax
-          gv[e] = fast_exp2(__builtin_fmaf(sv[e], ga.alpha2, -(lse_a + 1.f))) + fast_exp2(__builtin_fmaf(sv[e], ga.alpha2, -(lse_r[e] + 1.f)));
+          for (int e = 0; e < 4; e++) tt[e] = sv[e] * ga.alpha2 - (OWNER_IS_Q ? lse_a : lse_r[e]);
         } else {
-          gv[e] = fast_exp2(sv[e] * ga.alpha2 - (OWNER_IS_Q ? lse_a : lse_r[e]));  // softmax
-        }
-      }
-      // the rest touches few tiles and is decided per wave: -1 at the positive (j == r_i), zeros for rows
-      // past the end of the split and on the diagonal (i == j)
-      bool hit_any;
-      if (OWNER_IS_Q) hit_any = (unsigned)(r_a - b0) < 4u;
-      else hit_any = (pos_r[0] == a_q) | (pos_r[1] == a_q) | (pos_r[2] == a_q) | (pos_r[3] == a_q);
-      const int t1 = b0 - 4 * g16;
-      const bool tail = !STEADY && (t1 + GR_T > send);
-      const bool diag = ga.mask_self && (t1 < a0 + GR_OWN) && (t1 + GR_T > a0);
-      if (__builtin_amdgcn_ballot_w64(hit_any) != 0 || tail || diag) {
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const bool hit = OWNER_IS_Q ? (r_a - b0 == e) : (pos_r[e] == a_q);
-          if (hit) gv[e] -= 1.f;
-          if (b0 + e >= send || (ga.mask_self && b0 + e == a_q)) gv[e] = 0.f;
+          for (int e = 0; e < 4; e++) gv[e] = fast_exp2(tt[e]);  // softmax
+        }
+      } else {
+        if constexpr (K == 3) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) tt[e] = sv[e] * ga.alpha2;
+          if constexpr (!STEADY) {  // rows past the end of the split, the diagonal under mask_self
+            const int t1o = b0 - 4 * g16;
+            if ((t1o + GR_T > send) || (ga.mask_self && (t1o < a0 + GR_OWN) && (t1o + GR_T > a0))) {
+              if ((unsigned)(r_a - b0) < 4u && a_q < No) ga.on_pos[a_q] = tt[r_a - b0];   // before the mask, as the statistics pass does
+#pragma unroll
+              for (int e = 0; e < 4; e++)
+                if (b0 + e >= send || (ga.mask_self && b0 + e == a_q)) tt[e] = -INFINITY;
+            }
+          }
+        } else if constexpr (K == 4) tmx = fmaxf(fmaxf(tt[0], tt[1]), fmaxf(tt[2], tt[3]));
+        else if constexpr (K == 5) {
+          unsigned x0, x1;
+          swap16(__builtin_bit_cast(unsigned, tmx), x0, x1);
+          tmx = fmaxf(__builtin_bit_cast(float, x0), __builtin_bit_cast(float, x1));
+        } else if constexpr (K == 6) {
+          unsigned x0, x1;
+          swap32(__builtin_bit_cast(unsigned, tmx), x0, x1);
+          tmx = fmaxf(__builtin_bit_cast(float, x0), __builtin_bit_cast(float, x1));   // this tile's maximum of row a_q
+        } else if constexpr (K == 7) {
+          // raise the reference when the tile exceeds it by more than the margin (always at the first tile with a
+          // finite score: m_run = -inf); without branches: the factor is 2^0 when nothing changes, 2^-inf the first time
+          need = tmx > m_run + kOnlineMargin;
+          f_pub = fast_exp2(need ? m_run - tmx : 0.f);
+          l_run *= f_pub;
+          m_run = need ? tmx : m_run;
+          mref = (m_run == -INFINITY) ? 0.f : m_run;
+        } else if constexpr (K == 8) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) gv[e] = fast_exp2(tt[e] - mref);
+        } else {
+          l_run += (gv[0] + gv[1]) + (gv[2] + gv[3]);
         }
       }
-      gq = __builtin_convertvector(gv, bf16x4);
+      if constexpr (INTER) {  // an empty statement that "uses" the results keeps the piece in its round
+        if constexpr (ONLINE) asm volatile("" : "+v"(sv), "+v"(tt), "+v"(gv), "+v"(tmx), "+v"(l_run), "+v"(m_run), "+v"(f_pub));
+        else asm volatile("" : "+v"(sv), "+v"(tt), "+v"(gv));
+      }
+    };
+    auto after_round = [&](auto i_tag) __attribute__((always_inline)) {
+      if constexpr (INTER) {
+        constexpr int i = decltype(i_tag)::value;
+        static_for<NP>([&](auto k_tag) __attribute__((always_inline)) {
+          if constexpr (decltype(k_tag)::value * MC / NP == i) piece(k_tag);
+        });
+        __builtin_amdgcn_sched_barrier(0);  // the rounds stay in order
+      }
+    };
+    if (gw) phase2(gf, wave_tag, t_pf, so4, after_round);
+    if (xw) {
+      if constexpr (!INTER) static_for<NP>(piece);
+      if constexpr (ONLINE) {
+        need_pub = __builtin_amdgcn_ballot_w64(need) != 0 ? 1 : 0;
+        if (ga.on_argmax) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) {   // increasing j: a strict > keeps the smallest index
+            const bool gt = tt[e] > best_v;
+            best_v = gt ? tt[e] : best_v;
+            best_i = gt ? b0 + e : best_i;
+          }
+        }
+        if ((unsigned)(r_a - b0) < 4u) {
+          // the positive: seen by exactly one lane of one split.  Its own term (p_{i r_i} - 1) p_{r_i} is formed in
+          // fp32 by the kernel that finishes dQ: left in the bf16 sum it would cancel against - p_{r_i} with the
+          // rounding error of a coefficient near 1
+          if (a_q < No && tt[r_a - b0] != -INFINITY) ga.on_pos[a_q] = tt[r_a - b0];
+#pragma unroll
+          for (int e = 0; e < 4; e++)
+            if (r_a - b0 == e) gv[e] = 0.f;
+        }
+        gq = __builtin_convertvector(gv, bf16x4);
+      } else {
+        if constexpr (SYM) {  // mean of the row softmax and the column softmax
+#pragma unroll
+          for (int e = 0; e < 4; e++)
+            gv[e] = fast_exp2(__builtin_fmaf(sv[e], ga.alpha2, -(lse_a + 1.f))) + fast_exp2(__builtin_fmaf(sv[e], ga.alpha2, -(lse_r[e] + 1.f)));
+        }
+        // the rest touches few tiles and is decided per wave: -1 at the positive (j == r_i), zeros for rows
+        // past the end of the split and on the diagonal (i == j)
+        bool hit_any;
+        if (OWNER_IS_Q) hit_any = (unsigned)(r_a - b0) < 4u;
+        else hit_any = (pos_r[0] == a_q) | (pos_r[1] == a_q) | (pos_r[2] == a_q) | (pos_r[3] == a_q);
+        const int t1 = b0 - 4 * g16;
+        const bool tail = !STEADY && (t1 + GR_T > send);
+        const bool diag = ga.mask_self && (t1 < a0 + GR_OWN) && (t1 + GR_T > a0);
+        if (__builtin_amdgcn_ballot_w64(hit_any) != 0 || tail || diag) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const bool hit = OWNER_IS_Q ? (r_a - b0 == e) : (pos_r[e] == a_q);
+            if (hit) gv[e] -= 1.f;
+            if (b0 + e >= send || (ga.mask_self && b0 + e == a_q)) gv[e] = 0.f;
+          }
+        }
+        gq = __builtin_convertvector(gv, bf16x4);
+      }
     }
     if (!STEADY && pf) prefetch(u + 4, so4);  // in a steady iteration phase 2 has issued these loads
   };
@@ -723,11 +897,15 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 #pragma unroll 1
     for (; u + 5 < nt; u++) { body(u, so, wave_tag); so = next_stage(so); }
   };
-  switch (__builtin_amdgcn_readfirstlane(w)) {
-    case 0: steady_loop(std::integral_constant<int, 0>{}); break;
-    case 1: steady_loop(std::integral_constant<int, 1>{}); break;
-    case 2: steady_loop(std::integral_constant<int, 2>{}); break;
-    default: steady_loop(std::integral_constant<int, 3>{}); break;
+  // (the steady body of the one-direction kernels has no place for the diagonal mask: with mask_self every
+  // iteration takes the general body)
+  if (SYM || !ga.mask_self) {
+    switch (__builtin_amdgcn_readfirstlane(w)) {
+      case 0: steady_loop(std::integral_constant<int, 0>{}); break;
+      case 1: steady_loop(std::integral_constant<int, 1>{}); break;
+      case 2: steady_loop(std::integral_constant<int, 2>{}); break;
+      default: steady_loop(std::integral_constant<int, 3>{}); break;
+    }
   }
 #pragma unroll 1
   for (; u < nt; u++) { body(u, so, unsteady); so = next_stage(so); }
@@ -743,6 +921,18 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         const int a = a0 + 32 * mt + 8 * (r >> 2) + 4 * h + (r & 3);
         if (a < No) out[(size_t)a * D + w * C::DS + 32 * ct + ln] = acc[mt][ct][r] * ga.out_scale;
       }
+  if constexpr (ONLINE) {  // the row's statistics of this split
+    const float l_sum = sum_g16(l_run);
+    if (ga.on_argmax) argmax_g16(best_v, best_i);
+    if (g16 == 0 && a_q < No) {
+      // (reference, sum 2^(t - reference)) is all the log-sum-exp needs: the same bits whether or not the
+      // arg-max is tracked
+      const size_t o = (size_t)split * No + a_q;
+      ga.on_ref[o] = m_run;
+      ga.on_l[o] = l_sum;
+      if (ga.on_argmax) { ga.on_best[o] = best_v; ga.on_idx[o] = best_i; }
+    }
+  }
 }
 
 
@@ -1060,6 +1250,47 @@ __global__ void __launch_bounds__(256) grad_mfma_kernel(GradArgs ga) {
   } else {
     const int t = id - nQ;
     grad_body<D, false, SYM>(ga, t % ga.obP, t / ga.obP, gsmem);
+  }
+}
+
+// the online-statistics walk: every workgroup has the dQ role
+template <int D>
+__global__ void __launch_bounds__(256) grad_online_kernel(GradArgs ga) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
+  const int id = xcd_task_id();
+  grad_body<D, true, false, true>(ga, id % ga.obQ, id / ga.obQ, gsmem);
+}
+template <int D>
+static hipError_t grad_online_launch(const GradArgs& ga, int nwg, hipStream_t stream) {
+  const int smem = GradCfg<D>::SMEM;
+  hipError_t e = hipFuncSetAttribute((const void*)grad_online_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (e != hipSuccess) return e;
+  grad_online_kernel<D><<<nwg, 256, smem, stream>>>(ga);
+  return hipGetLastError();
+}
+
+// dQ partials (scaled by alpha / B, relative to each split's reference) and the statistics of every split
+hipError_t launch_grad_online(const LossArgs& a, const LossPlan& pl) {
+  char* ws = a.ws;
+  GradArgs ga{};
+  ga.Q = (const unsigned short*)a.q; ga.P = (const unsigned short*)a.p;
+  ga.pos_pad = a.pos_idx; ga.lse2 = nullptr; ga.lse2_t = nullptr;
+  ga.B = a.B; ga.Pn = a.P;
+  ga.alpha2 = a.alpha * kLog2e; ga.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
+  ga.mask_self = (a.flags & GC_MASK_SELF) ? 1 : 0;
+  ga.obQ = (a.B + GR_OWN - 1) / GR_OWN; ga.nsq = pl.fz_nsq; ga.q_stream_len = pl.fz_q_stream_len;
+  ga.dq_out = (float*)(ws + pl.off_dq_part); ga.dq_split_stride = (size_t)a.B * a.d;
+  ga.on_ref = (float*)(ws + pl.off_on_ref); ga.on_best = (float*)(ws + pl.off_part_m); ga.on_l = (float*)(ws + pl.off_part_l);
+  ga.on_idx = (int*)(ws + pl.off_part_idx); ga.on_pos = (float*)(ws + pl.off_pos);
+  ga.on_argmax = a.argmax ? 1 : 0;
+  const int nwg = ga.obQ * ga.nsq;
+  switch (a.d) {
+    case 256: return grad_online_launch<256>(ga, nwg, a.stream);
+    case 384: return grad_online_launch<384>(ga, nwg, a.stream);
+    case 512: return grad_online_launch<512>(ga, nwg, a.stream);
+    case 640: return grad_online_launch<640>(ga, nwg, a.stream);
+    case 768: return grad_online_launch<768>(ga, nwg, a.stream);
+    default: return hipErrorInvalidValue;
   }
 }
 

@@ -97,8 +97,11 @@ def test_bf16_shapes_and_edges(B, P, d, scale, temp):
         # the MFMA kernels round the coefficients g_ij to bf16: against the definition with that one rounding
         # the agreement is an order of magnitude closer
         same_g = O.loss_and_rep_grad(synth.widen(q), synth.widen(p), r.numpy(), scale, temp, g_dtype="bf16")
-        assert normerr(to_np(out["dq"]), same_g["dq"]) <= TOL_SAME_G
         assert normerr(to_np(out["dp"]), same_g["dp"]) <= TOL_SAME_G
+        # from d = 256 on dQ comes from the walk that forms the statistics as it goes: it rounds 2^(t - reference),
+        # not g, and adds the positive's term in fp32, so the same-coefficient oracle is not its model
+        if d < 256:
+            assert normerr(to_np(out["dq"]), same_g["dq"]) <= TOL_SAME_G
 
 
 @pytest.mark.parametrize("B,P,d,temp", [(700, 1400, 128, 0.07), (500, 1000, 256, 0.05), (384, 2000, 768, 0.05)])
@@ -114,7 +117,8 @@ def test_peaked_softmax_at_low_temperature(B, P, d, temp):
     assert relerr(to_np(out["lse"]), want["lse"]) <= 1e-5
     for k in ("dq", "dp"):
         assert relerr(to_np(out[k]), want[k]) <= TOL_BF16_PEAKED
-        assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
+        if k == "dp" or d < 256:   # see test_bf16_shapes_and_edges
+            assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
 
 
 @pytest.mark.parametrize("B,P,d,dtype", [(200, 700, 256, torch.bfloat16), (90, 300, 768, torch.bfloat16),
@@ -153,15 +157,22 @@ def test_mask_self(n, d, dtype):
 
 
 def test_optional_outputs_and_reuse_of_workspace():
+    """Asking for fewer outputs changes which kernels run (with dQ the statistics come from the dQ walk itself,
+    without it from the statistics pass), so across such calls the results agree to fp32 rounding, not bit for bit;
+    the same call twice does."""
     q, p, r = synth.config2()
     qd, pd, rd = q.to(DEV), p.to(DEV), r.to(DEV)
     full = gc.gc_loss_and_rep_grad_ex(qd, pd, rd)
     only = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("loss",), workspace=full["workspace"])
     torch.cuda.synchronize()
-    assert only["loss"].item() == full["loss"].item()
+    assert abs(only["loss"].item() - full["loss"].item()) <= 1e-6 * abs(full["loss"].item())
     only_dp = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("dp",), workspace=full["workspace"])
+    again_dp = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("dp",), workspace=full["workspace"])
+    only_dq = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("loss", "dq"), workspace=full["workspace"])
     torch.cuda.synchronize()
-    assert torch.equal(only_dp["dp"], full["dp"])
+    assert relerr(to_np(only_dp["dp"]), to_np(full["dp"])) <= 1e-5
+    assert torch.equal(only_dp["dp"], again_dp["dp"])
+    assert torch.equal(only_dq["dq"], full["dq"]) and only_dq["loss"].item() == full["loss"].item()
 
 
 def test_pos_idx_out_of_range_is_reported_not_faulted():
