@@ -3,17 +3,20 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
 
-A step is one pass of the loss + representation-gradient path (statistics pass,
-merge, gradient pass, partial sums) over one synthetic batch of the headline
-workload: B=4096 queries, P=8192 passages, d=768, bf16 storage, fp32 accumulate.
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+A step is one pass of the loss + representation-gradient path (dQ walk that forms
+the row statistics as it goes, merge of its splits into lse / loss rows / dQ, dP
+walk, partial sums + loss sum) over one synthetic batch of the headline workload:
+B=4096 queries, P=8192 passages, d=768, bf16 storage, fp32 accumulate.  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
 
 value      algorithmic TFLOP/s = 6*B*P*d / step time (three GEMMs: S, G*P, G^T*Q)
-roofline   for the dominant kernel (the gradient kernel): algorithmic flops of one
-           launch (4*B*P*d: the two gradient contractions) / its mean duration from
-           HIP events recorded by the library on the launch stream, against the
-           MI355X dense bf16 MFMA peak.  `executed_frac` counts the recomputed
-           score tiles as well (8*B*P*d flops per launch).
+roofline   for the dominant kernel (the dQ walk, grad_online_kernel<768>): the
+           algorithmic flops of one launch (4*B*P*d: the scores and G*P, both of
+           which it forms exactly once) / its mean duration from HIP events recorded
+           by the library on the launch stream, against the MI355X dense bf16 MFMA
+           peak.  The dP walk (2*B*P*d algorithmic, 4*B*P*d executed: it forms the
+           scores again) is listed beside it; `whole_path_executed_frac` counts all
+           8*B*P*d executed flops of a step.
 cpu_baseline  the fp64 numpy oracle timed on the host cores on the same batch.
 """
 import argparse
@@ -28,10 +31,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-# HBM bytes per gradient-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# readings of a plain 1 GiB read + 1 GiB write kernel (profiles/loss_path_config3_rocprofv3.txt):
-# 76.1 MB read + 50.3 MB written.
-TRAFFIC_BYTES = 126.6e6
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
+# readings of a plain 1 GiB read + 1 GiB write kernel (profiles/loss_path_config3_rocprofv3.txt)
+TRAFFIC_BYTES = 101.7e6   # 51.2 MB read + 50.5 MB written
 
 
 def cpu_baseline(q, p, r, flops):
@@ -169,9 +171,11 @@ def main():
     ms = (t1 - t0) * 1e3 / args.steps
     flops_alg = 6.0 * B * P * d
     value = flops_alg / (ms * 1e-3) / 1e12
-    k_alg = 4.0 * B * P * d          # G*P and G^T*Q
-    k_exe = 8.0 * B * P * d          # + the score tile recomputed in both walks
-    achieved = k_alg / (prof["ms_grad"] * 1e-3) / 1e12
+    # profile marks in fused mode: ms_stats = dQ walk with online statistics, ms_merge = merge of its splits,
+    # ms_grad = dP walk, ms_reduce = partial sums + loss sum
+    k_alg = 4.0 * B * P * d          # dQ walk: S and G*P, each formed once
+    achieved = k_alg / (prof["ms_stats"] * 1e-3) / 1e12
+    dp_alg = 2.0 * B * P * d / (prof["ms_grad"] * 1e-3) / 1e12
     rec = {
         "metric": "loss+rep-grad TFLOP/s & ms/step at B=4096,P=8192,d=768 bf16; % MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -180,12 +184,16 @@ def main():
         "config": {"workload": "config3 large-batch ICT-shaped: B=4096 queries, P=8192 passages, d=768, bf16 storage, "
                                "fp32 accumulate, pos_idx[i]=2i, iid N(0,1/d)", "B": B, "P": P, "d": d,
                    "loss": float(out["loss"].item())},
-        "roofline": {"bound": "mfma", "kernel": "grad_mfma_kernel<768>", "achieved": round(achieved, 2),
+        "roofline": {"bound": "mfma", "kernel": "grad_online_kernel<768> (dQ walk with online statistics)",
+                     "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": TRAFFIC_BYTES,
-                     "executed_frac": round(k_exe / (prof["ms_grad"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                     "kernel_ms": {k: round(prof[k], 4) for k in ("ms_stats", "ms_merge", "ms_grad", "ms_reduce")},
-                     "whole_path_executed_frac": round(10.0 * B * P * d / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "dp_walk": {"kernel": "grad_mfma_kernel<768, false>", "achieved": round(dp_alg, 2),
+                                 "frac": round(dp_alg / PEAK_BF16_TFLOPS, 4),
+                                 "executed_frac": round(2 * dp_alg / PEAK_BF16_TFLOPS, 4)},
+                     "kernel_ms": {"dq_walk_online": round(prof["ms_stats"], 4), "merge_and_dq": round(prof["ms_merge"], 4),
+                                   "dp_walk": round(prof["ms_grad"], 4), "partial_sums_and_loss": round(prof["ms_reduce"], 4)},
+                     "whole_path_executed_frac": round(8.0 * B * P * d / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                      # a bare MFMA loop on operands of random data sustains this on the box (the published peak
                      # is reached only when every MFMA reads the same constant registers)
                      "mfma_rate_measured_with_random_operands": 1850.0},

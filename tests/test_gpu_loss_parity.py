@@ -147,6 +147,36 @@ def test_very_large_logits_neither_overflow_nor_vanish(B, P, d, dtype):
     assert np.array_equal(to_np(out["argmax"]), want["argmax"])
 
 
+@pytest.mark.parametrize("order", ["rising", "falling"])
+@pytest.mark.parametrize("B,P,d", [(200, 2000, 256), (70, 3000, 768)])
+def test_scores_that_rise_or_fall_along_the_stream(B, P, d, order):
+    """Logits that grow steadily along the targets (about 7 in base 2 per 16-row tile, 600 in all): the walk that
+    forms the statistics as it goes has to raise its per-row reference, and rescale what it has accumulated, every
+    few tiles; falling, it keeps the first reference and most later terms underflow to nothing."""
+    g = np.random.default_rng(2800 + B)
+    u = g.standard_normal(d) / np.sqrt(d)
+    ramp = np.linspace(0.0, 1.0, P) if order == "rising" else np.linspace(1.0, 0.0, P)
+    q = torch.tensor(u[None, :] + 0.05 * g.standard_normal((B, d)) / np.sqrt(d), dtype=torch.float32).to(torch.bfloat16)
+    p = torch.tensor(ramp[:, None] * u[None, :] + 0.05 * g.standard_normal((P, d)) / np.sqrt(d), dtype=torch.float32).to(torch.bfloat16)
+    r = torch.from_numpy(g.integers(0, P, size=B).astype(np.int32))
+    scale = 600.0
+    q64, p64 = synth.widen(q), synth.widen(p)
+    want = O.loss_and_rep_grad(q64, p64, r.numpy(), scale, 1.0)
+    out = run_ex(q, p, r, scale, 1.0)
+    for k in ("loss", "dq", "dp", "lse"):
+        assert torch.isfinite(out[k]).all(), k
+    assert abs(out["loss"].item() - want["loss"]) <= 1e-4 * abs(want["loss"])
+    assert relerr(to_np(out["lse"]), want["lse"]) <= 1e-5
+    t_max = np.abs(scale * q64 @ p64.T).max() * math.log2(math.e)
+    g_err = 2.0 ** -8 + 4 * 2.0 ** -24 * t_max            # bf16 coefficient + fp32 exponent, see the large-logit test
+    assert np.abs(to_np(out["dq"]) - want["dq"]).max() <= scale / B * np.abs(p64).max() * g_err * 4
+    # every anchor's softmax sits on the same few targets here, so a row of dP sums B coefficients of size 1: their
+    # errors add like a random walk
+    assert np.abs(to_np(out["dp"]) - want["dp"]).max() <= scale / B * np.abs(q64).max() * g_err * 4 * math.sqrt(B)
+    amb = check_argmax(to_np(out["argmax"]), want, q64, p64, scale, 1e-3)
+    assert amb <= 2
+
+
 @pytest.mark.parametrize("n,d,dtype", [(96, 128, torch.bfloat16), (70, 24, torch.float32), (322, 256, torch.bfloat16)])
 def test_mask_self(n, d, dtype):
     q, p, _ = synth.dpr_batch(n, n, d, dtype, seed=3000 + n)
