@@ -733,6 +733,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     i32x4 fl = {0, 0, 0, 0};
     if (ONLINE && gw) fl = *(const i32x4*)(fwp + PAR0 * C::F_PAR + 256);
     if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
+    if constexpr (ONLINE) __builtin_amdgcn_sched_barrier(0);  // the flag test (and its wait for LDS) stays behind these MFMAs
     if (gw) p2_load(so0);   // ahead of the flag test: LDS answers in order, the test waits for the flags only
     if (ONLINE && gw) {
       // rare after the first tile: some row's reference went up, every wave rescales its columns of those rows
