@@ -10,6 +10,9 @@ B=4096 queries, P=8192 passages, d=768, bf16 storage, fp32 accumulate.  Inputs a
 resident in HBM before the timed region.  Prints ONE JSON line.
 
 value      algorithmic TFLOP/s = 6*B*P*d / step time (three GEMMs: S, G*P, G^T*Q)
+           K steps are timed with nothing else on the stream; the kernel times below
+           come from a second pass of K steps with HIP events at the kernel boundaries
+           (the event records cost about 6 % of a step).
 roofline   for the dominant kernel (the dQ walk, grad_online_kernel<768>): the
            algorithmic flops of one launch (4*B*P*d: the scores and G*P, both of
            which it forms exactly once) / its mean duration from HIP events recorded
@@ -158,13 +161,22 @@ def main():
             torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    gc.gc_profile_begin(args.steps)
+    # timed region: exactly K steps, nothing else on the stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # kernel durations: the same K steps again with the library's HIP events at the kernel boundaries (on the launch
+    # stream).  Five event records per step cost about 6 % of a step, so they stay out of the timed region above.
+    gc.gc_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
     prof = gc.gc_profile_end()
     assert gc.gc_check_async_error(ws) == gc.GC_OK
 
@@ -193,6 +205,8 @@ def main():
                                  "executed_frac": round(2 * dp_alg / PEAK_BF16_TFLOPS, 4)},
                      "kernel_ms": {"dq_walk_online": round(prof["ms_stats"], 4), "merge_and_dq": round(prof["ms_merge"], 4),
                                    "dp_walk": round(prof["ms_grad"], 4), "partial_sums_and_loss": round(prof["ms_reduce"], 4)},
+                     "kernel_ms_from": "HIP events on the launch stream over a second pass of the same %d steps "
+                                       "(%.4f ms/step with the events recorded)" % (args.steps, (t3 - t2) * 1e3 / args.steps),
                      "whole_path_executed_frac": round(8.0 * B * P * d / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                      # a bare MFMA loop on operands of random data sustains this on the box (the published peak
                      # is reached only when every MFMA reads the same constant registers)
