@@ -56,6 +56,11 @@ typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
 
 /* flags of gc_loss_and_rep_grad_ex */
 #define GC_MASK_SELF 1u /* s_ii = -inf (needs B == P >= 2): an anchor is never its own target */
+/* Which kernel sequence serves a call is chosen from the shape; these two override the choice where both exist
+ * (bf16, d a multiple of 128 from 256 to 768, dq asked for) and are ignored elsewhere.  For tests and measurements:
+ * the results of the two sequences agree to fp32 rounding, not bit for bit. */
+#define GC_PATH_ONLINE 2u     /* the dQ walk forms the row statistics itself, no statistics pass */
+#define GC_PATH_STATS_PASS 4u /* statistics pass, then both gradient walks in one launch */
 
 /* Text for a gc_status value (host; static storage, never NULL). */
 const char* gc_strerror(int status);
@@ -87,7 +92,7 @@ int gc_loss_and_rep_grad_f32(const float* q, const float* p, const int32_t* pos_
 /*
  * Extended form of the same computation.
  *   dt         type of q and p
- *   flags      0 or GC_MASK_SELF
+ *   flags      0 or GC_MASK_SELF, optionally with one of GC_PATH_ONLINE / GC_PATH_STATS_PASS
  *   loss, dq, dp, lse, argmax   each may be NULL (not produced).  lse[B] float is
  *              logsumexp_j s_ij; argmax[B] int32 is the smallest j that attains
  *              max_j s_ij in the kernel's fp32 scores.

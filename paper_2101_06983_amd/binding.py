@@ -16,6 +16,7 @@ GC_OK = 0
 GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_POS_IDX, GC_ERR_HIP = -1, -2, -3, -4, -5, -6
 GC_F32, GC_BF16 = 0, 1
 GC_MASK_SELF = 1
+GC_PATH_ONLINE, GC_PATH_STATS_PASS = 2, 4
 
 EXPORTS = [
     "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",

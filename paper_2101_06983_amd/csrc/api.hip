@@ -41,8 +41,14 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
     split_of(P, pl.nsq, pl.q_stream_len);
     split_of(B, pl.nsp, pl.p_stream_len);
     if (pl.one_walk) { pl.nsp = 1; pl.p_stream_len = B; }
-    // fused mode: each walk is a launch of its own and has to fill the GPU alone
+    // fused mode (workspace is planned for it wherever it can run; fused_auto says where it is also the faster one):
+    // each walk is a launch of its own and has to fill the GPU alone
+    // (it pays where the statistics pass it replaces is expensive against the extra partial sums: measured faster
+    // from d = 512 and 2^24 scores up, e.g. 0.251 against 0.261 ms at config 3 and 0.156 against 0.226 ms at
+    // B = 1024, P = 16384, and slower below, where launches and partials dominate)
+    // d = 384: a tie at config 3's size, 0.110 against 0.153 ms at B = 1024, P = 16384)
     pl.fused = (d >= 256 && !ntxent) ? 1 : 0;
+    pl.fused_auto = (pl.fused && d >= 384 && (long long)B * P >= (1ll << 24)) ? 1 : 0;
     if (pl.fused) {
       auto split_alone = [&](long long own_blocks, int n, int& ns, int& len) {
         long long La = (own_blocks * n + kNumCU - 1) / kNumCU;
@@ -135,9 +141,6 @@ static void prof_mark(int call, int mark, hipStream_t s) {
 void prof_mark_grad_kernel_done(hipStream_t s) { prof_mark(g_prof.calls, 3, s); }
 bool prof_active() { return g_prof.on; }
 
-// GC_NO_FUSED=1 in the environment keeps the statistics-pass path for every call (measurement aid)
-static const bool g_no_fused = [] { const char* e = getenv("GC_NO_FUSED"); return e && e[0] == '1'; }();
-
 static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   LossArgs a = a_in;
   // does the gradient pass of this call end in a sum of split partials (launch_grad_mfma)?
@@ -146,7 +149,8 @@ static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
   hipError_t e;
-  if (pl.fused && a.dq && !a.dz && !a.lse2_t && !g_no_fused) {
+  const bool want_online = (a.flags & GC_PATH_ONLINE) || (pl.fused_auto && !(a.flags & GC_PATH_STATS_PASS));
+  if (pl.fused && want_online && a.dq && !a.dz && !a.lse2_t) {
     // fused mode: online-statistics dQ walk | merge of its splits (lse2, row losses, dQ) | dP walk | partial sums
     e = launch_grad_online(a, pl);
     if (e != hipSuccess) return GC_ERR_HIP;
@@ -200,7 +204,8 @@ static int check_loss_args(gc_dtype dt, const void* q, const void* p, const int3
   if (!(scale > 0.f) || !(temp > 0.f) || !std::isfinite(scale) || !std::isfinite(temp)) return GC_ERR_SHAPE;
   if (!std::isfinite(scale / temp) || !(scale / temp > 0.f)) return GC_ERR_SHAPE;
   if (dt != GC_F32 && dt != GC_BF16) return GC_ERR_UNSUPPORTED;
-  if (flags & ~GC_MASK_SELF) return GC_ERR_UNSUPPORTED;
+  if (flags & ~(GC_MASK_SELF | GC_PATH_ONLINE | GC_PATH_STATS_PASS)) return GC_ERR_UNSUPPORTED;
+  if ((flags & GC_PATH_ONLINE) && (flags & GC_PATH_STATS_PASS)) return GC_ERR_UNSUPPORTED;
   if ((flags & GC_MASK_SELF) && (B != P || P < 2)) return GC_ERR_SHAPE;
   return GC_OK;
 }

@@ -51,7 +51,7 @@ struct LossPlan {
   int b_pad;             // B rounded up to 64: length of the padded lse2 / pos_pad arrays
   // fused mode (MFMA kernels, d >= 256, dQ wanted): no statistics pass; an online-statistics dQ walk, a kernel that
   // merges its splits into lse2 and dQ, then the dP walk.  Each walk fills the GPU alone, so they have splits of their own
-  int fused, fz_nsq, fz_nsp, fz_q_stream_len, fz_p_stream_len;
+  int fused, fused_auto, fz_nsq, fz_nsp, fz_q_stream_len, fz_p_stream_len;   // can run / is chosen without a flag
   size_t off_err, off_part_m, off_part_l, off_part_idx, off_pos, off_lse2, off_pos_pad, off_rowloss, off_dq_part,
       off_dp_part, off_pos_idx, off_on_ref, total;
 };

@@ -16,6 +16,10 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+# the two kernel sequences of the bf16 MFMA shapes from d = 256 (the flag is ignored where only one exists)
+PATHS = [gc.GC_PATH_ONLINE, gc.GC_PATH_STATS_PASS]
+
+
 def run_ex(q, p, r, scale=1.0, temp=1.0, flags=0):
     out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), scale, temp, flags)
     torch.cuda.synchronize()
@@ -88,20 +92,21 @@ def test_bf16_shapes_and_edges(B, P, d, scale, temp):
     g = np.random.default_rng(B + P)
     r = torch.from_numpy(g.integers(0, P, size=B).astype(np.int32))
     want = oracle_loss(q, p, r, scale, temp)
-    out = run_ex(q, p, r, scale, temp)
-    if P == 1:
-        assert out["loss"].item() == 0.0
-        assert float(out["dq"].abs().max()) == 0.0 and float(out["dp"].abs().max()) == 0.0
-    compare(out, want, TOL_BF16, q, p, scale / temp)
-    if d % 128 == 0 and P > 1:
-        # the MFMA kernels round the coefficients g_ij to bf16: against the definition with that one rounding
-        # the agreement is an order of magnitude closer
-        same_g = O.loss_and_rep_grad(synth.widen(q), synth.widen(p), r.numpy(), scale, temp, g_dtype="bf16")
-        assert normerr(to_np(out["dp"]), same_g["dp"]) <= TOL_SAME_G
-        # from d = 256 on dQ comes from the walk that forms the statistics as it goes: it rounds 2^(t - reference),
-        # not g, and adds the positive's term in fp32, so the same-coefficient oracle is not its model
-        if d < 256:
-            assert normerr(to_np(out["dq"]), same_g["dq"]) <= TOL_SAME_G
+    for path in PATHS:
+        out = run_ex(q, p, r, scale, temp, flags=path)
+        if P == 1:
+            assert out["loss"].item() == 0.0
+            assert float(out["dq"].abs().max()) == 0.0 and float(out["dp"].abs().max()) == 0.0
+        compare(out, want, TOL_BF16, q, p, scale / temp)
+        if d % 128 == 0 and P > 1:
+            # the MFMA kernels round the coefficients g_ij to bf16: against the definition with that one rounding
+            # the agreement is an order of magnitude closer
+            same_g = O.loss_and_rep_grad(synth.widen(q), synth.widen(p), r.numpy(), scale, temp, g_dtype="bf16")
+            assert normerr(to_np(out["dp"]), same_g["dp"]) <= TOL_SAME_G
+            # the walk that forms the statistics as it goes rounds 2^(t - reference), not g, and adds the positive's
+            # term in fp32, so the same-coefficient oracle is not the model of its dQ
+            if d < 256 or path == gc.GC_PATH_STATS_PASS:
+                assert normerr(to_np(out["dq"]), same_g["dq"]) <= TOL_SAME_G
 
 
 @pytest.mark.parametrize("B,P,d,temp", [(700, 1400, 128, 0.07), (500, 1000, 256, 0.05), (384, 2000, 768, 0.05)])
@@ -112,18 +117,20 @@ def test_peaked_softmax_at_low_temperature(B, P, d, temp):
     q64, p64 = synth.widen(q), synth.widen(p)
     want = O.loss_and_rep_grad(q64, p64, r.numpy(), 1.0, temp)
     same_g = O.loss_and_rep_grad(q64, p64, r.numpy(), 1.0, temp, g_dtype="bf16")
-    out = run_ex(q, p, r, 1.0, temp)
-    assert abs(out["loss"].item() - want["loss"]) <= 1e-5 * abs(want["loss"])
-    assert relerr(to_np(out["lse"]), want["lse"]) <= 1e-5
-    for k in ("dq", "dp"):
-        assert relerr(to_np(out[k]), want[k]) <= TOL_BF16_PEAKED
-        if k == "dp" or d < 256:   # see test_bf16_shapes_and_edges
-            assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
+    for path in PATHS:
+        out = run_ex(q, p, r, 1.0, temp, flags=path)
+        assert abs(out["loss"].item() - want["loss"]) <= 1e-5 * abs(want["loss"])
+        assert relerr(to_np(out["lse"]), want["lse"]) <= 1e-5
+        for k in ("dq", "dp"):
+            assert relerr(to_np(out[k]), want[k]) <= TOL_BF16_PEAKED
+            if k == "dp" or d < 256 or path == gc.GC_PATH_STATS_PASS:   # see test_bf16_shapes_and_edges
+                assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
 
 
 @pytest.mark.parametrize("B,P,d,dtype", [(200, 700, 256, torch.bfloat16), (90, 300, 768, torch.bfloat16),
                                          (64, 200, 128, torch.bfloat16), (40, 90, 48, torch.float32)])
-def test_very_large_logits_neither_overflow_nor_vanish(B, P, d, dtype):
+@pytest.mark.parametrize("path", PATHS)
+def test_very_large_logits_neither_overflow_nor_vanish(B, P, d, dtype, path):
     """Logits of 200 to 400 (scale 400 on unit-norm rows): every exponent the kernels form is <= 0, so nothing
     overflows, and each row's largest term is 1, so no row sum vanishes; the softmax is one-hot up to fp32."""
     q, p, r = synth.dpr_batch(B, P, d, dtype, seed=2700 + B, positive_mix=0.6)
@@ -131,7 +138,7 @@ def test_very_large_logits_neither_overflow_nor_vanish(B, P, d, dtype):
     q64, p64 = synth.widen(q), synth.widen(p)
     want = O.loss_and_rep_grad(q64, p64, r.numpy(), scale, 1.0)
     assert np.abs(scale * q64 @ p64.T).max() > 200.0
-    out = run_ex(q, p, r, scale, 1.0)
+    out = run_ex(q, p, r, scale, 1.0, flags=path)
     for k in ("loss", "dq", "dp", "lse"):
         assert torch.isfinite(out[k]).all(), k
     assert abs(out["loss"].item() - want["loss"]) <= 1e-4 * abs(want["loss"])
@@ -149,7 +156,8 @@ def test_very_large_logits_neither_overflow_nor_vanish(B, P, d, dtype):
 
 @pytest.mark.parametrize("order", ["rising", "falling"])
 @pytest.mark.parametrize("B,P,d", [(200, 2000, 256), (70, 3000, 768)])
-def test_scores_that_rise_or_fall_along_the_stream(B, P, d, order):
+@pytest.mark.parametrize("path", PATHS)
+def test_scores_that_rise_or_fall_along_the_stream(B, P, d, order, path):
     """Logits that grow steadily along the targets (about 7 in base 2 per 16-row tile, 600 in all): the walk that
     forms the statistics as it goes has to raise its per-row reference, and rescale what it has accumulated, every
     few tiles; falling, it keeps the first reference and most later terms underflow to nothing."""
@@ -162,7 +170,7 @@ def test_scores_that_rise_or_fall_along_the_stream(B, P, d, order):
     scale = 600.0
     q64, p64 = synth.widen(q), synth.widen(p)
     want = O.loss_and_rep_grad(q64, p64, r.numpy(), scale, 1.0)
-    out = run_ex(q, p, r, scale, 1.0)
+    out = run_ex(q, p, r, scale, 1.0, flags=path)
     for k in ("loss", "dq", "dp", "lse"):
         assert torch.isfinite(out[k]).all(), k
     assert abs(out["loss"].item() - want["loss"]) <= 1e-4 * abs(want["loss"])
@@ -182,8 +190,9 @@ def test_mask_self(n, d, dtype):
     q, p, _ = synth.dpr_batch(n, n, d, dtype, seed=3000 + n)
     r = torch.arange(n, dtype=torch.int32) ^ 1
     want = oracle_loss(q, p, r, 1.0, 0.5, mask_self=True)
-    out = run_ex(q, p, r, 1.0, 0.5, flags=gc.GC_MASK_SELF)
-    compare(out, want, TOL_BF16 if dtype == torch.bfloat16 else TOL_F32, q, p, 2.0)
+    for path in PATHS:
+        out = run_ex(q, p, r, 1.0, 0.5, flags=gc.GC_MASK_SELF | path)
+        compare(out, want, TOL_BF16 if dtype == torch.bfloat16 else TOL_F32, q, p, 2.0)
 
 
 def test_optional_outputs_and_reuse_of_workspace():
@@ -192,13 +201,13 @@ def test_optional_outputs_and_reuse_of_workspace():
     the same call twice does."""
     q, p, r = synth.config2()
     qd, pd, rd = q.to(DEV), p.to(DEV), r.to(DEV)
-    full = gc.gc_loss_and_rep_grad_ex(qd, pd, rd)
+    full = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, flags=gc.GC_PATH_ONLINE)
     only = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("loss",), workspace=full["workspace"])
     torch.cuda.synchronize()
     assert abs(only["loss"].item() - full["loss"].item()) <= 1e-6 * abs(full["loss"].item())
     only_dp = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("dp",), workspace=full["workspace"])
     again_dp = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("dp",), workspace=full["workspace"])
-    only_dq = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, want=("loss", "dq"), workspace=full["workspace"])
+    only_dq = gc.gc_loss_and_rep_grad_ex(qd, pd, rd, flags=gc.GC_PATH_ONLINE, want=("loss", "dq"), workspace=full["workspace"])
     torch.cuda.synchronize()
     assert relerr(to_np(only_dp["dp"]), to_np(full["dp"])) <= 1e-5
     assert torch.equal(only_dp["dp"], again_dp["dp"])

@@ -69,7 +69,8 @@ def test_argument_errors_are_raised_on_the_host():
     args = lambda **k: [k.get("dt", gc.GC_BF16), fake, fake, fake, k.get("B", 8), k.get("P", 16), 128, 1.0, 1.0,
                         k.get("flags", 0), fake, fake, fake, None, None, k.get("ws", fake), k.get("wsb", 1 << 30), None]
     assert ex(*args(dt=5)) == gc.GC_ERR_UNSUPPORTED
-    assert ex(*args(flags=2)) == gc.GC_ERR_UNSUPPORTED
+    assert ex(*args(flags=8)) == gc.GC_ERR_UNSUPPORTED
+    assert ex(*args(flags=gc.GC_PATH_ONLINE | gc.GC_PATH_STATS_PASS)) == gc.GC_ERR_UNSUPPORTED
     assert ex(*args(flags=gc.GC_MASK_SELF)) == gc.GC_ERR_SHAPE          # B != P
     assert ex(*args(ws=None)) == gc.GC_ERR_WORKSPACE
     assert ex(*args(ws=vp(264))) == gc.GC_ERR_WORKSPACE                  # misaligned
