@@ -61,6 +61,10 @@ typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
  * the results of the two sequences agree to fp32 rounding, not bit for bit. */
 #define GC_PATH_ONLINE 2u     /* the dQ walk forms the row statistics itself, no statistics pass */
 #define GC_PATH_STATS_PASS 4u /* statistics pass, then both gradient walks in one launch */
+/* The cache in bf16: dq and dp then point to bf16 [rows,d] buffers and receive the fp32 results rounded to nearest
+ * even (half the bytes of the cache; the rounding, up to 2^-9 relative per element, is then part of what Step 3 sees).
+ * Only where the MFMA kernels run (bf16 inputs, d a multiple of 128 up to 768), else GC_ERR_UNSUPPORTED. */
+#define GC_CACHE_BF16 8u
 
 /* Text for a gc_status value (host; static storage, never NULL). */
 const char* gc_strerror(int status);
@@ -92,7 +96,7 @@ int gc_loss_and_rep_grad_f32(const float* q, const float* p, const int32_t* pos_
 /*
  * Extended form of the same computation.
  *   dt         type of q and p
- *   flags      0 or GC_MASK_SELF, optionally with one of GC_PATH_ONLINE / GC_PATH_STATS_PASS
+ *   flags      0 or GC_MASK_SELF, optionally with one of GC_PATH_ONLINE / GC_PATH_STATS_PASS, and GC_CACHE_BF16
  *   loss, dq, dp, lse, argmax   each may be NULL (not produced).  lse[B] float is
  *              logsumexp_j s_ij; argmax[B] int32 is the smallest j that attains
  *              max_j s_ij in the kernel's fp32 scores.

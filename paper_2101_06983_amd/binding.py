@@ -17,6 +17,7 @@ GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_POS_IDX,
 GC_F32, GC_BF16 = 0, 1
 GC_MASK_SELF = 1
 GC_PATH_ONLINE, GC_PATH_STATS_PASS = 2, 4
+GC_CACHE_BF16 = 8
 
 EXPORTS = [
     "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",
@@ -178,11 +179,14 @@ def gc_loss_and_rep_grad_ex(q, p, pos_idx, scale=1.0, temp=1.0, flags=0, want=("
     P = p.shape[0]
     dev = q.device
     out = dict(out or {})
-    shapes = dict(loss=((1,), torch.float32), dq=((B, d), torch.float32), dp=((P, d), torch.float32),
+    cache = torch.bfloat16 if (flags & GC_CACHE_BF16) else torch.float32
+    shapes = dict(loss=((1,), torch.float32), dq=((B, d), cache), dp=((P, d), cache),
                   lse=((B,), torch.float32), argmax=((B,), torch.int32))
     for k in want:
         if k not in out:
             out[k] = torch.empty(shapes[k][0], dtype=shapes[k][1], device=dev)
+        elif out[k].dtype != shapes[k][1] or tuple(out[k].shape) != shapes[k][0] or not out[k].is_contiguous():
+            raise ValueError("preallocated %s must be a contiguous %s tensor of shape %s" % (k, shapes[k][1], shapes[k][0]))
     need = lib.gc_workspace_bytes(B, P, d, dt)
     if workspace is None:
         workspace = alloc_workspace(need, dev)

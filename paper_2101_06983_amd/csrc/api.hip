@@ -87,6 +87,10 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   pl.off_pos_pad = take((size_t)pl.b_pad * 4);
   pl.off_rowloss = take((size_t)B * 4);
   int dq_parts = (pl.nsq > 1 || ntxent) ? pl.nsq : 0, dp_parts = ((pl.nsp > 1 || ntxent) && !pl.one_walk) ? pl.nsp : 0;
+  if (pl.use_mfma && !ntxent) {  // a bf16 cache (GC_CACHE_BF16) always goes through a partial
+    if (dq_parts < 1) dq_parts = 1;
+    if (dp_parts < 1) dp_parts = 1;
+  }
   if (pl.fused) {
     if (pl.fz_nsq > dq_parts) dq_parts = pl.fz_nsq;            // the online walk always writes partials
     if (pl.fz_nsp > 1 && pl.fz_nsp > dp_parts) dp_parts = pl.fz_nsp;
@@ -144,8 +148,10 @@ bool prof_active() { return g_prof.on; }
 static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   LossArgs a = a_in;
   // does the gradient pass of this call end in a sum of split partials (launch_grad_mfma)?
+  const bool cache_bf16 = (a.flags & GC_CACHE_BF16) != 0;
   a.loss_with_partials = pl.use_mfma && !a.lse2_t &&
-                         (a.dz ? (!pl.one_walk || pl.nsq > 1) : ((a.dq && pl.nsq > 1) || (a.dp && pl.nsp > 1)));
+                         (a.dz ? (!pl.one_walk || pl.nsq > 1)
+                               : ((a.dq && (pl.nsq > 1 || cache_bf16)) || (a.dp && (pl.nsp > 1 || cache_bf16))));
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
   hipError_t e;
@@ -164,7 +170,7 @@ static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
       LossPlan pb = pl;
       b.dq = nullptr;
       pb.nsp = pl.fz_nsp; pb.p_stream_len = pl.fz_p_stream_len;
-      b.loss_with_partials = pb.nsp > 1;
+      b.loss_with_partials = pb.nsp > 1 || cache_bf16;
       loss_done = b.loss_with_partials;
       e = launch_grad_mfma(b, pb);   // records mark 3 after the walk
       if (e != hipSuccess) return GC_ERR_HIP;
@@ -204,7 +210,8 @@ static int check_loss_args(gc_dtype dt, const void* q, const void* p, const int3
   if (!(scale > 0.f) || !(temp > 0.f) || !std::isfinite(scale) || !std::isfinite(temp)) return GC_ERR_SHAPE;
   if (!std::isfinite(scale / temp) || !(scale / temp > 0.f)) return GC_ERR_SHAPE;
   if (dt != GC_F32 && dt != GC_BF16) return GC_ERR_UNSUPPORTED;
-  if (flags & ~(GC_MASK_SELF | GC_PATH_ONLINE | GC_PATH_STATS_PASS)) return GC_ERR_UNSUPPORTED;
+  if (flags & ~(GC_MASK_SELF | GC_PATH_ONLINE | GC_PATH_STATS_PASS | GC_CACHE_BF16)) return GC_ERR_UNSUPPORTED;
+  if ((flags & GC_CACHE_BF16) && !(dt == GC_BF16 && d % 128 == 0 && d >= 128 && d <= 768)) return GC_ERR_UNSUPPORTED;
   if ((flags & GC_PATH_ONLINE) && (flags & GC_PATH_STATS_PASS)) return GC_ERR_UNSUPPORTED;
   if ((flags & GC_MASK_SELF) && (B != P || P < 2)) return GC_ERR_SHAPE;
   return GC_OK;

@@ -97,6 +97,6 @@ bool prof_active();  // the measurement events of the loss path are being record
 // loss_of / pl: also carry the sum of the row losses of that call (see LossArgs::loss_with_partials)
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
                                  int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of = nullptr,
-                                 const LossPlan* pl = nullptr);
+                                 const LossPlan* pl = nullptr, bool out_bf16 = false);
 
 }  // namespace gc

@@ -246,6 +246,7 @@ struct ReduceSrc {
   int count[4];
   size_t stride[4];
   int nsrc;
+  int out_bf16;   // the sum is stored as bf16 (round to nearest even), `out` then points to bf16 elements
 };
 // With a loss sum attached the grid has one more workgroup, the first (so that it runs beside the others), which carries it (it has nothing to do with
 // the partial sums; it only saves a launch on the path that needs both).
@@ -260,7 +261,12 @@ __global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < rs.nsrc; s++)
     for (int k = 0; k < rs.count[s]; k++) acc += ((const f32x4*)(rs.ptr[s] + (size_t)k * rs.stride[s]))[e];
-  ((f32x4*)out)[e] = acc;
+  if (rs.out_bf16) {
+    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+    ((bf16x4_t*)out)[e] = __builtin_convertvector(acc, bf16x4_t);
+  } else {
+    ((f32x4*)out)[e] = acc;
+  }
 }
 __global__ void __launch_bounds__(256) partial_reduce_tail_kernel(float* __restrict__ out, ReduceSrc rs, size_t beg, size_t n) {
   size_t e = beg + (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -268,7 +274,8 @@ __global__ void __launch_bounds__(256) partial_reduce_tail_kernel(float* __restr
   float acc = 0.f;
   for (int s = 0; s < rs.nsrc; s++)
     for (int k = 0; k < rs.count[s]; k++) acc += rs.ptr[s][(size_t)k * rs.stride[s] + e];
-  out[e] = acc;
+  if (rs.out_bf16) ((__bf16*)out)[e] = (__bf16)acc;
+  else out[e] = acc;
 }
 
 // Fused mode: merge of what the splits of the online dQ walk left per anchor (reference, sum 2^(t - reference), and
@@ -284,6 +291,7 @@ struct FinishArgs {
   int nsq, B, Pn, d, b_pad;
   float out_scale;
   float* lse2; int32_t* pos_pad; float* rowloss; float* lse_out; int32_t* argmax_out; float* dq;
+  int dq_bf16;   // dq points to bf16 elements
 };
 __global__ void __launch_bounds__(256) online_finish_kernel(FinishArgs f) {
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -342,7 +350,12 @@ __global__ void __launch_bounds__(256) online_finish_kernel(FinishArgs f) {
     const s16x4 pv = ((const s16x4*)(f.P + (size_t)r_safe * f.d))[c];
 #pragma unroll
     for (int e = 0; e < 4; e++) acc[e] += cpos * bf2f((unsigned short)pv[e]);
-    ((f32x4*)(f.dq + (size_t)i * f.d))[c] = acc;
+    if (f.dq_bf16) {
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+      ((bf16x4_t*)((__bf16*)f.dq + (size_t)i * f.d))[c] = __builtin_convertvector(acc, bf16x4_t);
+    } else {
+      ((f32x4*)(f.dq + (size_t)i * f.d))[c] = acc;
+    }
   }
 }
 
@@ -356,7 +369,7 @@ hipError_t launch_online_finish(const LossArgs& a, const LossPlan& pl) {
   f.nsq = pl.fz_nsq; f.B = a.B; f.Pn = a.P; f.d = a.d; f.b_pad = pl.b_pad;
   f.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
   f.lse2 = (float*)(ws + pl.off_lse2); f.pos_pad = (int32_t*)(ws + pl.off_pos_pad); f.rowloss = (float*)(ws + pl.off_rowloss);
-  f.lse_out = a.lse; f.argmax_out = a.argmax; f.dq = a.dq;
+  f.lse_out = a.lse; f.argmax_out = a.argmax; f.dq = a.dq; f.dq_bf16 = (a.flags & GC_CACHE_BF16) ? 1 : 0;
   online_finish_kernel<<<(pl.b_pad + 3) / 4, 256, 0, a.stream>>>(f);
   return hipGetLastError();
 }
@@ -369,9 +382,11 @@ static LossSum loss_sum_of(const LossArgs& a, const LossPlan& pl) {
 }
 
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
-                                 int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of, const LossPlan* pl) {
+                                 int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of, const LossPlan* pl,
+                                 bool out_bf16) {
   ReduceSrc rs{};
   rs.nsrc = nsrc;
+  rs.out_bf16 = out_bf16 ? 1 : 0;
   for (int s = 0; s < nsrc; s++) { rs.ptr[s] = srcs[s]; rs.count[s] = counts[s]; rs.stride[s] = strides[s]; }
   LossSum ls{};
   if (loss_of) ls = loss_sum_of(*loss_of, *pl);

@@ -1338,7 +1338,9 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   const int own = (a.d == 128) ? G1_OWN : GR_OWN;   // owner rows per workgroup
   ga.obQ = want_q ? (a.B + own - 1) / own : 0; ga.nsq = pl.nsq; ga.q_stream_len = pl.q_stream_len;
   ga.obP = want_p ? (a.P + own - 1) / own : 0; ga.nsp = pl.nsp; ga.p_stream_len = pl.p_stream_len;
-  const bool q_direct = (pl.nsq == 1 && (!a.dz || one_walk)), p_direct = (pl.nsp == 1 && !a.dz);
+  // a bf16 cache is rounded by the kernel that sums the partials: with it even a single split goes through that kernel
+  const bool cache_bf16 = (a.flags & GC_CACHE_BF16) != 0;
+  const bool q_direct = (pl.nsq == 1 && (!a.dz || one_walk)) && !cache_bf16, p_direct = (pl.nsp == 1 && !a.dz) && !cache_bf16;
   ga.dq_out = q_direct ? (one_walk ? a.dz : a.dq) : (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
   ga.dp_out = p_direct ? a.dp : (float*)(ws + pl.off_dp_part); ga.dp_split_stride = np;
   const int nwg = ga.obQ * ga.nsq + ga.obP * ga.nsp;
@@ -1370,13 +1372,13 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   }
   if (want_q && !q_direct) {
     const float* srcs[1] = {ga.dq_out}; int counts[1] = {pl.nsq}; size_t strides[1] = {nq};
-    e = launch_partial_reduce(a.dq, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl);
+    e = launch_partial_reduce(a.dq, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl, cache_bf16);
     if (e != hipSuccess) return e;
     loss_of = nullptr;
   }
   if (want_p && !p_direct) {
     const float* srcs[1] = {ga.dp_out}; int counts[1] = {pl.nsp}; size_t strides[1] = {np};
-    e = launch_partial_reduce(a.dp, srcs, counts, strides, 1, np, a.stream, loss_of, &pl);
+    e = launch_partial_reduce(a.dp, srcs, counts, strides, 1, np, a.stream, loss_of, &pl, cache_bf16);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

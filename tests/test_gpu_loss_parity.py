@@ -185,6 +185,33 @@ def test_scores_that_rise_or_fall_along_the_stream(B, P, d, order, path):
     assert amb <= 2
 
 
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("B,P,d", [(128, 256, 768), (300, 1000, 128), (65, 257, 256), (1024, 16384, 384)])
+def test_cache_in_bf16(B, P, d, path):
+    """GC_CACHE_BF16: dq, dp are the fp32 results rounded to nearest even, bit for bit, on either kernel sequence
+    (the last shape is one where the library itself picks the online walk and where both outputs have split partials)."""
+    q, p, _ = synth.dpr_batch(B, P, d, seed=2900 + B, positive_mix=0.3)
+    r = torch.from_numpy(np.random.default_rng(B).integers(0, P, size=B).astype(np.int32))
+    f32 = run_ex(q, p, r, 1.0, 0.5, flags=path)
+    b16 = run_ex(q, p, r, 1.0, 0.5, flags=path | gc.GC_CACHE_BF16)
+    assert b16["dq"].dtype == torch.bfloat16 and b16["dp"].dtype == torch.bfloat16
+    assert b16["loss"].item() == f32["loss"].item()
+    assert torch.equal(b16["dq"], f32["dq"].to(torch.bfloat16))
+    assert torch.equal(b16["dp"], f32["dp"].to(torch.bfloat16))
+    want = oracle_loss(q, p, r, 1.0, 0.5)
+    assert relerr(to_np(b16["dq"].float()), want["dq"]) <= TOL_BF16 + 2.0 ** -8
+    assert relerr(to_np(b16["dp"].float()), want["dp"]) <= TOL_BF16 + 2.0 ** -8
+
+
+def test_cache_in_bf16_needs_the_mfma_shapes():
+    q, p, r = synth.dpr_batch(20, 40, 96, seed=2950)
+    with pytest.raises(gc.GradCacheError):
+        gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), flags=gc.GC_CACHE_BF16)
+    q, p, r = synth.dpr_batch(20, 40, 128, torch.float32, seed=2951)
+    with pytest.raises(gc.GradCacheError):
+        gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), flags=gc.GC_CACHE_BF16)
+
+
 @pytest.mark.parametrize("n,d,dtype", [(96, 128, torch.bfloat16), (70, 24, torch.float32), (322, 256, torch.bfloat16)])
 def test_mask_self(n, d, dtype):
     q, p, _ = synth.dpr_batch(n, n, d, dtype, seed=3000 + n)
