@@ -241,18 +241,23 @@ def test_optional_outputs_and_reuse_of_workspace():
     assert torch.equal(only_dq["dq"], full["dq"]) and only_dq["loss"].item() == full["loss"].item()
 
 
-def test_pos_idx_out_of_range_is_reported_not_faulted():
+@pytest.mark.parametrize("path", PATHS)
+def test_pos_idx_out_of_range_is_reported_not_faulted(path):
     q, p, r = synth.config2()
     r = r.clone()
     r[5] = 256          # == P
-    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), want=("loss",))
+    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), flags=path, want=("loss", "dq", "dp"))
     torch.cuda.synchronize()
     assert gc.gc_check_async_error(out["workspace"]) == gc.GC_ERR_POS_IDX
     assert math.isnan(out["loss"].item())
     r[5] = -3
-    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), want=("loss",), workspace=out["workspace"])
+    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), flags=path, want=("loss", "dq"), workspace=out["workspace"])
     torch.cuda.synchronize()
     assert gc.gc_check_async_error(out["workspace"]) == gc.GC_ERR_POS_IDX
+    r[5] = 7            # and the error word clears again
+    out = gc.gc_loss_and_rep_grad_ex(q.to(DEV), p.to(DEV), r.to(DEV), flags=path, want=("loss", "dq"), workspace=out["workspace"])
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error(out["workspace"]) == gc.GC_OK and math.isfinite(out["loss"].item())
 
 
 def test_config3_full_size_parity_invariants_and_reproducibility():
