@@ -90,6 +90,24 @@ def test_chunking_does_not_change_the_update():
         assert torch.equal(b["grads"][k], c["grads"][k]), k      # run-to-run reproducible
 
 
+def test_step_with_a_large_batch_takes_the_online_walk():
+    """B = P = 4096 with a small encoder (64-128-768): 2^24 scores, so Step 2 runs without a statistics pass; the
+    parameter gradients still equal the full-batch ones."""
+    xq, xp, r, params = synth.mlp_problem(B=4096, P=4096, din=64, dh=128, dout=768, seed=synth.SEED0 + 50)
+    want = O.mlp_fullbatch_grad(synth.widen(xq), synth.widen(xp), synth.widen(r), widen_params(params), 1.0, 0.2,
+                                rep_dtype="bf16")
+    out = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 256, 512, dev_params(params), 1.0, 0.2, keep=True)
+    torch.cuda.synchronize()
+    assert abs(out["loss"].item() - want["loss"]) <= TOL_BF16 * abs(want["loss"])
+    assert relerr(to_np(out["dq"]), want["dq"]) <= TOL_CHAIN
+    assert relerr(to_np(out["dp"]), want["dp"]) <= TOL_CHAIN
+    for k in ("W1", "b1", "W2", "b2"):
+        # a parameter gradient here is a sum over 8192 rows whose terms largely cancel (the cached gradients of a
+        # batch sum to about zero: invariant I1), so its size is that of a few terms while every row brings its
+        # rounding error: twice the chained tolerance
+        assert relerr(to_np(out["grads"][k]), want["grads"][k]) <= 2 * TOL_CHAIN, k
+
+
 def test_config5_full_size():
     xq, xp, r, params = synth.mlp_problem()
     want = O.mlp_chunked_grad(synth.widen(xq), synth.widen(xp), synth.widen(r), widen_params(params), 32, 32,
