@@ -1,5 +1,7 @@
 """GPU parity of the stand-in encoder steps (graph-less forward, chunk surrogate
 backward, whole Gradient Cache step) against the fp64 oracle."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -105,7 +107,14 @@ def test_step_with_a_large_batch_takes_the_online_walk():
         # a parameter gradient here is a sum over 8192 rows whose terms largely cancel (the cached gradients of a
         # batch sum to about zero: invariant I1), so its size is that of a few terms while every row brings its
         # rounding error: twice the chained tolerance
-        assert relerr(to_np(out["grads"][k]), want["grads"][k]) <= 2 * TOL_CHAIN, k
+        if k != "b2":
+            assert relerr(to_np(out["grads"][k]), want["grads"][k]) <= 2 * TOL_CHAIN, k
+    # db2 is the plain sum of all 8192 cached rows, of which the 4096 target rows sum to exactly zero in exact
+    # arithmetic (I1): what is left is small against the terms, while the rounding errors of the rows add like a
+    # random walk.  Held to that: sqrt(rows) times the chained-tolerance error of one row (as for the other sums: twice).
+    rows = 4096 + 4096
+    row_scale = max(np.abs(want["dq"]).max(), np.abs(want["dp"]).max())
+    assert np.abs(to_np(out["grads"]["b2"]) - want["grads"]["b2"]).max() <= 2 * TOL_CHAIN * math.sqrt(rows) * row_scale
 
 
 def test_config5_full_size():
