@@ -177,7 +177,7 @@ static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
     } else {
       prof_mark(call, 3, a.stream);
     }
-    if (!loss_done && launch_loss_sum(a, pl) != hipSuccess) return GC_ERR_HIP;
+    if (!loss_done && !a.defer_loss_sum && launch_loss_sum(a, pl) != hipSuccess) return GC_ERR_HIP;
     prof_mark(call, 4, a.stream);
     if (g_prof.on) g_prof.calls++;
     return GC_OK;
@@ -233,13 +233,6 @@ __global__ void invert_perm_kernel(const int32_t* r, int32_t* rinv, int n) {
   if (i < n) {
     const int j = r[i];
     if (j >= 0 && j < n) rinv[j] = i;
-  }
-}
-// loss = (l1 + l2) / 2; the error word of the first direction also takes the second's
-__global__ void combine_sym_kernel(const float* l1, const float* l2, float* loss, int* err1, const int* err2) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    if (loss) *loss = 0.5f * (*l1 + *l2);
-    if (*err2) *err1 = *err2;
   }
 }
 
@@ -420,12 +413,16 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
   LossArgs a{};
   a.dt = GC_BF16; a.B = n; a.P = n; a.d = d; a.alpha = scale / temp; a.stream = s;
+  a.defer_loss_sum = true;   // one launch sums the row losses of both directions at the end
+  LossArgs a1, a2;
   if (sp.pl.use_mfma) {
     // statistics of both directions (Eq. 1 as it stands, then with the two sides exchanged) ...
     a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = l; a.ws = ws;
+    a1 = a;
     rc = run_loss(a, sp.pl);
     if (rc != GC_OK) return rc;
     a.q = p; a.p = q; a.pos_idx = rinv; a.loss = l + 1; a.ws = ws + sp.off2;
+    a2 = a;
     rc = run_loss(a, sp.pl);
     if (rc != GC_OK) return rc;
     // ... and one gradient pass with the mean of the two softmaxes as coefficients
@@ -440,9 +437,11 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
     a.grad_mul = 0.5f;
     // direction 1: anchors against targets (Eq. 1); direction 2: the same with the two sides exchanged
     a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = l; a.dq = g[0]; a.dp = g[1]; a.ws = ws;
+    a1 = a;
     rc = run_loss(a, sp.pl);
     if (rc != GC_OK) return rc;
     a.q = p; a.p = q; a.pos_idx = rinv; a.loss = l + 1; a.dq = g[2]; a.dp = g[3]; a.ws = ws + sp.off2;
+    a2 = a;
     rc = run_loss(a, sp.pl);
     if (rc != GC_OK) return rc;
     // dL/df = Eq. 5 of direction 1 + Eq. 6 of direction 2, dL/dg the other two; fixed order
@@ -452,8 +451,7 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
     { const float* srcs[2] = {g[1], g[2]}; int counts[2] = {1, 1}; size_t strides[2] = {ne, ne};
       if (launch_partial_reduce(dp, srcs, counts, strides, 2, ne, s) != hipSuccess) return GC_ERR_HIP; }
   }
-  combine_sym_kernel<<<1, 64, 0, s>>>(l, l + 1, loss, (int*)(ws + sp.pl.off_err), (const int*)(ws + sp.off2 + sp.pl.off_err));
-  return hipGetLastError() == hipSuccess ? GC_OK : GC_ERR_HIP;
+  return launch_sym_loss_sum(a1, a2, sp.pl, loss) == hipSuccess ? GC_OK : GC_ERR_HIP;
 }
 
 }  // extern "C"

@@ -79,6 +79,7 @@ struct LossArgs {
   // set by run_loss when the gradient pass ends in a sum of split partials: that launch then also sums the row
   // losses (one launch less); the statistics merge leaves the sum to it
   bool loss_with_partials;
+  bool defer_loss_sum;   // the caller sums the row losses itself (the symmetric loss: both directions in one launch)
   char* ws;
   hipStream_t stream;
 };
@@ -91,6 +92,8 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_grad_online(const LossArgs& a, const LossPlan& pl);    // fused mode: dQ walk with online statistics
 hipError_t launch_online_finish(const LossArgs& a, const LossPlan& pl);  // ... its splits -> lse2, row losses, dQ
 hipError_t launch_loss_sum(const LossArgs& a, const LossPlan& pl);       // the fixed-order sum of the row losses alone
+// symmetric loss: both directions' sums in one launch, loss = (l1 + l2) / 2, the first error word takes the second's
+hipError_t launch_sym_loss_sum(const LossArgs& a1, const LossArgs& a2, const LossPlan& pl, float* loss);
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl);
 void prof_mark_grad_kernel_done(hipStream_t s);  // measurement aid: event after the main gradient kernel(s)
 bool prof_active();  // the measurement events of the loss path are being recorded

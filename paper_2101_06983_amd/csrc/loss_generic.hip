@@ -417,6 +417,21 @@ hipError_t launch_loss_sum(const LossArgs& a, const LossPlan& pl) {
   return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(1024) sym_loss_reduce_kernel(LossSum l1, LossSum l2, float* loss) {
+  __shared__ float red[1024];
+  loss_sum_block<1024>(l1, red);   // thread 0 writes *l1.loss and *l1.err ...
+  __syncthreads();
+  loss_sum_block<1024>(l2, red);
+  if (threadIdx.x == 0) {          // ... and reads them back itself
+    if (loss) *loss = 0.5f * (*l1.loss + *l2.loss);
+    if (*l2.err) *l1.err = *l2.err;
+  }
+}
+hipError_t launch_sym_loss_sum(const LossArgs& a1, const LossArgs& a2, const LossPlan& pl, float* loss) {
+  sym_loss_reduce_kernel<<<1, 1024, 0, a1.stream>>>(loss_sum_of(a1, pl), loss_sum_of(a2, pl), loss);
+  return hipGetLastError();
+}
+
 hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
   auto merge = [&](auto lanes_tag) {
@@ -432,7 +447,7 @@ hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
   else if (pl.stat_splits <= 16) merge(std::integral_constant<int, 16>{});
   else merge(std::integral_constant<int, 64>{});
   // the sum of the row losses: by a launch of its own, unless a sum of gradient partials follows that carries it
-  if (!a.loss_with_partials) loss_reduce_kernel<<<1, 1024, 0, a.stream>>>(loss_sum_of(a, pl));
+  if (!a.loss_with_partials && !a.defer_loss_sum) loss_reduce_kernel<<<1, 1024, 0, a.stream>>>(loss_sum_of(a, pl));
   return hipGetLastError();
 }
 
