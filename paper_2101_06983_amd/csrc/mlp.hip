@@ -289,8 +289,9 @@ __global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
 
 // One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
 // sub-batch c-1 and the re-encode of sub-batch c are independent of each other (three sets of buffers), and none of
-// them fills the GPU alone.  Workgroups [0, n_wg) take the weight-gradient tiles (n_wg2 of them dW2), the next n_dh
-// the n-tiles of dH, the rest the tiles of the re-encode.  A count of 0 switches a part off (pipeline ends).
+// them fills the GPU alone.  The first n_dh workgroups take the n-tiles of dH, the next n_enc the tiles of the
+// re-encode, the remaining n_wg the weight-gradient tiles (n_wg2 of them dW2).  A count of 0 switches a part off
+// (pipeline ends).
 struct Step3Args {
   WgradArgs g2, g1; int n_wg2, n_wg;
   SkinnyArgs dh; int n_dh;
@@ -301,27 +302,29 @@ __global__ void __launch_bounds__(256, 3) mlp_step3_kernel(Step3Args a) {
   constexpr size_t kLds = kA + kB > sizeof(SkinnyRed) * 4 ? kA + kB : sizeof(SkinnyRed) * 4;
   __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
   int id = blockIdx.x;
-  if (id < a.n_wg) {
-    unsigned short* As = (unsigned short*)lds;
-    unsigned short* Bs = (unsigned short*)(lds + kA);
-    if (id < a.n_wg2) {
-      const int nb = a.g2.N / 128;
-      wgrad_tile<true>(a.g2, id % nb, id / nb, As, Bs);
-    } else {
-      const int nb = a.g1.N / 128;
-      wgrad_tile<false>(a.g1, (id - a.n_wg2) % nb, (id - a.n_wg2) / nb, As, Bs);
-    }
-    return;
-  }
-  id -= a.n_wg;
+  // the long-running workgroups (they stream whole weight rows) come first, the many short weight-gradient tiles
+  // fill in behind them (1.16 -> 1.08 ms per step at config 5 against the other order)
   SkinnyRed* red = (SkinnyRed*)lds;
   if (id < a.n_dh) {
     for (int by = 0; by * 32 < a.dh.M; by++) skinny_tile<true, EP_DH, 2>(a.dh, id, by, red);
     return;
   }
   id -= a.n_dh;
-  const int nb = a.enc.N / 32;
-  skinny_tile<false, EP_GELU, 2>(a.enc, id % nb, id / nb, red);
+  if (id < a.n_enc) {
+    const int nb = a.enc.N / 32;
+    skinny_tile<false, EP_GELU, 2>(a.enc, id % nb, id / nb, red);
+    return;
+  }
+  id -= a.n_enc;
+  unsigned short* As = (unsigned short*)lds;
+  unsigned short* Bs = (unsigned short*)(lds + kA);
+  if (id < a.n_wg2) {
+    const int nb = a.g2.N / 128;
+    wgrad_tile<true>(a.g2, id % nb, id / nb, As, Bs);
+  } else {
+    const int nb = a.g1.N / 128;
+    wgrad_tile<false>(a.g1, (id - a.n_wg2) % nb, (id - a.n_wg2) / nb, As, Bs);
+  }
 }
 
 // Wt[n][k] = W[k][n] (bf16), 32 x 32 tiles through LDS; K and N multiples of 32
