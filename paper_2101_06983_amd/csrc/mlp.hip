@@ -61,33 +61,37 @@ __device__ __forceinline__ void load8(const void* base, size_t idx, bool live, u
 struct WgradArgs {
   const void* A; int lda;   // elements
   const float* B; int ldb;
-  int M, N, K;              // M a multiple of 32, N a multiple of 128, K = rows of the sub-batch (any)
+  int M, N, K;              // M a multiple of 64 (WG_M), N a multiple of 128, K = rows of the sub-batch (any)
   float* C; int ldc;        // += in place (one workgroup per tile: single writer)
   float* colsum;            // optional: [N] += column sums of B (db2; written by the m-tile 0 workgroups)
 };
 
-constexpr int WG_KCH = 32, WG_A_LD = 32 + 8, WG_B_LD = 128 + 8;  // LDS tiles (bf16): [k rows][width + 8], hi then lo part
+// a workgroup's tile of C is WG_M x 128 (two 32-row MFMA tiles that share the B operand in LDS)
+constexpr int WG_M = 64;
+constexpr int WG_KCH = 32, WG_A_LD = WG_M + 8, WG_B_LD = 128 + 8;  // LDS tiles (bf16): [k rows][width + 8], hi then lo part
 
 template <bool A_F32>
 __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, unsigned short* As, unsigned short* Bs) {
   constexpr int KCH = WG_KCH, A_LD = WG_A_LD, B_LD = WG_B_LD;
   constexpr int A_LO = KCH * A_LD, B_LO = KCH * B_LD;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
-  const int n0 = bx * 128, m0 = by * 32;
+  const int n0 = bx * 128, m0 = by * WG_M;
 
   // the accumulator tile starts from its current value in HBM (read issued first: it is the longest wait);
-  // lane holds column n, rows m0 + 8 (r / 4) + 4 h + r % 4
+  // lane holds column n, rows m0 + 32 mt + 8 (r / 4) + 4 h + r % 4
   const int n = n0 + wave * 32 + ln;
-  f32x16 acc;
+  f32x16 acc[2];
 #pragma unroll
-  for (int r = 0; r < 16; r++) {
-    const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
-    acc[r] = (m < g.M) ? g.C[(size_t)m * g.ldc + n] : 0.f;
-  }
+  for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int m = m0 + 32 * mt + 8 * (r >> 2) + 4 * h + (r & 3);
+      acc[mt][r] = (m < g.M) ? g.C[(size_t)m * g.ldc + n] : 0.f;
+    }
 
   for (int k0 = 0; k0 < g.K; k0 += KCH) {
-    for (int c = tid; c < KCH * 4; c += 256) {   // A[k][m0 .. m0 + 31]
-      const int r = c / 4, cc = c % 4;
+    for (int c = tid; c < KCH * (WG_M / 8); c += 256) {   // A[k][m0 .. m0 + WG_M - 1]
+      const int r = c / (WG_M / 8), cc = c % (WG_M / 8);
       u32x4 vh, vl;
       load8<A_F32>(g.A, (size_t)(k0 + r) * g.lda + m0 + cc * 8, k0 + r < g.K, vh, vl);
       *(u32x4*)(As + r * A_LD + cc * 8) = vh;
@@ -111,18 +115,24 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
         s16x8 t = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, t);
       };
-      const bf16x8 af = frag(As, A_LD, 0), bfv = frag(Bs, B_LD, wave * 32);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfv, acc, 0, 0, 0);
-      if (A_F32) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(As + A_LO, A_LD, 0), bfv, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, frag(Bs + B_LO, B_LD, wave * 32), acc, 0, 0, 0);
+      const bf16x8 bfv = frag(Bs, B_LD, wave * 32), bfl = frag(Bs + B_LO, B_LD, wave * 32);
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++) {
+        const bf16x8 af = frag(As, A_LD, 32 * mt);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfv, acc[mt], 0, 0, 0);
+        if (A_F32) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(As + A_LO, A_LD, 32 * mt), bfv, acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfl, acc[mt], 0, 0, 0);
+      }
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int r = 0; r < 16; r++) {
-    const int m = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
-    if (m < g.M) g.C[(size_t)m * g.ldc + n] = acc[r];
-  }
+  for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int m = m0 + 32 * mt + 8 * (r >> 2) + 4 * h + (r & 3);
+      if (m < g.M) g.C[(size_t)m * g.ldc + n] = acc[mt][r];
+    }
   if (g.colsum && by == 0 && tid < 128) {
     float s = 0.f;
     for (int k = 0; k < g.K; k++) s += g.B[(size_t)k * g.ldb + n0 + tid];
@@ -150,7 +160,7 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g2, WgradArgs 
 __global__ void __launch_bounds__(256) wgrad_splitk_kernel(WgradArgs g, int rows_per_slice) {
   __shared__ __attribute__((aligned(16))) unsigned short As[2 * WG_KCH * WG_A_LD];
   __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * WG_KCH * WG_B_LD];
-  const int nb = g.N / 128, tiles = nb * (g.M / 32);
+  const int nb = g.N / 128, tiles = nb * (g.M / WG_M);
   const int tile = blockIdx.x % tiles, slice = blockIdx.x / tiles;
   const int k0 = slice * rows_per_slice;
   WgradArgs s = g;
@@ -430,7 +440,7 @@ static hipError_t mlp_backward_wgrad(const void* x, int rows, const gc_mlp_param
                                      const MlpWs& ws, hipStream_t s) {
   WgradArgs g2, g1;
   wgrad_args(x, rows, w, u, acc, ws, g2, g1);
-  const int n2 = (w->dout / 128) * (w->dh / 32), n1 = (w->dh / 128) * (w->din / 32);
+  const int n2 = (w->dout / 128) * (w->dh / WG_M), n1 = (w->dh / 128) * (w->din / WG_M);
   mlp_wgrad_kernel<<<n2 + n1, 256, 0, s>>>(g2, g1, n2);
   return hipGetLastError();
 }
@@ -546,7 +556,7 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
                                base + sw.off_loss, sw.loss_bytes, (void*)s);
   if (rc != GC_OK) return rc;
   // Step 3: per sub-batch re-encode and backward of the cached rows; gradients accumulated in index order
-  const int n2 = (w->dout / 128) * (w->dh / 32), n1 = (w->dh / 128) * (w->din / 32);
+  const int n2 = (w->dout / 128) * (w->dh / WG_M), n1 = (w->dh / 128) * (w->din / WG_M);
   for (int i = 0; i < nsub + 2; i++) {
     Step3Args a3{};
     if (i >= 2) {                      // weight gradients of sub-batch i-2
@@ -687,7 +697,7 @@ static BilinearWs plan_bilinear(int B, int P, int d) {
   w.off_omT = take((size_t)d * d * 2);
   w.off_H = take((size_t)B * d * 2);
   w.off_A = take((size_t)B * d * 4);
-  const int tiles = (d / 128) * (d / 32);
+  const int tiles = (d / 128) * (d / WG_M);
   int slices = (4 * kNumCU + tiles - 1) / tiles;           // about four workgroups per CU
   const int max_slices = (B + 127) / 128;                   // at least 128 rows per slice
   if (slices > max_slices) slices = max_slices;
@@ -747,7 +757,7 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
     fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, n, 0.f);
     WgradArgs g{};
     g.A = q; g.lda = d; g.B = A; g.ldb = d; g.M = d; g.N = d; g.K = B; g.C = part; g.ldc = d;
-    wgrad_splitk_kernel<<<(d / 128) * (d / 32) * w.slices, 256, 0, s>>>(g, w.rows_per_slice);
+    wgrad_splitk_kernel<<<(d / 128) * (d / WG_M) * w.slices, 256, 0, s>>>(g, w.rows_per_slice);
     if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
     const float* srcs[1] = {part}; int counts[1] = {w.slices}; size_t strides[1] = {(size_t)d * d};
     if (launch_partial_reduce(domega, srcs, counts, strides, 1, (size_t)d * d, s) != hipSuccess) return GC_ERR_HIP;
