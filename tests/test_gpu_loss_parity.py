@@ -84,6 +84,7 @@ def test_config2_dpr_shaped_bf16():
     (600, 1100, 128, 1.0, 0.2),    # d = 128 kernel: several 256-row owner blocks, ragged owner and stream ends
     (257, 64, 128, 2.0, 1.0),      # d = 128: one row past an owner block, two stream tiles
     (2048, 4096, 128, 1.0, 1.0),   # d = 128: long streams, split partials
+    (1030, 16390, 384, 1.0, 0.5),  # several splits of a long ragged stream, a ragged last owner block, on both sequences
     (64, 96, 96, 1.0, 1.0),        # d not a multiple of 128: general kernel on bf16 storage
     (20, 50, 8, 1.0, 1.0),
 ])
