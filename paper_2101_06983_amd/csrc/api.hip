@@ -16,7 +16,8 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   pl.use_mfma = (dt == GC_BF16 && d % 128 == 0 && d >= 128 && d <= 768) ? 1 : 0;
   if (pl.use_mfma) {
     const int n_ablk = ceil_div(B, 256), tiles = ceil_div(P, 256);
-    int splits = ceil_div(kNumCU, n_ablk);
+    // d = 128 has a statistics kernel of 256 threads, two workgroups to a CU
+    int splits = ceil_div(d == 128 ? 2 * kNumCU : kNumCU, n_ablk);
     if (splits > 64) splits = 64;  // the merge kernel combines at most 64 splits per anchor
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;

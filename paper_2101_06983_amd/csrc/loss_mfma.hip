@@ -314,7 +314,9 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
   }
 }
 
+static hipError_t launch_stats128(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
+  if (a.d == 128) return launch_stats128(a, pl);   // whole anchor rows in registers: a kernel of its own
   char* ws = a.ws;
   const int n_ablk = (a.B + ST_TN - 1) / ST_TN;
   const size_t smem = (size_t)2 * ST_STAGE_BYTES;
@@ -1239,6 +1241,191 @@ __global__ void __launch_bounds__(256) grad128_kernel(GradArgs ga) {
     const int t = id - nQ;
     grad128_body<false, SYM>(ga, t % ga.obP, t / ga.obP, gsmem);
   }
+}
+
+// ===========================================================================
+// Statistics pass for d = 128 (Eq. 4's normaliser, the positive's logit and the arg-max, per anchor and split).
+// The layout of the d = 128 gradient pass without its second contraction: a workgroup (4 waves) owns 256 anchors,
+// each wave 64 of them with all 128 columns in registers, and all four share the streamed target tiles (32 rows)
+// through the same LDS ring.  Lane (n, h) holds, for its two anchors 32 i + n, the scores of 16 of a tile's 32
+// targets; the other 16 are in lane (n, h ^ 1).  The running (max, sum, arg-max) of an anchor therefore lives in
+// a lane of its own and no lane talks to another before the end of the stream: 16 MFMAs against about 5 vector
+// operations per score, which a second workgroup on the same CU runs behind the first one's MFMAs.
+// ===========================================================================
+constexpr int S1_AHEAD = 6;   // tile u is read, tiles u+1 .. u+5 are in flight, tile u+6 goes where tile u-2 was
+template <bool ARGMAX>
+__global__ void __launch_bounds__(256, 2) stats128_kernel(const unsigned short* __restrict__ Q,
+                                                          const unsigned short* __restrict__ Pm,
+                                                          const int32_t* __restrict__ pos_idx, int B, int P,
+                                                          float alpha2, int mask_self, int n_ablk, int cols_per_split,
+                                                          float* __restrict__ part_m, float* __restrict__ part_l,
+                                                          int* __restrict__ part_idx, float* __restrict__ pos_t) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char s1mem[];
+  constexpr int D = 128;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, h = lane >> 5, ln = lane & 31;
+  const int task = xcd_task_id();
+  const int ablk = task % n_ablk, split = task / n_ablk;
+  const int a0 = ablk * G1_OWN + w * G1_OWN_W;   // this wave's first anchor
+  const int sbeg = split * cols_per_split, send = min(P, sbeg + cols_per_split);
+  const int nt = (send - sbeg + G1_T - 1) / G1_T;   // >= 1
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)s1mem);
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+
+  // anchors as B fragments: lane (ln, h) holds anchor 32 n + ln, columns 16 ks + 8 h .. + 7
+  bf16x8 ofrag[2][8];
+  int own_idx[2], r_o[2];
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+    own_idx[n] = a0 + 32 * n + ln;
+    const int row = min(own_idx[n], B - 1);
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) ofrag[n][ks] = *(const bf16x8*)(Q + (size_t)row * D + 16 * ks + 8 * h);
+    r_o[n] = (own_idx[n] < B) ? pos_idx[own_idx[n]] : -1;
+  }
+  // the compiler's own loads end here (it does not see the direct-to-LDS loads counted by wait_vmem below)
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) asm volatile("" : "+v"(ofrag[n][ks]));
+    asm volatile("" : "+v"(r_o[n]));
+  }
+
+  // loads of a streamed tile: 8 instructions of 4 rows, two per wave; lane -> (row, chunk position)
+  auto src_of = [&](int it, int max_row) __attribute__((always_inline)) -> unsigned {
+    const int row = 4 * it + (lane >> 4);
+    const int c = (lane & 15) ^ swz128(row);
+    return (unsigned)(min(row, max_row) * (D * 2) + c * 16);
+  };
+  const unsigned voff_full[2] = {src_of(2 * w, G1_T - 1), src_of(2 * w + 1, G1_T - 1)};
+  auto prefetch = [&](int u) __attribute__((always_inline)) {
+    const int t0 = sbeg + u * G1_T;
+    const unsigned st = lds0 + (u & (G1_STAGES - 1)) * G1_STAGE;
+    const unsigned short* tile = Pm + (size_t)t0 * D;
+    if (t0 + G1_T <= P) {
+      dma_group<1>(tile, &voff_full[0], st + G1_STAT + (2 * wu) * 1024);
+      dma_group<1>(tile, &voff_full[1], st + G1_STAT + (2 * wu + 1) * 1024);
+    } else {  // ragged last tile: rows past the end re-read the last valid row (masked below)
+#pragma unroll
+      for (int k = 0; k < 2; k++) {
+        const unsigned off = src_of(2 * w + k, P - 1 - t0);
+        dma_group<1>(tile, &off, st + G1_STAT + (2 * wu + k) * 1024);
+      }
+    }
+  };
+  const unsigned sw_ln = swz128(ln);
+
+  float rm[2], rl[2], rpos[2];
+  int ridx[2];
+  bool got[2];
+#pragma unroll
+  for (int n = 0; n < 2; n++) { rm[n] = -INFINITY; rl[n] = 0.f; rpos[n] = 0.f; ridx[n] = 0x7fffffff; got[n] = false; }
+
+#pragma unroll 1
+  for (int u = 0; u < min(nt, S1_AHEAD); u++) prefetch(u);
+
+#pragma unroll 1
+  for (int u = 0; u < nt; u++) {
+    // my loads of tile u have landed: two instructions per tile, tiles up to u + S1_AHEAD - 1 have been started
+    const int later = min(nt - 1, u + S1_AHEAD - 1) - u;
+    if (later >= 5) wait_vmem<10>(); else if (later == 4) wait_vmem<8>(); else if (later == 3) wait_vmem<6>();
+    else if (later == 2) wait_vmem<4>(); else if (later == 1) wait_vmem<2>(); else wait_vmem<0>();
+    __syncthreads();  // ... and everybody's; everybody is past tile u-1, so the stage of tile u-2 is free
+    if (u + S1_AHEAD < nt) prefetch(u + S1_AHEAD);
+    const unsigned char* st = s1mem + (u & (G1_STAGES - 1)) * G1_STAGE;
+    const int t0 = sbeg + u * G1_T;
+
+    bf16x8 pfr[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) pfr[k] = *(const bf16x8*)(st + G1_STAT + ln * 256 + (((2 * k + h) ^ (int)sw_ln) * 16));
+    f32x16 s[2];
+#pragma unroll
+    for (int n = 0; n < 2; n++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) s[n][r] = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; k++)
+#pragma unroll
+      for (int n = 0; n < 2; n++) s[n] = mfma32(pfr[k], ofrag[n][k], s[n]);
+
+    // online statistics; s holds raw dot products, the base-2 logit is alpha2 * s (alpha2 > 0: same order).
+    // Register r of lane (ln, h) is target t0 + 8 (r / 4) + 4 h + r % 4: increasing in r.
+    // the masks that can touch this tile: few tiles, and one scalar branch for the wave (as a per-lane condition the
+    // compiler turns the masking into selects that every tile then pays for)
+    bool rare = (t0 + G1_T > send) || (mask_self && t0 < a0 + G1_OWN_W && t0 + G1_T > a0);
+    rare = rare || (unsigned)(r_o[0] - t0) < (unsigned)G1_T || (unsigned)(r_o[1] - t0) < (unsigned)G1_T;
+    if (__builtin_amdgcn_ballot_w64(rare) != 0) {
+#pragma unroll
+      for (int n = 0; n < 2; n++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int j = t0 + 8 * (r >> 2) + 4 * h + (r & 3);
+          const bool masked = j >= send || (mask_self && j == own_idx[n]);
+          if (j == r_o[n] && !masked) { rpos[n] = s[n][r] * alpha2; got[n] = true; }
+          if (masked) s[n][r] = -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < 2; n++) {
+      float tmr = -INFINITY; int tc = 0;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const float t = s[n][r];
+        if (ARGMAX) {
+          const bool le = t <= tmr;   // strict >: the first (smallest) index attaining the maximum
+          tmr = le ? tmr : t;
+          tc = le ? tc : r;
+        } else {
+          tmr = fmaxf(tmr, t);
+        }
+      }
+      if (tmr > -INFINITY) {
+        const float tm = tmr * alpha2;
+        const float mn = fmaxf(rm[n], tm);
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) sum += fast_exp2(__builtin_fmaf(s[n][r], alpha2, -mn));
+        rl[n] = rl[n] * fast_exp2(rm[n] - mn) + sum;
+        if (ARGMAX && tm > rm[n]) ridx[n] = t0 + 8 * (tc >> 2) + 4 * h + (tc & 3);  // later tiles have larger indices
+        rm[n] = mn;
+      }
+    }
+  }
+
+  // the positive's score is seen by exactly one lane of one workgroup
+#pragma unroll
+  for (int n = 0; n < 2; n++)
+    if (got[n] && own_idx[n] < B) pos_t[own_idx[n]] = rpos[n];
+  // combine the two half-waves (same anchor, the other 16 targets of every tile), then write the split partial
+#pragma unroll
+  for (int n = 0; n < 2; n++) {
+    const float m2 = __shfl_xor(rm[n], 32), l2 = __shfl_xor(rl[n], 32);
+    const int i2 = __shfl_xor(ridx[n], 32);
+    stat_merge(rm[n], rl[n], ridx[n], m2, l2, i2);
+    if (h == 0 && own_idx[n] < B) {
+      const size_t o = (size_t)split * B + own_idx[n];
+      part_m[o] = rm[n]; part_l[o] = rl[n]; part_idx[o] = ridx[n];
+    }
+  }
+}
+
+template <bool ARGMAX>
+static hipError_t stats128_launch(const LossArgs& a, const LossPlan& pl) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)stats128_kernel<ARGMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, G1_SMEM);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  char* ws = a.ws;
+  const int n_ablk = (a.B + G1_OWN - 1) / G1_OWN;
+  stats128_kernel<ARGMAX><<<n_ablk * pl.stat_splits, 256, G1_SMEM, a.stream>>>(
+      (const unsigned short*)a.q, (const unsigned short*)a.p, a.pos_idx, a.B, a.P, a.alpha * kLog2e,
+      (a.flags & GC_MASK_SELF) ? 1 : 0, n_ablk, pl.stat_cols_per_split, (float*)(ws + pl.off_part_m),
+      (float*)(ws + pl.off_part_l), (int*)(ws + pl.off_part_idx), (float*)(ws + pl.off_pos));
+  return hipGetLastError();
+}
+static hipError_t launch_stats128(const LossArgs& a, const LossPlan& pl) {
+  return a.argmax ? stats128_launch<true>(a, pl) : stats128_launch<false>(a, pl);
 }
 
 template <int D, bool SYM>
