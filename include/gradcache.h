@@ -14,14 +14,19 @@
  *   - All tensor pointers are DEVICE pointers unless marked "host".  Matrices
  *     are row-major and contiguous (leading dimension = number of columns).
  *   - The caller owns every buffer, the workspace included; the library frees
- *     nothing the caller passed.  Entry points that take no workspace argument
- *     use a per-device buffer the library allocates with hipMalloc on first use
- *     and grows on demand; two such calls that overlap in time on one device
- *     race on it - use the *_ex forms with your own workspace for that.
+ *     nothing the caller passed.  gc_loss_and_rep_grad_bf16 / _f32 take no
+ *     workspace argument: they use a per-device buffer the library allocates
+ *     with hipMalloc on first use and grows on demand (growing frees the old
+ *     buffer with hipFree, which waits for the device; while `stream` is being
+ *     captured into a graph a call that would have to grow it returns
+ *     GC_ERR_UNSUPPORTED instead).  Two such calls that overlap in time on one
+ *     device race on it - use the *_ex forms with your own workspace for that,
+ *     or gc_loss_and_rep_grad_bf16_static where nothing may be allocated.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  A
  *     call only enqueues work and returns; outputs are valid once the stream
  *     has been synchronised.  No call synchronises the device, except
- *     gc_check_async_error.
+ *     gc_check_async_error, gc_step_mlp_release and the workspace growth
+ *     described above.
  *   - Return value: GC_OK or a negative gc_status.  All argument checks are
  *     made on the host before the first HIP call, so a bad call enqueues
  *     nothing.  pos_idx values cannot be checked on the host: a value outside
@@ -173,6 +178,11 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
  * workspace: gc_bilinear_workspace_bytes(B, P, d) (0 for an unsupported shape).
  */
 size_t gc_bilinear_workspace_bytes(int B, int P, int d);
+/* Where a call leaves its two intermediates inside its workspace (host, pure): byte offsets of H[B,d] (bf16, the
+ * stored h_i = Omega^T f(s_i) that the scores were formed from) and of A[B,d] (float, a_i = sum_j w_ij g(t_j), from
+ * which u = A Omega^T and dOmega = F^T A follow).  For callers that keep them and for stage-by-stage checks.
+ * Errors: GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_UNSUPPORTED as for the call itself. */
+int gc_bilinear_workspace_layout(int B, int P, int d, size_t* off_h, size_t* off_a);
 int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
                                     const void* omega, float scale, float temp, float* loss, float* u, float* v,
                                     float* domega, void* workspace, size_t workspace_bytes, void* stream);
@@ -237,6 +247,13 @@ int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32
                      int chunk_p, const gc_mlp_params* w, float scale, float temp, float* loss,
                      const gc_mlp_grads* grads, void* q_rep, void* p_rep, float* dq, float* dp, void* workspace,
                      size_t workspace_bytes, void* stream);
+
+/* Forgets the recordings gc_step_mlp_bf16 keeps for the current device (at most 8 argument sets): call it before
+ * freeing buffers that a recorded call named, or to give the graph memory back.  It waits for the device to be
+ * idle (the one call besides gc_check_async_error that synchronises), then destroys the recorded graphs and the
+ * library's capture stream; later calls record afresh.  A recorded call must always be issued on one stream at a
+ * time: replays on two streams share the workspace and race.  Errors: GC_ERR_HIP. */
+int gc_step_mlp_release(void);
 
 #ifdef __cplusplus
 }

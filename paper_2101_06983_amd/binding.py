@@ -23,10 +23,11 @@ EXPORTS = [
     "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",
     "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
     "gc_ntxent_loss_and_grad_bf16", "gc_bidirectional_workspace_bytes",
-    "gc_bidirectional_loss_and_rep_grad_bf16", "gc_bilinear_workspace_bytes", "gc_bilinear_loss_and_grads_bf16",
+    "gc_bidirectional_loss_and_rep_grad_bf16", "gc_bilinear_workspace_bytes", "gc_bilinear_workspace_layout",
+    "gc_bilinear_loss_and_grads_bf16",
     "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
     "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
-    "gc_profile_begin", "gc_profile_end",
+    "gc_step_mlp_release", "gc_profile_begin", "gc_profile_end",
 ]
 
 
@@ -80,6 +81,8 @@ def load():
     lib.gc_bidirectional_loss_and_rep_grad_bf16.argtypes = [vp, vp, vp, ci, ci, cf, cf, vp, vp, vp, vp, sz, vp]
     lib.gc_bilinear_workspace_bytes.restype = sz
     lib.gc_bilinear_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.gc_bilinear_workspace_layout.restype = ci
+    lib.gc_bilinear_workspace_layout.argtypes = [ci, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.gc_bilinear_loss_and_grads_bf16.restype = ci
     lib.gc_bilinear_loss_and_grads_bf16.argtypes = [vp, vp, vp, ci, ci, ci, vp, cf, cf, vp, vp, vp, vp, vp, sz, vp]
     pp, pg = ctypes.POINTER(gc_mlp_params), ctypes.POINTER(gc_mlp_grads)
@@ -93,6 +96,8 @@ def load():
     lib.gc_step_mlp_workspace_bytes.argtypes = [ci, ci, ci, ci, pp]
     lib.gc_step_mlp_bf16.restype = ci
     lib.gc_step_mlp_bf16.argtypes = [vp, ci, vp, ci, vp, ci, ci, pp, cf, cf, vp, pg, vp, vp, vp, vp, vp, sz, vp]
+    lib.gc_step_mlp_release.restype = ci
+    lib.gc_step_mlp_release.argtypes = []
     lib.gc_profile_begin.restype = ci
     lib.gc_profile_begin.argtypes = [ci]
     fp = ctypes.POINTER(ctypes.c_float)
@@ -280,6 +285,28 @@ def gc_bilinear_loss_and_grads_bf16(q, p, pos_idx, omega, scale=1.0, temp=1.0, w
     _check(rc, "gc_bilinear_loss_and_grads_bf16")
     out["workspace"] = workspace
     return out
+
+
+def gc_step_mlp_release():
+    """Waits for the device and drops the graphs gc_step_mlp_bf16 has recorded on it."""
+    _check(load().gc_step_mlp_release(), "gc_step_mlp_release")
+
+
+def gc_bilinear_workspace_layout(B, P, d):
+    """(off_h, off_a): byte offsets, from the 256-byte aligned workspace start, of H [B,d] bf16 and A [B,d] float."""
+    a, b = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().gc_bilinear_workspace_layout(B, P, d, ctypes.byref(a), ctypes.byref(b)), "gc_bilinear_workspace_layout")
+    return a.value, b.value
+
+
+def bilinear_intermediates(workspace, B, P, d):
+    """Views (no copy) of the H and A a gc_bilinear_loss_and_grads_bf16 call left in `workspace`."""
+    off_h, off_a = gc_bilinear_workspace_layout(B, P, d)
+    base = workspace.data_ptr()
+    skip = (base + 255) // 256 * 256 - base
+    h = workspace[skip + off_h: skip + off_h + B * d * 2].view(torch.bfloat16).view(B, d)
+    a = workspace[skip + off_a: skip + off_a + B * d * 4].view(torch.float32).view(B, d)
+    return h, a
 
 
 # ----------------------------------------------------------------------------- stand-in encoder

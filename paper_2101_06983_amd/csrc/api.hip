@@ -11,8 +11,24 @@ namespace gc {
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// Compute units of the current device (sizes grids and the stream splits of the workspace plan), asked once per
+// process; without a device (the host-only checks of the test-suite) the MI355X count.
+int num_cu() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+    cached = n;
+  else
+    cached = kNumCUDefault;
+  (void)hipGetLastError();
+  return cached;
+}
+
 LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   LossPlan pl{};
+  const int kNumCU = num_cu();
   pl.use_mfma = (dt == GC_BF16 && d % 128 == 0 && d >= 128 && d <= 768) ? 1 : 0;
   if (pl.use_mfma) {
     const int n_ablk = ceil_div(B, 256), tiles = ceil_div(P, 256);
@@ -115,11 +131,16 @@ static std::mutex g_ws_mutex;
 static void* g_ws_ptr[64];
 static size_t g_ws_bytes[64];
 
-static int own_workspace(size_t need, void** out) {
+static int own_workspace(size_t need, hipStream_t stream, void** out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
   std::lock_guard<std::mutex> lock(g_ws_mutex);
   if (g_ws_bytes[dev] < need) {
+    // growing allocates, and frees the old buffer (which waits for the device): neither is legal while the
+    // caller's stream is being captured into a graph
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+    if (cap != hipStreamCaptureStatusNone) return GC_ERR_UNSUPPORTED;
     if (g_ws_ptr[dev]) (void)hipFree(g_ws_ptr[dev]);  // waits for work that still uses it
     g_ws_ptr[dev] = nullptr;
     g_ws_bytes[dev] = 0;
@@ -283,7 +304,7 @@ static int simple_loss(gc_dtype dt, const void* q, const void* p, const int32_t*
   if (!loss || !dq || !dp) return GC_ERR_NULL;
   const size_t need = make_loss_plan(B, P, d, dt, false).total;
   void* ws = nullptr;
-  rc = own_workspace(need, &ws);
+  rc = own_workspace(need, (hipStream_t)stream, &ws);
   if (rc != GC_OK) return rc;
   return gc_loss_and_rep_grad_ex(dt, q, p, pos_idx, B, P, d, scale, temp, 0, loss, dq, dp, nullptr, nullptr, ws, need,
                                  stream);
@@ -318,7 +339,12 @@ int gc_profile_begin(int max_calls) {
   if (g_prof.ev) return GC_ERR_UNSUPPORTED;  // already open
   g_prof.ev = new hipEvent_t[(size_t)max_calls * kMarks];
   for (int i = 0; i < max_calls * kMarks; i++)
-    if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return GC_ERR_HIP;
+    if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {   // give back what was made: a later begin starts afresh
+      for (int k = 0; k < i; k++) (void)hipEventDestroy(g_prof.ev[k]);
+      delete[] g_prof.ev;
+      g_prof.ev = nullptr;
+      return GC_ERR_HIP;
+    }
   g_prof.max_calls = max_calls;
   g_prof.calls = 0;
   g_prof.on = true;

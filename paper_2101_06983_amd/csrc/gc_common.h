@@ -21,7 +21,8 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kNumCU = 256;  // MI355X; used only to size grids and workspace splits
+constexpr int kNumCUDefault = 256;  // MI355X; what num_cu() answers when no device can be asked
+int num_cu();                       // compute units of the current device: sizes grids and workspace splits
 
 // fp32 -> bf16 bits, round to nearest even (inputs here are finite).
 __device__ __forceinline__ unsigned short f2bf(float f) {

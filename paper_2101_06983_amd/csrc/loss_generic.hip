@@ -67,8 +67,9 @@ __global__ void __launch_bounds__(256) stats_generic_kernel(const T* __restrict_
     float t = score_tile<T>(Q, Pm, B, P, d, row0, col0, alpha2, Qs, Ps);
     int j = col0 + tx;
     bool valid = (j < cend) && !(mask_self && j == i);
+    // (a positive that the self-mask removes has the logit -inf: its row loss is then +inf)
+    if (j < cend && j == ri && i < B) pos_t[i] = valid ? t : -INFINITY;
     if (valid) {
-      if (j == ri && i < B) pos_t[i] = t;
       if (t > m) {  // strict: ties keep the smaller index (columns are visited in increasing order)
         l = l * exp2f(m - t) + 1.f;
         m = t;

@@ -36,21 +36,24 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // lds_base + 1024 k + lane * 16 and reads gbase + voff[k] + 1024 k: the instruction's immediate
 // offset moves both addresses, so callers pass voff[k] with 1024 k already subtracted.  The
 // compiler does not see these loads: the reader waits with wait_vmem<N>().
+// Every statement below that sets M0 says so in its clobber list.  M0 is a register the backend reserves (it never
+// keeps a value of its own there across other code and sets it right before each instruction of its own that needs
+// it); the clobber states the write, so that nothing it may ever cache there is assumed to survive.
 template <int N>
 __device__ __forceinline__ void dma_group(const void* gbase, const unsigned* voff, unsigned lds_base) {
   if constexpr (N == 1) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff[0]), "s"(gbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff[0]), "s"(gbase) : "memory", "m0");
   } else if constexpr (N == 2) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\tglobal_load_lds_dwordx4 %2, %3 offset:1024"
-                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "s"(gbase) : "memory");
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "s"(gbase) : "memory", "m0");
   } else if constexpr (N == 3) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %4\n\tglobal_load_lds_dwordx4 %2, %4 offset:1024\n\t"
                  "global_load_lds_dwordx4 %3, %4 offset:2048"
-                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(gbase) : "memory");
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(gbase) : "memory", "m0");
   } else {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\tglobal_load_lds_dwordx4 %2, %5 offset:1024\n\t"
                  "global_load_lds_dwordx4 %3, %5 offset:2048\n\tglobal_load_lds_dwordx4 %4, %5 offset:3072"
-                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase) : "memory");
+                 ::"s"(lds_base), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(gbase) : "memory", "m0");
   }
 }
 // One such load with immediate offset IMM (a multiple of 1024 below 4096): lands at lds_base + IMM +
@@ -58,7 +61,7 @@ __device__ __forceinline__ void dma_group(const void* gbase, const unsigned* vof
 // traffic across it; callers order it against the readers of its target with wait_vmem / barriers.
 template <int IMM>
 __device__ __forceinline__ void dma_piece(const void* gbase, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3" ::"s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3" ::"s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM) : "m0");
 }
 // The same, placed by data dependences instead of fences: the statement claims to rewrite the
 // registers pin_a / pin_b (it does not touch them), so it is scheduled after the last reader of
@@ -71,17 +74,17 @@ __device__ __forceinline__ void dma_piece_pinned(const void* gbase, unsigned vof
     unsigned long long keep;
     if constexpr (TWO)
       asm volatile("s_mov_b64 %2, exec\n\ts_mov_b64 exec, 0xff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %5 offset:%6\n\ts_mov_b64 exec, %2"
-                   : "+v"(pa), "+v"(pb), "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+                   : "+v"(pa), "+v"(pb), "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM) : "m0");
     else
       asm volatile("s_mov_b64 %1, exec\n\ts_mov_b64 exec, 0xff\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %4 offset:%5\n\ts_mov_b64 exec, %1"
-                   : "+v"(pa), "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+                   : "+v"(pa), "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM) : "m0");
   } else {
     if constexpr (TWO)
       asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %4 offset:%5"
-                   : "+v"(pa), "+v"(pb) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+                   : "+v"(pa), "+v"(pb) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM) : "m0");
     else
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 offset:%4"
-                   : "+v"(pa) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM));
+                   : "+v"(pa) : "s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM) : "m0");
   }
   pin_a[0] = pa;
   if constexpr (TWO) pin_b[0] = pb;
@@ -304,14 +307,28 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
 #pragma unroll
   for (int nt = 0; nt < 2; nt++) {
     int a = a_col[nt], r = r_of[nt];
-    if (a < B && r >= cbeg && r < cend && !(mask_self && r == a)) {
+    if (a < B && r >= cbeg && r < cend) {
       // lane that held row r: rows of this lane are brow(mt, reg) with 4*(lane>>5) offset
       int rel = (r - cbeg) % ST_TM;  // row inside its tile
       int wmr = rel / 128, in = rel % 128;
       int half = (in % 8) / 4;
-      if (wmr == wm && half == (lane >> 5)) pos_t[a] = rpos[nt];
+      // a positive that the self-mask removes has the logit -inf (its row loss is then +inf)
+      if (wmr == wm && half == (lane >> 5)) pos_t[a] = (mask_self && r == a) ? -INFINITY : rpos[nt];
     }
   }
+}
+
+// A kernel that uses more than 64 KB of dynamic LDS has to be opted in (hipFuncSetAttribute): once per kernel and
+// device, remembered in `done` (a function-local array of the launcher, one per kernel instantiation).
+static hipError_t ensure_dyn_lds(const void* fn, int bytes, bool (&done)[64]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done[dev] = true;
+  return e;
 }
 
 static hipError_t launch_stats128(const LossArgs& a, const LossPlan& pl);
@@ -320,12 +337,8 @@ hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
   char* ws = a.ws;
   const int n_ablk = (a.B + ST_TN - 1) / ST_TN;
   const size_t smem = (size_t)2 * ST_STAGE_BYTES;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)stats_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static bool attr_done[64];
+  if (hipError_t e = ensure_dyn_lds((const void*)stats_mfma_kernel, (int)smem, attr_done); e != hipSuccess) return e;
   stats_mfma_kernel<<<n_ablk * pl.stat_splits, 512, smem, a.stream>>>(
       (const unsigned short*)a.q, (const unsigned short*)a.p, a.pos_idx, a.B, a.P, a.d, a.alpha * kLog2e,
       (a.flags & GC_MASK_SELF) ? 1 : 0, n_ablk, pl.stat_cols_per_split, (float*)(ws + pl.off_part_m),
@@ -790,7 +803,6 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
           if constexpr (!STEADY) {  // rows past the end of the split, the diagonal under mask_self
             const int t1o = b0 - 4 * g16;
             if ((t1o + GR_T > send) || (ga.mask_self && (t1o < a0 + GR_OWN) && (t1o + GR_T > a0))) {
-              if ((unsigned)(r_a - b0) < 4u && a_q < No) ga.on_pos[a_q] = tt[r_a - b0];   // before the mask, as the statistics pass does
 #pragma unroll
               for (int e = 0; e < 4; e++)
                 if (b0 + e >= send || (ga.mask_self && b0 + e == a_q)) tt[e] = -INFINITY;
@@ -851,7 +863,9 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
           // the positive: seen by exactly one lane of one split.  Its own term (p_{i r_i} - 1) p_{r_i} is formed in
           // fp32 by the kernel that finishes dQ: left in the bf16 sum it would cancel against - p_{r_i} with the
           // rounding error of a coefficient near 1
-          if (a_q < No && tt[r_a - b0] != -INFINITY) ga.on_pos[a_q] = tt[r_a - b0];
+          // (rows past the end of this split belong to the next one; a positive that the self-mask removes keeps
+          // its -inf, so that row's loss is +inf)
+          if (a_q < No && r_a < send) ga.on_pos[a_q] = tt[r_a - b0];
 #pragma unroll
           for (int e = 0; e < 4; e++)
             if (r_a - b0 == e) gv[e] = 0.f;
@@ -966,7 +980,7 @@ __device__ __forceinline__ int swz128(int row) { return ((row & 3) << 1) | ((row
 __device__ __forceinline__ void dma_lanes16(const void* gbase, unsigned voff, unsigned lds_base) {
   unsigned long long keep;
   asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffff\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
-               : "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+               : "=&s"(keep) : "s"(lds_base), "v"(voff), "s"(gbase) : "memory", "m0");
 }
 
 template <bool OWNER_IS_Q, bool SYM>
@@ -1359,8 +1373,10 @@ __global__ void __launch_bounds__(256, 2) stats128_kernel(const unsigned short* 
 #pragma unroll
         for (int r = 0; r < 16; r++) {
           const int j = t0 + 8 * (r >> 2) + 4 * h + (r & 3);
-          const bool masked = j >= send || (mask_self && j == own_idx[n]);
-          if (j == r_o[n] && !masked) { rpos[n] = s[n][r] * alpha2; got[n] = true; }
+          const bool self = mask_self && j == own_idx[n];
+          const bool masked = j >= send || self;
+          // (a positive that the self-mask removes has the logit -inf: its row loss is then +inf)
+          if (j == r_o[n] && j < send) { rpos[n] = self ? -INFINITY : s[n][r] * alpha2; got[n] = true; }
           if (masked) s[n][r] = -INFINITY;
         }
     }
@@ -1410,12 +1426,8 @@ __global__ void __launch_bounds__(256, 2) stats128_kernel(const unsigned short* 
 
 template <bool ARGMAX>
 static hipError_t stats128_launch(const LossArgs& a, const LossPlan& pl) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)stats128_kernel<ARGMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, G1_SMEM);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static bool attr_done[64];
+  if (hipError_t e = ensure_dyn_lds((const void*)stats128_kernel<ARGMAX>, G1_SMEM, attr_done); e != hipSuccess) return e;
   char* ws = a.ws;
   const int n_ablk = (a.B + G1_OWN - 1) / G1_OWN;
   stats128_kernel<ARGMAX><<<n_ablk * pl.stat_splits, 256, G1_SMEM, a.stream>>>(
@@ -1451,8 +1463,8 @@ __global__ void __launch_bounds__(256) grad_online_kernel(GradArgs ga) {
 template <int D>
 static hipError_t grad_online_launch(const GradArgs& ga, int nwg, hipStream_t stream) {
   const int smem = GradCfg<D>::SMEM;
-  hipError_t e = hipFuncSetAttribute((const void*)grad_online_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (e != hipSuccess) return e;
+  static bool attr_done[64];
+  if (hipError_t e = ensure_dyn_lds((const void*)grad_online_kernel<D>, smem, attr_done); e != hipSuccess) return e;
   grad_online_kernel<D><<<nwg, 256, smem, stream>>>(ga);
   return hipGetLastError();
 }
@@ -1485,8 +1497,8 @@ hipError_t launch_grad_online(const LossArgs& a, const LossPlan& pl) {
 template <int D, bool SYM>
 static hipError_t grad_mfma_launch_as(const GradArgs& ga, int nwg, hipStream_t stream) {
   const int smem = GradCfg<D>::SMEM;
-  hipError_t e = hipFuncSetAttribute((const void*)grad_mfma_kernel<D, SYM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (e != hipSuccess) return e;
+  static bool attr_done[64];
+  if (hipError_t e = ensure_dyn_lds((const void*)grad_mfma_kernel<D, SYM>, smem, attr_done); e != hipSuccess) return e;
   grad_mfma_kernel<D, SYM><<<nwg, 256, smem, stream>>>(ga);
   return hipGetLastError();
 }
@@ -1496,12 +1508,8 @@ static hipError_t grad_mfma_launch(const GradArgs& ga, int nwg, hipStream_t stre
 }
 template <bool SYM>
 static hipError_t grad128_launch(const GradArgs& ga, int nwg, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)grad128_kernel<SYM>, hipFuncAttributeMaxDynamicSharedMemorySize, G1_SMEM);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static bool attr_done[64];
+  if (hipError_t e = ensure_dyn_lds((const void*)grad128_kernel<SYM>, G1_SMEM, attr_done); e != hipSuccess) return e;
   grad128_kernel<SYM><<<nwg, 256, G1_SMEM, stream>>>(ga);
   return hipGetLastError();
 }

@@ -620,11 +620,31 @@ static int run_step(const StepCall& c, hipStream_t s) {
   return enqueue_step(c, s);
 }
 
+// Drops what run_step has recorded for the current device: waits for the device, then destroys the graph
+// executables and the capture stream.
+static int release_step_graphs() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_step_mutex);
+  StepGraphs& G = g_step_graphs[dev];
+  if (G.n == 0 && !G.cap) return GC_OK;
+  if (hipDeviceSynchronize() != hipSuccess) return GC_ERR_HIP;   // a graph in flight is never destroyed
+  int rc = GC_OK;
+  for (int i = 0; i < G.n; i++)
+    if (G.g[i].exec && hipGraphExecDestroy(G.g[i].exec) != hipSuccess) rc = GC_ERR_HIP;
+  G.n = 0;
+  if (G.cap && hipStreamDestroy(G.cap) != hipSuccess) rc = GC_ERR_HIP;
+  G.cap = nullptr;
+  return rc;
+}
+
 }  // namespace gc
 
 using namespace gc;
 
 extern "C" {
+
+int gc_step_mlp_release(void) { return release_step_graphs(); }
 
 size_t gc_mlp_workspace_bytes(int rows, const gc_mlp_params* w) {
   if (rows < 1 || check_mlp_params(w) != GC_OK) return 0;
@@ -698,7 +718,7 @@ static BilinearWs plan_bilinear(int B, int P, int d) {
   w.off_H = take((size_t)B * d * 2);
   w.off_A = take((size_t)B * d * 4);
   const int tiles = (d / 128) * (d / WG_M);
-  int slices = (4 * kNumCU + tiles - 1) / tiles;           // about four workgroups per CU
+  int slices = (4 * num_cu() + tiles - 1) / tiles;           // about four workgroups per CU
   const int max_slices = (B + 127) / 128;                   // at least 128 rows per slice
   if (slices > max_slices) slices = max_slices;
   if (slices > 64) slices = 64;
@@ -716,6 +736,16 @@ static bool bilinear_shape_ok(int B, int P, int d) {
 size_t gc_bilinear_workspace_bytes(int B, int P, int d) {
   if (!bilinear_shape_ok(B, P, d) || d % 128 || d > 768) return 0;
   return plan_bilinear(B, P, d).total;
+}
+
+int gc_bilinear_workspace_layout(int B, int P, int d, size_t* off_h, size_t* off_a) {
+  if (!off_h || !off_a) return GC_ERR_NULL;
+  if (!bilinear_shape_ok(B, P, d)) return GC_ERR_SHAPE;
+  if (d % 128 || d > 768) return GC_ERR_UNSUPPORTED;
+  const BilinearWs w = plan_bilinear(B, P, d);
+  *off_h = w.off_H;
+  *off_a = w.off_A;
+  return GC_OK;
 }
 
 int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,

@@ -29,6 +29,17 @@ def relerr(got, want):
     return float(np.abs(got - want).max() / den)
 
 
+def check(label, err, tol):
+    """Asserts err <= tol and prints both, so that the margin under every bound is on record
+    (`pytest -rP` shows the lines of passing tests)."""
+    print("parity %-44s err %.3e  tol %.3e  (%.0f %% of the bound)" % (label, err, tol, 100.0 * err / tol if tol > 0 else 0.0))
+    assert err <= tol, "%s: %.4e > %.4e" % (label, err, tol)
+
+
+def check_loss(label, got, want, tol, abs_floor=0.0):
+    check(label, abs(float(got) - float(want)), tol * abs(float(want)) + abs_floor)
+
+
 def normerr(got, want):
     """Frobenius norm of the difference over the Frobenius norm of the expected tensor."""
     got = np.asarray(got, dtype=np.float64)

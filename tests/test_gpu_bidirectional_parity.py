@@ -9,7 +9,7 @@ import torch
 from oracle import gc_oracle as O
 from paper_2101_06983_amd import binding as gc
 from paper_2101_06983_amd import synth
-from parity import TOL_BF16, TOL_BF16_PEAKED, TOL_SAME_G, normerr, relerr, to_np
+from parity import TOL_BF16, TOL_BF16_PEAKED, TOL_SAME_G, check, check_loss, normerr, relerr, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -40,13 +40,14 @@ def test_bidirectional_matches_the_oracle(n, d, scale, temp, tol):
     want = O.bidirectional(q64, p64, r.numpy(), scale, temp)
     same_g = O.bidirectional(q64, p64, r.numpy(), scale, temp, g_dtype="bf16")
     out = run(q, p, r, scale, temp)
-    assert abs(out["loss"].item() - want["loss"]) <= 1e-5 * abs(want["loss"])     # the loss has no bf16 step
+    tag = "bidir n=%d d=%d" % (n, d)
+    check_loss(tag + " loss", out["loss"].item(), want["loss"], 1e-5)     # the loss has no bf16 step
     for k in ("dq", "dp"):
         if d % 128 == 0:     # MFMA kernels: bf16 coefficients
-            assert relerr(to_np(out[k]), want[k]) <= tol
-            assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
+            check(tag + " " + k, relerr(to_np(out[k]), want[k]), tol)
+            check(tag + " " + k + " vs same-g", normerr(to_np(out[k]), same_g[k]), TOL_SAME_G)
         else:                # fp32-FMA kernels: nothing is rounded to bf16
-            assert relerr(to_np(out[k]), want[k]) <= 1e-5
+            check(tag + " " + k, relerr(to_np(out[k]), want[k]), 1e-5)
 
 
 def test_bidirectional_at_the_benchmark_size():
@@ -55,9 +56,9 @@ def test_bidirectional_at_the_benchmark_size():
     q, p, r = problem(n, d, 6400)
     want = O.bidirectional(synth.widen(q), synth.widen(p), r.numpy(), 1.0, 1.0)
     out = run(q, p, r, 1.0, 1.0)
-    assert abs(out["loss"].item() - want["loss"]) <= 1e-5 * abs(want["loss"])
+    check_loss("bidir n=8192 loss", out["loss"].item(), want["loss"], 1e-5)
     for k in ("dq", "dp"):
-        assert relerr(to_np(out[k]), want[k]) <= TOL_BF16
+        check("bidir n=8192 " + k, relerr(to_np(out[k]), want[k]), TOL_BF16)
     # Euler identity: sum_i <q_i, dq_i> = sum_j <p_j, dp_j> (both are (alpha/n) sum_ij g_ij <q_i, p_j>)
     a = float((synth.widen(q) * to_np(out["dq"])).sum()), float((synth.widen(p) * to_np(out["dp"])).sum())
     assert abs(a[0] - a[1]) <= 1e-3 * max(abs(a[0]), abs(a[1]), 1e-6)

@@ -9,8 +9,8 @@ import torch
 from paper_2101_06983_amd import binding as gc
 from paper_2101_06983_amd import synth
 from oracle import gc_oracle as O
-from parity import (TOL_BF16, TOL_BF16_PEAKED, TOL_F32, TOL_SAME_G, check_argmax, normerr, oracle_loss, relerr,
-                    to_np)
+from parity import (TOL_BF16, TOL_BF16_PEAKED, TOL_F32, TOL_SAME_G, check, check_argmax, check_loss, normerr,
+                    oracle_loss, relerr, to_np)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -27,11 +27,11 @@ def run_ex(q, p, r, scale=1.0, temp=1.0, flags=0):
     return out
 
 
-def compare(out, want, tol, q=None, p=None, alpha=1.0, gap_tol=1e-5):
-    assert abs(out["loss"].item() - want["loss"]) <= tol * abs(want["loss"]) + 1e-30
-    assert relerr(to_np(out["dq"]), want["dq"]) <= tol
-    assert relerr(to_np(out["dp"]), want["dp"]) <= tol
-    assert relerr(to_np(out["lse"]), want["lse"]) <= tol
+def compare(out, want, tol, q=None, p=None, alpha=1.0, gap_tol=1e-5, label=""):
+    check_loss(label + " loss", out["loss"].item(), want["loss"], tol, 1e-30)
+    check(label + " dq", relerr(to_np(out["dq"]), want["dq"]), tol)
+    check(label + " dp", relerr(to_np(out["dp"]), want["dp"]), tol)
+    check(label + " lse", relerr(to_np(out["lse"]), want["lse"]), tol)
     amb = check_argmax(to_np(out["argmax"]), want, synth.widen(q), synth.widen(p), alpha, gap_tol)
     assert amb <= max(1, len(want["argmax"]) // 1000)
 
@@ -46,10 +46,10 @@ def test_config1_tiny_fp32():
     loss, dq, dp = gc.gc_loss_and_rep_grad_f32(q.to(DEV), p.to(DEV), r.to(DEV))
     torch.cuda.synchronize()
     assert gc.gc_check_async_error() == gc.GC_OK
-    assert abs(loss.item() - want["loss"]) <= TOL_F32 * want["loss"]
-    assert relerr(to_np(dq), want["dq"]) <= TOL_F32
-    assert relerr(to_np(dp), want["dp"]) <= TOL_F32
-    compare(run_ex(q, p, r), want, TOL_F32, q, p)
+    check_loss("config1 loss", loss.item(), want["loss"], TOL_F32)
+    check("config1 dq", relerr(to_np(dq), want["dq"]), TOL_F32)
+    check("config1 dp", relerr(to_np(dp), want["dp"]), TOL_F32)
+    compare(run_ex(q, p, r), want, TOL_F32, q, p, label="config1 ex")
 
 
 @pytest.mark.parametrize("B,P,d,scale,temp", [(37, 53, 20, 1.0, 1.0), (1, 1, 7, 1.0, 1.0), (1, 40, 64, 2.0, 0.5),
@@ -59,7 +59,7 @@ def test_fp32_general_shapes(B, P, d, scale, temp):
     g = np.random.default_rng(B)
     r = torch.from_numpy(g.integers(0, P, size=B).astype(np.int32))   # shared positives, unused targets
     want = oracle_loss(q, p, r, scale, temp)
-    compare(run_ex(q, p, r, scale, temp), want, TOL_F32, q, p, scale / temp)
+    compare(run_ex(q, p, r, scale, temp), want, TOL_F32, q, p, scale / temp, label="fp32 %dx%dx%d" % (B, P, d))
 
 
 def test_config2_dpr_shaped_bf16():
@@ -68,10 +68,10 @@ def test_config2_dpr_shaped_bf16():
     assert 4.9 < want["loss"] < 5.2
     loss, dq, dp = gc.gc_loss_and_rep_grad_bf16(q.to(DEV), p.to(DEV), r.to(DEV))
     torch.cuda.synchronize()
-    assert abs(loss.item() - want["loss"]) <= TOL_BF16 * want["loss"]
-    assert relerr(to_np(dq), want["dq"]) <= TOL_BF16
-    assert relerr(to_np(dp), want["dp"]) <= TOL_BF16
-    compare(run_ex(q, p, r), want, TOL_BF16, q, p)
+    check_loss("config2 loss", loss.item(), want["loss"], TOL_BF16)
+    check("config2 dq", relerr(to_np(dq), want["dq"]), TOL_BF16)
+    check("config2 dp", relerr(to_np(dp), want["dp"]), TOL_BF16)
+    compare(run_ex(q, p, r), want, TOL_BF16, q, p, label="config2 ex")
 
 
 @pytest.mark.parametrize("B,P,d,scale,temp", [
@@ -98,16 +98,17 @@ def test_bf16_shapes_and_edges(B, P, d, scale, temp):
         if P == 1:
             assert out["loss"].item() == 0.0
             assert float(out["dq"].abs().max()) == 0.0 and float(out["dp"].abs().max()) == 0.0
-        compare(out, want, TOL_BF16, q, p, scale / temp)
+        tag = "bf16 %dx%dx%d path %d" % (B, P, d, path)
+        compare(out, want, TOL_BF16, q, p, scale / temp, label=tag)
         if d % 128 == 0 and P > 1:
             # the MFMA kernels round the coefficients g_ij to bf16: against the definition with that one rounding
             # the agreement is an order of magnitude closer
             same_g = O.loss_and_rep_grad(synth.widen(q), synth.widen(p), r.numpy(), scale, temp, g_dtype="bf16")
-            assert normerr(to_np(out["dp"]), same_g["dp"]) <= TOL_SAME_G
+            check(tag + " dp vs same-g", normerr(to_np(out["dp"]), same_g["dp"]), TOL_SAME_G)
             # the walk that forms the statistics as it goes rounds 2^(t - reference), not g, and adds the positive's
             # term in fp32, so the same-coefficient oracle is not the model of its dQ
             if d < 256 or path == gc.GC_PATH_STATS_PASS:
-                assert normerr(to_np(out["dq"]), same_g["dq"]) <= TOL_SAME_G
+                check(tag + " dq vs same-g", normerr(to_np(out["dq"]), same_g["dq"]), TOL_SAME_G)
 
 
 @pytest.mark.parametrize("B,P,d,temp", [(700, 1400, 128, 0.07), (500, 1000, 256, 0.05), (384, 2000, 768, 0.05)])
@@ -120,12 +121,13 @@ def test_peaked_softmax_at_low_temperature(B, P, d, temp):
     same_g = O.loss_and_rep_grad(q64, p64, r.numpy(), 1.0, temp, g_dtype="bf16")
     for path in PATHS:
         out = run_ex(q, p, r, 1.0, temp, flags=path)
-        assert abs(out["loss"].item() - want["loss"]) <= 1e-5 * abs(want["loss"])
-        assert relerr(to_np(out["lse"]), want["lse"]) <= 1e-5
+        tag = "peaked %dx%dx%d path %d" % (B, P, d, path)
+        check_loss(tag + " loss", out["loss"].item(), want["loss"], 1e-5)
+        check(tag + " lse", relerr(to_np(out["lse"]), want["lse"]), 1e-5)
         for k in ("dq", "dp"):
-            assert relerr(to_np(out[k]), want[k]) <= TOL_BF16_PEAKED
+            check(tag + " " + k, relerr(to_np(out[k]), want[k]), TOL_BF16_PEAKED)
             if k == "dp" or d < 256 or path == gc.GC_PATH_STATS_PASS:   # see test_bf16_shapes_and_edges
-                assert normerr(to_np(out[k]), same_g[k]) <= TOL_SAME_G
+                check(tag + " " + k + " vs same-g", normerr(to_np(out[k]), same_g[k]), TOL_SAME_G)
 
 
 @pytest.mark.parametrize("B,P,d,dtype", [(200, 700, 256, torch.bfloat16), (90, 300, 768, torch.bfloat16),
@@ -200,8 +202,8 @@ def test_cache_in_bf16(B, P, d, path):
     assert torch.equal(b16["dq"], f32["dq"].to(torch.bfloat16))
     assert torch.equal(b16["dp"], f32["dp"].to(torch.bfloat16))
     want = oracle_loss(q, p, r, 1.0, 0.5)
-    assert relerr(to_np(b16["dq"].float()), want["dq"]) <= TOL_BF16 + 2.0 ** -8
-    assert relerr(to_np(b16["dp"].float()), want["dp"]) <= TOL_BF16 + 2.0 ** -8
+    check("bf16 cache dq", relerr(to_np(b16["dq"].float()), want["dq"]), TOL_BF16 + 2.0 ** -8)
+    check("bf16 cache dp", relerr(to_np(b16["dp"].float()), want["dp"]), TOL_BF16 + 2.0 ** -8)
 
 
 def test_cache_in_bf16_needs_the_mfma_shapes():
@@ -220,7 +222,24 @@ def test_mask_self(n, d, dtype):
     want = oracle_loss(q, p, r, 1.0, 0.5, mask_self=True)
     for path in PATHS:
         out = run_ex(q, p, r, 1.0, 0.5, flags=gc.GC_MASK_SELF | path)
-        compare(out, want, TOL_BF16 if dtype == torch.bfloat16 else TOL_F32, q, p, 2.0)
+        compare(out, want, TOL_BF16 if dtype == torch.bfloat16 else TOL_F32, q, p, 2.0, label="mask_self n=%d d=%d path %d" % (n, d, path))
+
+
+@pytest.mark.parametrize("n,d,dtype", [(96, 128, torch.bfloat16), (70, 24, torch.float32), (322, 256, torch.bfloat16),
+                                       (200, 768, torch.bfloat16)])
+def test_mask_self_with_a_positive_on_the_diagonal_gives_an_infinite_loss(n, d, dtype):
+    """Eq. 1 with s_ii = -inf and r_i = i for one anchor: that anchor's positive logit is -inf, so the loss is
+    +inf (as in the oracle), never a stale or unmasked value; the other rows' statistics are unaffected."""
+    q, p, _ = synth.dpr_batch(n, n, d, dtype, seed=3100 + n)
+    r = torch.arange(n, dtype=torch.int32) ^ 1
+    r[5] = 5
+    want = oracle_loss(q, p, r, 1.0, 0.5, mask_self=True)
+    assert want["loss"] == math.inf
+    for path in PATHS:
+        out = run_ex(q, p, r, 1.0, 0.5, flags=gc.GC_MASK_SELF | path)
+        assert out["loss"].item() == math.inf, path
+        check("diagonal positive n=%d path %d lse" % (n, path), relerr(to_np(out["lse"]), want["lse"]),
+              TOL_BF16 if dtype == torch.bfloat16 else TOL_F32)
 
 
 def test_optional_outputs_and_reuse_of_workspace():
@@ -266,7 +285,9 @@ def test_config3_full_size_parity_invariants_and_reproducibility():
     want = oracle_loss(q, p, r)
     assert abs(want["loss"] - (math.log(8192) + 1 / 1536)) < 0.01
     out = run_ex(q, p, r)
-    compare(out, want, TOL_BF16, q, p, 1.0, gap_tol=2e-6)
+    compare(out, want, TOL_BF16, q, p, 1.0, gap_tol=2e-6, label="config3 (library's choice: online walk)")
+    # the other kernel sequence (statistics pass, then both walks in one launch: what every call without dq takes)
+    compare(run_ex(q, p, r, flags=gc.GC_PATH_STATS_PASS), want, TOL_BF16, q, p, 1.0, gap_tol=2e-6, label="config3 statistics pass")
     dq, dp = to_np(out["dq"]), to_np(out["dp"])
     q64, p64 = synth.widen(q), synth.widen(p)
     # I1: rows of softmax - Y sum to zero  =>  sum_j dp_j = 0

@@ -7,7 +7,7 @@ import torch
 from oracle import gc_oracle as O
 from paper_2101_06983_amd import binding as gc
 from paper_2101_06983_amd import synth
-from parity import TOL_BF16, relerr, to_np
+from parity import TOL_BF16, check, check_loss, relerr, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -21,8 +21,8 @@ def test_ntxent_small(n, d, tau):
     want = O.ntxent(synth.widen(z), tau)
     loss, dz = gc.gc_ntxent_loss_and_grad_bf16(z.to(DEV), tau)
     torch.cuda.synchronize()
-    assert abs(loss.item() - want["loss"]) <= TOL_BF16 * abs(want["loss"])
-    assert relerr(to_np(dz), want["dz"]) <= TOL_BF16
+    check_loss("ntxent n=%d d=%d loss" % (n, d), loss.item(), want["loss"], TOL_BF16)
+    check("ntxent n=%d d=%d dz" % (n, d), relerr(to_np(dz), want["dz"]), TOL_BF16)
 
 
 def test_config4_full_size():
@@ -32,8 +32,8 @@ def test_config4_full_size():
     assert abs(want["loss"] - (math.log(16383) + 1 / (2 * 128 * tau * tau))) < 0.1
     loss, dz = gc.gc_ntxent_loss_and_grad_bf16(z.to(DEV), tau)
     torch.cuda.synchronize()
-    assert abs(loss.item() - want["loss"]) <= TOL_BF16 * abs(want["loss"])
-    assert relerr(to_np(dz), want["dz"]) <= TOL_BF16
+    check_loss("config4 loss", loss.item(), want["loss"], TOL_BF16)
+    check("config4 dz", relerr(to_np(dz), want["dz"]), TOL_BF16)
     loss2, dz2 = gc.gc_ntxent_loss_and_grad_bf16(z.to(DEV), tau)
     torch.cuda.synchronize()
     assert torch.equal(dz, dz2) and loss.item() == loss2.item()
