@@ -10,8 +10,9 @@ B=4096 queries, P=8192 passages, d=768, bf16 storage, fp32 accumulate.  Inputs a
 resident in HBM before the timed region.  Prints ONE JSON line.
 
 value      algorithmic TFLOP/s = 6*B*P*d / step time (three GEMMs: S, G*P, G^T*Q)
-           K steps are timed with nothing else on the stream; the kernel times below
-           come from a second pass of K steps with HIP events at the kernel boundaries
+           K steps are timed with nothing else on the stream (mean); a second pass of K
+           steps, each between two HIP events, gives the median and the minimum; the
+           kernel times come from a third pass with HIP events at the kernel boundaries
            (the event records cost about 6 % of a step).
 roofline   for the dominant kernel (the dQ walk, grad_online_kernel<768>): the
            algorithmic flops of one launch (4*B*P*d: the scores and G*P, both of
@@ -34,9 +35,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# readings of a plain 1 GiB read + 1 GiB write kernel (profiles/loss_path_config3_rocprofv3.txt)
-TRAFFIC_BYTES = 101.7e6   # 51.2 MB read + 50.5 MB written
+PEAK_HBM_BYTES_PER_S = 8.0e12   # MI355X HBM3E, published
+PROFILE_FILE = os.path.join("profiles", "loss_path_config3_rocprofv3.txt")
+
+
+def counter_traffic():
+    """HBM bytes per launch of the dominant kernel.  Hardware counters cannot be read from inside this process: they
+    come from separate `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this same command, scaled by what
+    the same counters read for a plain copy kernel of known size, and are written down (with their date) in a
+    `TRAFFIC {json}` line of the committed summary under profiles/.  None if that file or line is missing."""
+    try:
+        for line in open(os.path.join(ROOT, PROFILE_FILE)):
+            if line.startswith("TRAFFIC "):
+                return json.loads(line[len("TRAFFIC "):])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def cpu_baseline(q, p, r, flops):
@@ -168,6 +182,16 @@ def main():
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # per-step durations: the same K steps again, each between two HIP events on the launch stream (torch's current
+    # stream, which the binding passes to the library): median and minimum beside the mean of the timed region
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in ev)
+    step_median, step_min = per_step[len(per_step) // 2], per_step[0]
     # kernel durations: the same K steps again with the library's HIP events at the kernel boundaries (on the launch
     # stream).  Five event records per step cost about 6 % of a step, so they stay out of the timed region above.
     gc.gc_profile_begin(args.steps)
@@ -188,10 +212,15 @@ def main():
     k_alg = 4.0 * B * P * d          # dQ walk: S and G*P, each formed once
     achieved = k_alg / (prof["ms_stats"] * 1e-3) / 1e12
     dp_alg = 2.0 * B * P * d / (prof["ms_grad"] * 1e-3) / 1e12
+    kernel_sum = prof["ms_stats"] + prof["ms_merge"] + prof["ms_grad"] + prof["ms_reduce"]
+    alg_bytes = (B + P) * d * 2 + (B + P) * d * 4 + B * 4 + 4      # read Q, P, pos_idx; write dq, dp, loss
+    tr = counter_traffic()
+    traffic = (tr["hbm_read_bytes"] + tr["hbm_write_bytes"]) if tr else None
     rec = {
         "metric": "loss+rep-grad TFLOP/s & ms/step at B=4096,P=8192,d=768 bf16; % MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms, 4), "ms_per_step_median": round(step_median, 4), "ms_per_step_min": round(step_min, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config3 large-batch ICT-shaped: B=4096 queries, P=8192 passages, d=768, bf16 storage, "
                                "fp32 accumulate, pos_idx[i]=2i, iid N(0,1/d)", "B": B, "P": P, "d": d,
@@ -199,7 +228,13 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "grad_online_kernel<768> (dQ walk with online statistics)",
                      "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": TRAFFIC_BYTES,
+                     "traffic": traffic,
+                     "traffic_from": ("%s (separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                                      "measured %s)" % (PROFILE_FILE, tr["measured"])) if tr else None,
+                     # fraction of the HBM peak the dominant kernel's counter traffic amounts to over its duration
+                     "hbm_frac": round(traffic / (prof["ms_stats"] * 1e-3) / PEAK_HBM_BYTES_PER_S, 4) if tr else None,
+                     # ... and the whole step's algorithmic bytes (inputs read once, outputs written once)
+                     "hbm_frac_algorithmic_whole_step": round(alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S, 4),
                      "dp_walk": {"kernel": "grad_mfma_kernel<768, false>", "achieved": round(dp_alg, 2),
                                  "frac": round(dp_alg / PEAK_BF16_TFLOPS, 4),
                                  "executed_frac": round(2 * dp_alg / PEAK_BF16_TFLOPS, 4)},
@@ -207,10 +242,9 @@ def main():
                                    "dp_walk": round(prof["ms_grad"], 4), "partial_sums_and_loss": round(prof["ms_reduce"], 4)},
                      "kernel_ms_from": "HIP events on the launch stream over a second pass of the same %d steps "
                                        "(%.4f ms/step with the events recorded)" % (args.steps, (t3 - t2) * 1e3 / args.steps),
+                     "kernel_ms_sum": round(kernel_sum, 4),
                      "whole_path_executed_frac": round(8.0 * B * P * d / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                     # a bare MFMA loop on operands of random data sustains this on the box (the published peak
-                     # is reached only when every MFMA reads the same constant registers)
-                     "mfma_rate_measured_with_random_operands": 1850.0},
+                     "whole_path_algorithmic_frac": round(6.0 * B * P * d / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(q, p, r, flops_alg)
