@@ -54,7 +54,8 @@ typedef enum {
   GC_ERR_UNSUPPORTED = -3, /* dtype, flag or shape combination not implemented */
   GC_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned (256 B) or smaller than the *_workspace_bytes value */
   GC_ERR_POS_IDX = -5,     /* reported by gc_check_async_error: some pos_idx[i] was outside [0, P) */
-  GC_ERR_HIP = -6          /* a HIP runtime call failed (launch, allocation) */
+  GC_ERR_HIP = -6,         /* a HIP runtime call failed (launch, allocation) */
+  GC_ERR_TOO_LARGE = -7    /* gc_loss_and_rep_grad_bf16_static: the shape needs more scratch than GC_STATIC_SCRATCH_BYTES */
 } gc_status;
 
 typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
@@ -99,6 +100,23 @@ int gc_loss_and_rep_grad_f32(const float* q, const float* p, const int32_t* pos_
                              float scale, float temp, float* loss, float* dq, float* dp, void* stream);
 
 /*
+ * The same call for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and bit-identical results as gc_loss_and_rep_grad_bf16, but
+ * the workspace (row statistics, split partial sums, the error word) is a fixed array of GC_STATIC_SCRATCH_BYTES in
+ * the library's device image, one copy per GPU, held until the process ends: the call makes no hipMalloc, hipFree
+ * or other allocating call, and its first use on a device only looks the array's address up.  Shapes with
+ * gc_workspace_bytes(B, P, d, GC_BF16) > GC_STATIC_SCRATCH_BYTES are rejected with GC_ERR_TOO_LARGE and nothing is
+ * enqueued (the limit covers e.g. B = 512, P = 1024, d = 768).  Every call on a GPU uses that GPU's one array,
+ * which keeps the previous call's contents (the kernels overwrite what they read): two calls that overlap in time
+ * on one GPU, on whatever streams, race; calls on one stream are safe.  A pos_idx outside [0, P) shows as
+ * loss = NaN, and gc_check_async_error(NULL) also reads this array's error word.
+ * Errors: GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_TOO_LARGE, GC_ERR_HIP.
+ */
+#define GC_STATIC_SCRATCH_BYTES (16u << 20)
+int gc_loss_and_rep_grad_bf16_static(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                                     float scale, float temp, float* loss, float* dq, float* dp, void* stream);
+
+/*
  * Extended form of the same computation.
  *   dt         type of q and p
  *   flags      0 or GC_MASK_SELF, optionally with one of GC_PATH_ONLINE / GC_PATH_STATS_PASS, and GC_CACHE_BF16
@@ -113,7 +131,8 @@ int gc_loss_and_rep_grad_ex(gc_dtype dt, const void* q, const void* p, const int
 
 /* After the stream has been synchronised by the caller: copies the device error
  * word of `workspace` to the host (a blocking 4-byte copy) and returns GC_OK or
- * GC_ERR_POS_IDX.  workspace == NULL checks the library's own per-device buffer. */
+ * GC_ERR_POS_IDX.  workspace == NULL checks the library's own per-device buffer
+ * and the static array of gc_loss_and_rep_grad_bf16_static (those that have been used). */
 int gc_check_async_error(const void* workspace);
 
 /*

@@ -14,6 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libgradcache.so")
 
 GC_OK = 0
 GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_POS_IDX, GC_ERR_HIP = -1, -2, -3, -4, -5, -6
+GC_ERR_TOO_LARGE = -7
+GC_STATIC_SCRATCH_BYTES = 16 << 20
 GC_F32, GC_BF16 = 0, 1
 GC_MASK_SELF = 1
 GC_PATH_ONLINE, GC_PATH_STATS_PASS = 2, 4
@@ -21,6 +23,7 @@ GC_CACHE_BF16 = 8
 
 EXPORTS = [
     "gc_strerror", "gc_workspace_bytes", "gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32",
+    "gc_loss_and_rep_grad_bf16_static",
     "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
     "gc_ntxent_loss_and_grad_bf16", "gc_bidirectional_workspace_bytes",
     "gc_bidirectional_loss_and_rep_grad_bf16", "gc_bilinear_workspace_bytes", "gc_bilinear_workspace_layout",
@@ -63,7 +66,7 @@ def load():
     lib.gc_strerror.argtypes = [ci]
     lib.gc_workspace_bytes.restype = sz
     lib.gc_workspace_bytes.argtypes = [ci, ci, ci, ci]
-    for name in ("gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32"):
+    for name in ("gc_loss_and_rep_grad_bf16", "gc_loss_and_rep_grad_f32", "gc_loss_and_rep_grad_bf16_static"):
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [vp, vp, vp, ci, ci, ci, cf, cf, vp, vp, vp, vp]
@@ -146,14 +149,20 @@ def gc_workspace_bytes(B, P, d, dt):
     return load().gc_workspace_bytes(B, P, d, dt)
 
 
-def _simple(fn_name, dtype, q, p, pos_idx, scale, temp, stream):
+def _simple(fn_name, dtype, q, p, pos_idx, scale, temp, stream, out=None):
     lib = load()
     _dev_contig(q, dtype, "q"); _dev_contig(p, dtype, "p"); _dev_contig(pos_idx, torch.int32, "pos_idx")
     B, d = q.shape
     P = p.shape[0]
-    loss = torch.empty(1, dtype=torch.float32, device=q.device)
-    dq = torch.empty(B, d, dtype=torch.float32, device=q.device)
-    dp = torch.empty(P, d, dtype=torch.float32, device=q.device)
+    if out is not None:
+        loss, dq, dp = out
+        _dev_contig(loss, torch.float32, "loss"); _dev_contig(dq, torch.float32, "dq"); _dev_contig(dp, torch.float32, "dp")
+        if loss.numel() != 1 or tuple(dq.shape) != (B, d) or tuple(dp.shape) != (P, d):
+            raise ValueError("preallocated outputs must be loss[1], dq[B,d], dp[P,d]")
+    else:
+        loss = torch.empty(1, dtype=torch.float32, device=q.device)
+        dq = torch.empty(B, d, dtype=torch.float32, device=q.device)
+        dp = torch.empty(P, d, dtype=torch.float32, device=q.device)
     rc = getattr(lib, fn_name)(_ptr(q), _ptr(p), _ptr(pos_idx), B, P, d, scale, temp, _ptr(loss), _ptr(dq), _ptr(dp),
                                _stream(stream))
     _check(rc, fn_name)
@@ -162,6 +171,12 @@ def _simple(fn_name, dtype, q, p, pos_idx, scale, temp, stream):
 
 def gc_loss_and_rep_grad_bf16(q, p, pos_idx, scale=1.0, temp=1.0, stream=None):
     return _simple("gc_loss_and_rep_grad_bf16", torch.bfloat16, q, p, pos_idx, scale, temp, stream)
+
+
+def gc_loss_and_rep_grad_bf16_static(q, p, pos_idx, scale=1.0, temp=1.0, stream=None, out=None):
+    """The call that allocates nothing inside the library (its workspace is a fixed array in the device image).
+    `out` = (loss, dq, dp) preallocated makes the whole call allocation-free."""
+    return _simple("gc_loss_and_rep_grad_bf16_static", torch.bfloat16, q, p, pos_idx, scale, temp, stream, out)
 
 
 def gc_loss_and_rep_grad_f32(q, p, pos_idx, scale=1.0, temp=1.0, stream=None):

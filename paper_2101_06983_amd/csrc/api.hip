@@ -6,6 +6,9 @@
 
 #include "gc_common.h"
 
+// The workspace of gc_loss_and_rep_grad_bf16_static (see static_scratch below): a fixed array in the device image.
+static __device__ __align__(256) unsigned char scratch[GC_STATIC_SCRATCH_BYTES];
+
 namespace gc {
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -152,6 +155,25 @@ static int own_workspace(size_t need, hipStream_t stream, void** out) {
   return GC_OK;
 }
 
+// ---- the workspace of the entry point that allocates nothing: a fixed array in the device image ---------------
+// One copy per GPU, at an address of its own.  Host code never uses the array's name as an address (on the host
+// it is only a handle for the lookup): the address is asked for once per device, with that device current, and
+// kept; kernels get it as an ordinary pointer argument, exactly as they get a caller's workspace.
+static void* g_scratch_ptr[64];   // per device: what hipGetSymbolAddress answered (under g_ws_mutex)
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return GC_ERR_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return GC_OK;
+}
+
 // ---- measurement aid: HIP events around the phases of the loss path ------------------------------
 struct Profile {
   bool on = false;
@@ -273,6 +295,7 @@ const char* gc_strerror(int status) {
     case GC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case GC_ERR_POS_IDX: return "pos_idx value outside [0, P)";
     case GC_ERR_HIP: return "HIP runtime call failed";
+    case GC_ERR_TOO_LARGE: return "shape needs more scratch than the static buffer holds (GC_STATIC_SCRATCH_BYTES)";
     default: return "unknown gc_status";
   }
 }
@@ -315,23 +338,43 @@ int gc_loss_and_rep_grad_bf16(const void* q, const void* p, const int32_t* pos_i
   return simple_loss(GC_BF16, q, p, pos_idx, B, P, d, scale, temp, loss, dq, dp, stream);
 }
 
+int gc_loss_and_rep_grad_bf16_static(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                                     float scale, float temp, float* loss, float* dq, float* dp, void* stream) {
+  int rc = check_loss_args(GC_BF16, q, p, pos_idx, B, P, d, scale, temp, 0);
+  if (rc != GC_OK) return rc;
+  if (!loss || !dq || !dp) return GC_ERR_NULL;
+  const size_t need = make_loss_plan(B, P, d, GC_BF16, false).total;
+  if (need > (size_t)GC_STATIC_SCRATCH_BYTES) return GC_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != GC_OK) return rc;
+  // every word of the workspace that a kernel of this path reads has been written by an earlier kernel of the same
+  // call (statistics, partial sums, the error word): nothing has to start at zero
+  return gc_loss_and_rep_grad_ex(GC_BF16, q, p, pos_idx, B, P, d, scale, temp, 0, loss, dq, dp, nullptr, nullptr, ws,
+                                 need, stream);
+}
+
 int gc_loss_and_rep_grad_f32(const float* q, const float* p, const int32_t* pos_idx, int B, int P, int d, float scale,
                              float temp, float* loss, float* dq, float* dp, void* stream) {
   return simple_loss(GC_F32, q, p, pos_idx, B, P, d, scale, temp, loss, dq, dp, stream);
 }
 
 int gc_check_async_error(const void* workspace) {
-  const void* ws = workspace;
-  if (!ws) {
+  const void* ws[2] = {workspace, nullptr};
+  if (!workspace) {   // the library's own buffers of this device, as far as they have been used
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    ws = g_ws_ptr[dev];
-    if (!ws) return GC_OK;  // nothing has run yet
+    ws[0] = g_ws_ptr[dev];
+    ws[1] = g_scratch_ptr[dev];
   }
-  int word = 0;
-  if (hipMemcpy(&word, ws, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return GC_ERR_HIP;
-  return word ? GC_ERR_POS_IDX : GC_OK;
+  for (const void* w : ws) {
+    if (!w) continue;
+    int word = 0;
+    if (hipMemcpy(&word, w, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return GC_ERR_HIP;
+    if (word) return GC_ERR_POS_IDX;
+  }
+  return GC_OK;
 }
 
 int gc_profile_begin(int max_calls) {

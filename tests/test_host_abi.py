@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_strerror_texts():
     assert gc.strerror(0) == "ok"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert gc.strerror(code) and "unknown" not in gc.strerror(code)
     assert "unknown" in gc.strerror(-99)
 
@@ -65,6 +65,11 @@ def test_argument_errors_are_raised_on_the_host():
     assert f(fake, fake, fake, 8, 16, 128, 1.0, 0.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
     assert f(fake, fake, fake, 8, 16, 128, float("nan"), 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
     assert f(fake, fake, fake, 8, 16, 128, float("inf"), 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    st = lib.gc_loss_and_rep_grad_bf16_static
+    assert st(None, fake, fake, 8, 16, 128, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_NULL
+    assert st(fake, fake, fake, 8, 16, 128, 1.0, 1.0, fake, None, fake, None) == gc.GC_ERR_NULL
+    assert st(fake, fake, fake, 8, 0, 128, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_SHAPE
+    assert st(fake, fake, fake, 4096, 8192, 768, 1.0, 1.0, fake, fake, fake, None) == gc.GC_ERR_TOO_LARGE
     ex = lib.gc_loss_and_rep_grad_ex
     args = lambda **k: [k.get("dt", gc.GC_BF16), fake, fake, fake, k.get("B", 8), k.get("P", 16), 128, 1.0, 1.0,
                         k.get("flags", 0), fake, fake, fake, None, None, k.get("ws", fake), k.get("wsb", 1 << 30), None]
