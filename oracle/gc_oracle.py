@@ -34,19 +34,13 @@ def _f64(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
 
 
-def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False, g_dtype=None):
+def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False):
     """Contrastive loss (Eq. 1) and its representation gradients (Eq. 4-7).
 
     q: [B, d] anchors f(s_i); p: [P, d] targets g(t_j); pos_idx: [B] ints r_i.
     Logits are s_ij = (scale / temp) * <q_i, p_j>  (Eq. 1 with the 1/tau kept;
     `scale` is an extra multiplier on the dot product, 1 in the paper).
     mask_self: s_ii = -inf (needs B == P), used by the NT-Xent variation.
-    g_dtype: None is the definition in fp64 throughout.  "bf16" rounds the
-    coefficients g_ij = p_ij - [j == r_i] to bf16 (nearest even) before the two
-    contractions of Eq. 5 and Eq. 6, which are still summed in fp64: the value
-    of a path that feeds those contractions bf16 operands.  Each g_ij then
-    carries a relative error of at most 2^-8, so dq and dp stay within 2^-8 of
-    sum_j |g_ij| |p_j| resp. sum_i |g_ij| |q_i| of the definition.
 
     Returns dict with
       loss      Eq. 1, mean over the B anchors
@@ -86,9 +80,6 @@ def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False, g_dty
     # g_ij = p_ij - [j == r_i]
     g = np.exp(s - lse[:, None])
     g[np.arange(B), r] -= 1.0
-    if g_dtype is not None:
-        assert g_dtype == "bf16"
-        g = round_to_bf16(g)
 
     # Eq. 5:  dL/df(s_i) = -(1/|S|) (g(t_{r_i}) - sum_j p_ij g(t_j))      (* alpha)
     dq = (alpha / B) * (g @ p)
@@ -98,7 +89,7 @@ def loss_and_rep_grad(q, p, pos_idx, scale=1.0, temp=1.0, mask_self=False, g_dty
                 argmax=argmax.astype(np.int64), dq=dq, dp=dp)
 
 
-def ntxent(z, temp, g_dtype=None):
+def ntxent(z, temp):
     """NT-Xent over 2N views (the loss variation named in Sec. Related Work /
     Step 2's remark that other contrastive losses are supported).
 
@@ -113,11 +104,11 @@ def ntxent(z, temp, g_dtype=None):
     n = z.shape[0]
     assert n % 2 == 0 and n >= 2
     r = np.arange(n) ^ 1
-    out = loss_and_rep_grad(z, z, r, scale=1.0, temp=temp, mask_self=True, g_dtype=g_dtype)
+    out = loss_and_rep_grad(z, z, r, scale=1.0, temp=temp, mask_self=True)
     return dict(loss=out["loss"], dz=out["dq"] + out["dp"], lse=out["lse"])
 
 
-def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0, g_dtype=None):
+def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0):
     """Symmetric in-batch-negative loss: anchors against targets and targets
     against anchors (one of the loss variations Step 2 admits; the method only
     needs dL/df(s_i) and dL/dg(t_j)).  B = P = n and r must be a bijection:
@@ -129,7 +120,6 @@ def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0, g_dtype=None):
       g_ij = 1/2 (p^row_ij + p^col_ij) - [j == r_i],
     and dL/df(s_i) = (alpha/n) sum_j g_ij g(t_j), dL/dg(t_j) = (alpha/n) sum_i g_ij f(s_i)
     (Eq. 5 of one term plus Eq. 6 of the other, halved).
-    g_dtype="bf16" rounds g_ij before the two contractions, as in loss_and_rep_grad.
     Returns dict(loss, dq, dp)."""
     q = _f64(q)
     p = _f64(p)
@@ -145,13 +135,10 @@ def bidirectional(q, p, pos_idx, scale=1.0, temp=1.0, g_dtype=None):
     loss = 0.5 * (np.sum(lse_row - pos) + np.sum(lse_col[r] - pos)) / n
     g = 0.5 * (np.exp(s - lse_row[:, None]) + np.exp(s - lse_col[None, :]))
     g[np.arange(n), r] -= 1.0
-    if g_dtype is not None:
-        assert g_dtype == "bf16"
-        g = round_to_bf16(g)
     return dict(loss=float(loss), dq=(alpha / n) * (g @ p), dp=(alpha / n) * (g.T @ q))
 
 
-def bilinear_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, rep_dtype=None, g_dtype=None):
+def bilinear_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, rep_dtype=None):
     """Loss with a parameterised distance function (Sec. "Extend to Deep Distance
     Function"), for the bilinear form Phi_Omega(f, g) = f^T Omega g, Omega [d, d]:
       d_ij = f(s_i)^T Omega g(t_j)                     (the section's first equation)
@@ -164,7 +151,6 @@ def bilinear_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, rep_dtype=None,
     rep_dtype="bf16": the products h_i = Omega^T f(s_i) are stored in bf16 before
     they meet the targets (scores d_ij = <h_i, g(t_j)> and v_j = sum_i w_ij h_i use
     the stored values); u and dOmega flow through the unrounded bilinear form.
-    g_dtype="bf16": w is rounded to bf16 (in units of alpha/B) before it is contracted.
     Returns dict(loss, w, u, v, domega)."""
     q = _f64(q)
     p = _f64(p)
@@ -182,9 +168,6 @@ def bilinear_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, rep_dtype=None,
     loss = np.sum(lse - s[np.arange(B), r]) / B
     g = np.exp(s - lse[:, None])
     g[np.arange(B), r] -= 1.0
-    if g_dtype is not None:
-        assert g_dtype == "bf16"
-        g = round_to_bf16(g)
     w = (alpha / B) * g
     a = w @ p                                    # sum_j w_ij g(t_j)
     return dict(loss=float(loss), w=w, u=a @ om.T, v=w.T @ h, domega=q.T @ a)
@@ -248,9 +231,8 @@ def _zeros_like_params(params):
 
 def round_to_bf16(a):
     """Round-to-nearest-even of every entry to the bf16 grid (8 significant bits),
-    returned as float64.  Used for two stated storage precisions: representations
-    that a workload keeps in bf16 (Step 1 stores all representations), and the
-    coefficients g_ij of Eq. 5-6 when g_dtype="bf16" is asked for.
+    returned as float64.  Used for one stated storage precision: representations
+    that a workload keeps in bf16 (Step 1 stores all representations).
     Pinned against torch's bfloat16 cast in the tests."""
     x = np.ascontiguousarray(np.asarray(a, dtype=np.float64).astype(np.float32))
     u = x.view(np.uint32).astype(np.uint64)

@@ -106,9 +106,12 @@ LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent) {
   pl.off_lse2 = take((size_t)pl.b_pad * 4);
   pl.off_pos_pad = take((size_t)pl.b_pad * 4);
   pl.off_rowloss = take((size_t)B * 4);
+  // an anchor per target (see PosFix); among the statistics: everything below off_dq_part is what a call that only
+  // forms statistics touches (the symmetric loss sizes its second workspace by that)
+  pl.off_inv = take(pl.use_mfma ? (size_t)P * 4 : 0);
   int dq_parts = (pl.nsq > 1 || ntxent) ? pl.nsq : 0, dp_parts = ((pl.nsp > 1 || ntxent) && !pl.one_walk) ? pl.nsp : 0;
-  if (pl.use_mfma && !ntxent) {  // a bf16 cache (GC_CACHE_BF16) always goes through a partial
-    if (dq_parts < 1) dq_parts = 1;
+  if (pl.use_mfma && !ntxent) {  // the MFMA walks always write partials: the kernel that sums them adds the
+    if (dq_parts < 1) dq_parts = 1;  // positive's term in fp32 (PosFix) and rounds a bf16 cache
     if (dp_parts < 1) dp_parts = 1;
   }
   if (pl.fused) {
@@ -192,10 +195,7 @@ bool prof_active() { return g_prof.on; }
 static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   LossArgs a = a_in;
   // does the gradient pass of this call end in a sum of split partials (launch_grad_mfma)?
-  const bool cache_bf16 = (a.flags & GC_CACHE_BF16) != 0;
-  a.loss_with_partials = pl.use_mfma && !a.lse2_t &&
-                         (a.dz ? (!pl.one_walk || pl.nsq > 1)
-                               : ((a.dq && (pl.nsq > 1 || cache_bf16)) || (a.dp && (pl.nsp > 1 || cache_bf16))));
+  a.loss_with_partials = pl.use_mfma && !a.lse2_t && (a.dz || a.dq || a.dp);
   const int call = g_prof.calls;
   prof_mark(call, 0, a.stream);
   hipError_t e;
@@ -214,8 +214,8 @@ static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
       LossPlan pb = pl;
       b.dq = nullptr;
       pb.nsp = pl.fz_nsp; pb.p_stream_len = pl.fz_p_stream_len;
-      b.loss_with_partials = pb.nsp > 1 || cache_bf16;
-      loss_done = b.loss_with_partials;
+      b.loss_with_partials = true;   // the dP walk always ends in the sum of its partials
+      loss_done = true;
       e = launch_grad_mfma(b, pb);   // records mark 3 after the walk
       if (e != hipSuccess) return GC_ERR_HIP;
     } else {
@@ -498,6 +498,8 @@ int gc_bidirectional_loss_and_rep_grad_bf16(const void* q, const void* p, const 
     // ... and one gradient pass with the mean of the two softmaxes as coefficients
     a.q = q; a.p = p; a.pos_idx = pos_idx; a.loss = nullptr; a.ws = ws; a.dq = dq; a.dp = dp;
     a.lse2_t = (const float*)(ws + sp.off2 + sp.pl.off_lse2);
+    a.pos_inv = rinv;
+    a.zero_word = (const int*)(ws + sp.pl.off_err) + 1;   // zeroed by the first direction's merge, raised by nobody here
     rc = run_loss(a, sp.pl);
     if (rc != GC_OK) return rc;
   } else {

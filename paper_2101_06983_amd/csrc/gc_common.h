@@ -54,7 +54,7 @@ struct LossPlan {
   // merges its splits into lse2 and dQ, then the dP walk.  Each walk fills the GPU alone, so they have splits of their own
   int fused, fused_auto, fz_nsq, fz_nsp, fz_q_stream_len, fz_p_stream_len;   // can run / is chosen without a flag
   size_t off_err, off_part_m, off_part_l, off_part_idx, off_pos, off_lse2, off_pos_pad, off_rowloss, off_dq_part,
-      off_dp_part, off_pos_idx, off_on_ref, total;
+      off_dp_part, off_pos_idx, off_on_ref, off_inv, total;
 };
 
 LossPlan make_loss_plan(int B, int P, int d, gc_dtype dt, bool ntxent);
@@ -77,12 +77,35 @@ struct LossArgs {
   // symmetric loss in one gradient pass (MFMA kernels only): log2-domain log-sum-exp per target over the anchors,
   // padded like the per-anchor one; with it set the statistics of this call are taken as already in `ws`
   const float* lse2_t;
+  // ... with the inverse of the pairing (pos_inv[r_i] = i, a bijection there) and a device word that holds 0, for
+  // the positive's term of the dP rows (PosFix)
+  const int32_t* pos_inv;
+  const int* zero_word;
   // set by run_loss when the gradient pass ends in a sum of split partials: that launch then also sums the row
   // losses (one launch less); the statistics merge leaves the sum to it
   bool loss_with_partials;
   bool defer_loss_sum;   // the caller sums the row losses itself (the symmetric loss: both directions in one launch)
   char* ws;
   hipStream_t stream;
+};
+
+// The positive's own term of Eq. 5 / Eq. 6, (p_{i r_i} - 1) g(t_{r_i}) resp. (p_{i r_i} - 1) f(s_i), is not part of the bf16
+// contractions of the MFMA walks (they take the coefficient 0 at the positive): rounded to bf16, this one coefficient
+// of size up to 1 next to P - 1 small ones would be the whole error of its gradient row.  The kernel that sums the
+// split partials adds it in fp32 from the row statistics:
+//   c_i = scale * (2^(pos_t_i - lse2_i) - 1)                                       one direction
+//   c_i = scale * (1/2 (2^(pos_t_i - lse2_i) + 2^(pos_t_i - lse2_t[r_i])) - 1)     symmetric loss, NT-Xent
+struct PosFix {
+  int mode;                     // 0: nothing to add; 1: output rows are anchors (dq, dz); 2: output rows are targets (dp)
+  const int32_t* pos;           // [B] r_i
+  const int32_t* inv;           // mode 2: [P], inv[j] = an anchor i with r_i = j where there is one (always checked)
+  const int* shared;            // mode 2: nonzero when some target is the positive of several anchors (then: a scan)
+  const float* pos_t;           // [B] base-2 logit of the positive
+  const float* lse2;            // [B] base-2 log-sum-exp per anchor
+  const float* lse2_t;          // [P] the same per target over the anchors (symmetric forms), else nullptr
+  const unsigned short* other;  // bf16 rows that the term multiplies: targets (mode 1), anchors (mode 2)
+  int B, P, d;
+  float scale;
 };
 
 // kernel-launching halves (one per .hip file)
@@ -101,6 +124,6 @@ bool prof_active();  // the measurement events of the loss path are being record
 // loss_of / pl: also carry the sum of the row losses of that call (see LossArgs::loss_with_partials)
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
                                  int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of = nullptr,
-                                 const LossPlan* pl = nullptr, bool out_bf16 = false);
+                                 const LossPlan* pl = nullptr, bool out_bf16 = false, const PosFix* fix = nullptr);
 
 }  // namespace gc

@@ -107,8 +107,10 @@ __global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restric
                                                          const int32_t* __restrict__ pos_idx, int B, int P, int nsplit,
                                                          int b_pad, float* __restrict__ lse2, int32_t* __restrict__ pos_pad,
                                                          float* __restrict__ rowloss, float* __restrict__ lse_out,
-                                                         int32_t* __restrict__ argmax_out) {
+                                                         int32_t* __restrict__ argmax_out, int32_t* __restrict__ inv,
+                                                         int* __restrict__ shared) {
   constexpr int ROWS = 256 / LANES;
+  if (shared && blockIdx.x == 0 && threadIdx.x == 0) *shared = 0;   // raised later by the gradient kernel's check
   const int s = threadIdx.x % LANES;
   const int i = blockIdx.x * ROWS + threadIdx.x / LANES;
   const bool live = (i < B) && (s < nsplit);
@@ -136,6 +138,7 @@ __global__ void __launch_bounds__(256) stats_merge_kernel(const float* __restric
   pos_pad[i] = r;
   const bool ok = (r >= 0 && r < P);
   rowloss[i] = ok ? (l2 - pos_t[i]) * kLn2 : NAN;
+  if (inv && ok) inv[r] = i;   // an anchor per target; which one, when several share it, is not relied upon
   if (lse_out) lse_out[i] = l2 * kLn2;
   if (argmax_out) argmax_out[i] = bi;
 }
@@ -251,7 +254,20 @@ struct ReduceSrc {
 };
 // With a loss sum attached the grid has one more workgroup, the first (so that it runs beside the others), which carries it (it has nothing to do with
 // the partial sums; it only saves a launch on the path that needs both).
-__global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__ out, ReduceSrc rs, size_t n4, LossSum ls) {
+// coefficient of the positive of anchor i (target r), see PosFix
+__device__ __forceinline__ float pos_coeff(const PosFix& f, int i, int r) {
+  const float t = f.pos_t[i];
+  float c = exp2f(t - f.lse2[i]);
+  if (f.lse2_t) c = 0.5f * (c + exp2f(t - f.lse2_t[r]));
+  return f.scale * (c - 1.f);
+}
+__device__ __forceinline__ void add_row4(f32x4& acc, float c, const unsigned short* row, int col) {
+  const s16x4 v = *(const s16x4*)(row + col);
+#pragma unroll
+  for (int k = 0; k < 4; k++) acc[k] += c * bf2f((unsigned short)v[k]);
+}
+__global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__ out, ReduceSrc rs, size_t n4, LossSum ls,
+                                                            PosFix fx) {
   __shared__ float red[1024];
   if (ls.rowloss && blockIdx.x == 0) {
     loss_sum_block<256>(ls, red);
@@ -262,6 +278,19 @@ __global__ void __launch_bounds__(256) partial_reduce_kernel(float* __restrict__
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < rs.nsrc; s++)
     for (int k = 0; k < rs.count[s]; k++) acc += ((const f32x4*)(rs.ptr[s] + (size_t)k * rs.stride[s]))[e];
+  if (fx.mode) {   // the positive's term, in fp32, after the partials (d is a multiple of 4 here)
+    const int row = (int)((e * 4) / (size_t)fx.d), col = (int)((e * 4) % (size_t)fx.d);
+    if (fx.mode == 1) {
+      const int r = fx.pos[row];
+      if (r >= 0 && r < fx.P) add_row4(acc, pos_coeff(fx, row, r), fx.other + (size_t)r * fx.d, col);
+    } else if (*fx.shared == 0) {
+      const int i = fx.inv[row];   // whatever the workspace held if no anchor names this target: checked
+      if (i >= 0 && i < fx.B && fx.pos[i] == row) add_row4(acc, pos_coeff(fx, i, row), fx.other + (size_t)i * fx.d, col);
+    } else {   // some target is shared: every anchor that names this one, in index order
+      for (int i = 0; i < fx.B; i++)
+        if (fx.pos[i] == row) add_row4(acc, pos_coeff(fx, i, row), fx.other + (size_t)i * fx.d, col);
+    }
+  }
   if (rs.out_bf16) {
     typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
     ((bf16x4_t*)out)[e] = __builtin_convertvector(acc, bf16x4_t);
@@ -293,9 +322,11 @@ struct FinishArgs {
   float out_scale;
   float* lse2; int32_t* pos_pad; float* rowloss; float* lse_out; int32_t* argmax_out; float* dq;
   int dq_bf16;   // dq points to bf16 elements
+  int32_t* inv; int* shared;   // an anchor per target and the "several anchors share a target" word (see PosFix)
 };
 __global__ void __launch_bounds__(256) online_finish_kernel(FinishArgs f) {
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *f.shared = 0;   // raised later by the dP walk's check
   if (i >= f.b_pad) return;
   if (i >= f.B) {
     if (lane == 0) { f.lse2[i] = INFINITY; f.pos_pad[i] = -1; }
@@ -326,6 +357,7 @@ __global__ void __launch_bounds__(256) online_finish_kernel(FinishArgs f) {
     f.lse2[i] = l2;
     f.pos_pad[i] = r;
     f.rowloss[i] = ok ? (l2 - pos) * kLn2 : NAN;
+    if (ok) f.inv[r] = i;
     if (f.lse_out) f.lse_out[i] = l2 * kLn2;
     if (f.argmax_out) {
       float bv = -INFINITY; int bi = 0x7fffffff;
@@ -371,6 +403,7 @@ hipError_t launch_online_finish(const LossArgs& a, const LossPlan& pl) {
   f.out_scale = a.alpha / (float)a.B * (a.grad_mul != 0.f ? a.grad_mul : 1.f);
   f.lse2 = (float*)(ws + pl.off_lse2); f.pos_pad = (int32_t*)(ws + pl.off_pos_pad); f.rowloss = (float*)(ws + pl.off_rowloss);
   f.lse_out = a.lse; f.argmax_out = a.argmax; f.dq = a.dq; f.dq_bf16 = (a.flags & GC_CACHE_BF16) ? 1 : 0;
+  f.inv = (int32_t*)(ws + pl.off_inv); f.shared = (int*)(ws + pl.off_err) + 1;
   online_finish_kernel<<<(pl.b_pad + 3) / 4, 256, 0, a.stream>>>(f);
   return hipGetLastError();
 }
@@ -384,16 +417,19 @@ static LossSum loss_sum_of(const LossArgs& a, const LossPlan& pl) {
 
 hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int* counts, const size_t* strides,
                                  int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of, const LossPlan* pl,
-                                 bool out_bf16) {
+                                 bool out_bf16, const PosFix* fix) {
   ReduceSrc rs{};
   rs.nsrc = nsrc;
   rs.out_bf16 = out_bf16 ? 1 : 0;
   for (int s = 0; s < nsrc; s++) { rs.ptr[s] = srcs[s]; rs.count[s] = counts[s]; rs.stride[s] = strides[s]; }
   LossSum ls{};
   if (loss_of) ls = loss_sum_of(*loss_of, *pl);
+  PosFix fx{};
+  if (fix) fx = *fix;
+  if (fx.mode && (n % 4 || fx.d % 4)) return hipErrorInvalidValue;   // the term is added by the 4-element kernel only
   size_t n4 = n / 4;
   if (n4 || loss_of)
-    partial_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256 + (loss_of ? 1 : 0))), 256, 0, stream>>>(out, rs, n4, ls);
+    partial_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256 + (loss_of ? 1 : 0))), 256, 0, stream>>>(out, rs, n4, ls, fx);
   if (n4 * 4 < n) partial_reduce_tail_kernel<<<1, 256, 0, stream>>>(out, rs, n4 * 4, n);
   return hipGetLastError();
 }
@@ -441,7 +477,8 @@ hipError_t launch_stats_merge(const LossArgs& a, const LossPlan& pl) {
     stats_merge_kernel<LANES><<<(pl.b_pad + ROWS - 1) / ROWS, 256, 0, a.stream>>>(
         (const float*)(ws + pl.off_part_m), (const float*)(ws + pl.off_part_l), (const int*)(ws + pl.off_part_idx),
         (const float*)(ws + pl.off_pos), a.pos_idx, a.B, a.P, pl.stat_splits, pl.b_pad, (float*)(ws + pl.off_lse2),
-        (int32_t*)(ws + pl.off_pos_pad), (float*)(ws + pl.off_rowloss), a.lse, a.argmax);
+        (int32_t*)(ws + pl.off_pos_pad), (float*)(ws + pl.off_rowloss), a.lse, a.argmax,
+        pl.use_mfma ? (int32_t*)(ws + pl.off_inv) : nullptr, pl.use_mfma ? (int*)(ws + pl.off_err) + 1 : nullptr);
   };
   if (pl.stat_splits <= 1) merge(std::integral_constant<int, 1>{});
   else if (pl.stat_splits <= 4) merge(std::integral_constant<int, 4>{});

@@ -424,7 +424,22 @@ struct GradArgs {
   float* on_ref; float* on_l; int* on_idx; float* on_pos;
   float* on_best;  // per split and anchor: the true maximum, written (with on_idx) only when on_argmax is set
   int on_argmax;   // track the true maximum and its first index
+  // an anchor per target, as the statistics merge left it, and the word that check_shared_positives raises
+  const int32_t* inv; int* shared;
 };
+
+// The kernel that sums the partials adds each positive's own term to its dP row through inv[j] (an anchor with
+// r_i = j).  That is enough when no two anchors share a target; here every workgroup looks at a slice of the anchors
+// and raises *shared when one of them is not the anchor recorded for its target (the sum kernel then scans).
+__device__ __forceinline__ void check_shared_positives(const GradArgs& ga) {
+  if (!ga.inv) return;
+  const int per = (ga.B + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int i0 = (int)blockIdx.x * per, i1 = min(ga.B, i0 + per);
+  for (int i = i0 + (int)threadIdx.x; i < i1; i += (int)blockDim.x) {
+    const int r = ga.pos_pad[i];
+    if (r >= 0 && r < ga.Pn && ga.inv[r] != i) *ga.shared = 1;
+  }
+}
 
 // max / sum over the four lanes that share lane % 16 (v_permlane16_swap / v_permlane32_swap give every lane both
 // partners' values, so all four lanes end with the same bits)
@@ -877,8 +892,9 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
           for (int e = 0; e < 4; e++)
             gv[e] = fast_exp2(__builtin_fmaf(sv[e], ga.alpha2, -(lse_a + 1.f))) + fast_exp2(__builtin_fmaf(sv[e], ga.alpha2, -(lse_r[e] + 1.f)));
         }
-        // the rest touches few tiles and is decided per wave: -1 at the positive (j == r_i), zeros for rows
-        // past the end of the split and on the diagonal (i == j)
+        // the rest touches few tiles and is decided per wave: 0 at the positive (j == r_i; its term is added in fp32
+        // by the kernel that sums the partials, see PosFix), zeros for rows past the end of the split and on the
+        // diagonal (i == j)
         bool hit_any;
         if (OWNER_IS_Q) hit_any = (unsigned)(r_a - b0) < 4u;
         else hit_any = (pos_r[0] == a_q) | (pos_r[1] == a_q) | (pos_r[2] == a_q) | (pos_r[3] == a_q);
@@ -889,8 +905,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 #pragma unroll
           for (int e = 0; e < 4; e++) {
             const bool hit = OWNER_IS_Q ? (r_a - b0 == e) : (pos_r[e] == a_q);
-            if (hit) gv[e] -= 1.f;
-            if (b0 + e >= send || (ga.mask_self && b0 + e == a_q)) gv[e] = 0.f;
+            if (hit || b0 + e >= send || (ga.mask_self && b0 + e == a_q)) gv[e] = 0.f;
           }
         }
         gq = __builtin_convertvector(gv, bf16x4);
@@ -1174,7 +1189,8 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
       if constexpr (STEADY) __builtin_amdgcn_sched_barrier(0);  // the rounds stay in order
     });
     if (sm) {
-      // -1 at the positive (j == r_i), zeros for rows past the end of the split and on the diagonal: few tiles
+      // 0 at the positive (j == r_i: its term is added in fp32 by the kernel that sums the partials, see PosFix),
+      // zeros for rows past the end of the split and on the diagonal: few tiles
       bool rare = (t0 + G1_T > send) || (ga.mask_self && (t0 < a0 + G1_OWN_W) && (t0 + G1_T > a0));
       if (OWNER_IS_Q) {
         rare = rare || (unsigned)(r_o[0] - t0) < (unsigned)G1_T || (unsigned)(r_o[1] - t0) < (unsigned)G1_T;
@@ -1191,8 +1207,7 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
           for (int r = 0; r < 16; r++) {
             const int m = t0 + 8 * (r >> 2) + 4 * h + (r & 3);   // streamed row of this register
             const bool hit = OWNER_IS_Q ? (r_o[n] == m) : (pos_r[r >> 2][r & 3] == own_idx[n]);
-            if (hit) sacc[PT ^ 1][n][r] -= 1.f;
-            if (m >= send || (ga.mask_self && m == own_idx[n])) sacc[PT ^ 1][n][r] = 0.f;
+            if (hit || m >= send || (ga.mask_self && m == own_idx[n])) sacc[PT ^ 1][n][r] = 0.f;
           }
       }
     }
@@ -1247,6 +1262,7 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
 template <bool SYM>
 __global__ void __launch_bounds__(256) grad128_kernel(GradArgs ga) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
+  check_shared_positives(ga);
   const int nQ = ga.obQ * ga.nsq;
   const int id = xcd_task_id();
   if (id < nQ) {
@@ -1443,6 +1459,7 @@ static hipError_t launch_stats128(const LossArgs& a, const LossPlan& pl) {
 template <int D, bool SYM>
 __global__ void __launch_bounds__(256) grad_mfma_kernel(GradArgs ga) {
   extern __shared__ __attribute__((aligned(16))) unsigned char gsmem[];
+  check_shared_positives(ga);
   const int nQ = ga.obQ * ga.nsq;
   const int id = xcd_task_id();
   if (id < nQ) {
@@ -1533,11 +1550,14 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   const int own = (a.d == 128) ? G1_OWN : GR_OWN;   // owner rows per workgroup
   ga.obQ = want_q ? (a.B + own - 1) / own : 0; ga.nsq = pl.nsq; ga.q_stream_len = pl.q_stream_len;
   ga.obP = want_p ? (a.P + own - 1) / own : 0; ga.nsp = pl.nsp; ga.p_stream_len = pl.p_stream_len;
-  // a bf16 cache is rounded by the kernel that sums the partials: with it even a single split goes through that kernel
+  // every output goes through the kernel that sums the split partials (a single split included): it adds the
+  // positive's term in fp32 (PosFix) and rounds a bf16 cache
   const bool cache_bf16 = (a.flags & GC_CACHE_BF16) != 0;
-  const bool q_direct = (pl.nsq == 1 && (!a.dz || one_walk)) && !cache_bf16, p_direct = (pl.nsp == 1 && !a.dz) && !cache_bf16;
-  ga.dq_out = q_direct ? (one_walk ? a.dz : a.dq) : (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
-  ga.dp_out = p_direct ? a.dp : (float*)(ws + pl.off_dp_part); ga.dp_split_stride = np;
+  ga.dq_out = (float*)(ws + pl.off_dq_part); ga.dq_split_stride = nq;
+  ga.dp_out = (float*)(ws + pl.off_dp_part); ga.dp_split_stride = np;
+  // the symmetric loss inverts its pairing itself (a bijection); one direction: the merge left an anchor per target
+  const bool sym_pairs = a.lse2_t != nullptr;
+  if (want_p && !sym_pairs) { ga.inv = (const int32_t*)(ws + pl.off_inv); ga.shared = (int*)(ws + pl.off_err) + 1; }
   const int nwg = ga.obQ * ga.nsq + ga.obP * ga.nsp;
   if (nwg == 0) { prof_mark_grad_kernel_done(a.stream); return hipSuccess; }
   hipError_t e;
@@ -1552,28 +1572,29 @@ hipError_t launch_grad_mfma(const LossArgs& a, const LossPlan& pl) {
   }
   if (e != hipSuccess) return e;
   prof_mark_grad_kernel_done(a.stream);
-  // fixed-order sums of the split partials; the first of these launches also sums the row losses if asked to
+  // fixed-order sums of the split partials, each with the positive's term of its rows; the first of these
+  // launches also sums the row losses if asked to
+  PosFix fx{};
+  fx.pos = ga.pos_pad; fx.pos_t = (const float*)(ws + pl.off_pos); fx.lse2 = ga.lse2; fx.lse2_t = ga.lse2_t;
+  fx.B = a.B; fx.P = a.P; fx.d = a.d; fx.scale = ga.out_scale;
   const LossArgs* loss_of = a.loss_with_partials ? &a : nullptr;
-  if (one_walk) {
-    if (q_direct) return hipSuccess;
+  if (a.dz) {   // NT-Xent, one walk: rows are anchors, the positive of view i is view i ^ 1
+    fx.mode = 1; fx.other = ga.P;
     const float* srcs[1] = {ga.dq_out}; int counts[1] = {pl.nsq}; size_t strides[1] = {nq};
-    return launch_partial_reduce(a.dz, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl);
+    return launch_partial_reduce(a.dz, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl, false, &fx);
   }
-  if (a.dz) {
-    const float* srcs[2] = {ga.dq_out, ga.dp_out};
-    int counts[2] = {pl.nsq, pl.nsp};
-    size_t strides[2] = {nq, np};
-    return launch_partial_reduce(a.dz, srcs, counts, strides, 2, nq, a.stream, loss_of, &pl);
-  }
-  if (want_q && !q_direct) {
+  if (want_q) {
+    fx.mode = 1; fx.other = ga.P;
     const float* srcs[1] = {ga.dq_out}; int counts[1] = {pl.nsq}; size_t strides[1] = {nq};
-    e = launch_partial_reduce(a.dq, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl, cache_bf16);
+    e = launch_partial_reduce(a.dq, srcs, counts, strides, 1, nq, a.stream, loss_of, &pl, cache_bf16, &fx);
     if (e != hipSuccess) return e;
     loss_of = nullptr;
   }
-  if (want_p && !p_direct) {
+  if (want_p) {
+    fx.mode = 2; fx.other = ga.Q;
+    fx.inv = sym_pairs ? a.pos_inv : ga.inv; fx.shared = sym_pairs ? a.zero_word : ga.shared;
     const float* srcs[1] = {ga.dp_out}; int counts[1] = {pl.nsp}; size_t strides[1] = {np};
-    e = launch_partial_reduce(a.dp, srcs, counts, strides, 1, np, a.stream, loss_of, &pl, cache_bf16);
+    e = launch_partial_reduce(a.dp, srcs, counts, strides, 1, np, a.stream, loss_of, &pl, cache_bf16, &fx);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -9,7 +9,7 @@ import torch
 from oracle import gc_oracle as O
 from paper_2101_06983_amd import binding as gc
 from paper_2101_06983_amd import synth
-from parity import TOL_BF16, TOL_BF16_PEAKED, TOL_SAME_G, check, check_loss, normerr, relerr, to_np
+from parity import TOL_BF16, check, check_loss, relerr, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -29,23 +29,21 @@ def run(q, p, r, scale, temp):
 
 
 @pytest.mark.parametrize("n,d,scale,temp,tol", [(96, 128, 1.0, 0.5, TOL_BF16), (300, 256, 2.0, 1.0, TOL_BF16),
-                                                (257, 64, 1.0, 0.1, TOL_BF16_PEAKED), (1024, 768, 1.0, 1.0, TOL_BF16),
-                                                (1500, 128, 1.0, 0.07, TOL_BF16_PEAKED),
-                                                (1500, 256, 1.0, 0.07, TOL_BF16_PEAKED),
+                                                (257, 64, 1.0, 0.1, TOL_BF16), (1024, 768, 1.0, 1.0, TOL_BF16),
+                                                (1500, 128, 1.0, 0.07, TOL_BF16),
+                                                (1500, 256, 1.0, 0.07, TOL_BF16),
                                                 (200, 384, 1.0, 1.0, TOL_BF16), (333, 512, 1.5, 0.5, TOL_BF16),
-                                                (130, 640, 1.0, 0.2, TOL_BF16_PEAKED), (64, 96, 1.0, 1.0, TOL_BF16)])
+                                                (130, 640, 1.0, 0.2, TOL_BF16), (64, 96, 1.0, 1.0, TOL_BF16)])
 def test_bidirectional_matches_the_oracle(n, d, scale, temp, tol):
     q, p, r = problem(n, d, 6000 + n)
     q64, p64 = synth.widen(q), synth.widen(p)
     want = O.bidirectional(q64, p64, r.numpy(), scale, temp)
-    same_g = O.bidirectional(q64, p64, r.numpy(), scale, temp, g_dtype="bf16")
     out = run(q, p, r, scale, temp)
     tag = "bidir n=%d d=%d" % (n, d)
     check_loss(tag + " loss", out["loss"].item(), want["loss"], 1e-5)     # the loss has no bf16 step
     for k in ("dq", "dp"):
         if d % 128 == 0:     # MFMA kernels: bf16 coefficients
             check(tag + " " + k, relerr(to_np(out[k]), want[k]), tol)
-            check(tag + " " + k + " vs same-g", normerr(to_np(out[k]), same_g[k]), TOL_SAME_G)
         else:                # fp32-FMA kernels: nothing is rounded to bf16
             check(tag + " " + k, relerr(to_np(out[k]), want[k]), 1e-5)
 

@@ -9,8 +9,7 @@ import torch
 from paper_2101_06983_amd import binding as gc
 from paper_2101_06983_amd import synth
 from oracle import gc_oracle as O
-from parity import (TOL_BF16, TOL_BF16_PEAKED, TOL_F32, TOL_SAME_G, check, check_argmax, check_loss, normerr,
-                    oracle_loss, relerr, to_np)
+from parity import TOL_BF16, TOL_F32, check, check_argmax, check_loss, oracle_loss, relerr, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -100,34 +99,23 @@ def test_bf16_shapes_and_edges(B, P, d, scale, temp):
             assert float(out["dq"].abs().max()) == 0.0 and float(out["dp"].abs().max()) == 0.0
         tag = "bf16 %dx%dx%d path %d" % (B, P, d, path)
         compare(out, want, TOL_BF16, q, p, scale / temp, label=tag)
-        if d % 128 == 0 and P > 1:
-            # the MFMA kernels round the coefficients g_ij to bf16: against the definition with that one rounding
-            # the agreement is an order of magnitude closer
-            same_g = O.loss_and_rep_grad(synth.widen(q), synth.widen(p), r.numpy(), scale, temp, g_dtype="bf16")
-            check(tag + " dp vs same-g", normerr(to_np(out["dp"]), same_g["dp"]), TOL_SAME_G)
-            # the walk that forms the statistics as it goes rounds 2^(t - reference), not g, and adds the positive's
-            # term in fp32, so the same-coefficient oracle is not the model of its dQ
-            if d < 256 or path == gc.GC_PATH_STATS_PASS:
-                check(tag + " dq vs same-g", normerr(to_np(out["dq"]), same_g["dq"]), TOL_SAME_G)
 
 
 @pytest.mark.parametrize("B,P,d,temp", [(700, 1400, 128, 0.07), (500, 1000, 256, 0.05), (384, 2000, 768, 0.05)])
 def test_peaked_softmax_at_low_temperature(B, P, d, temp):
-    """Strong positives and a low temperature: a few coefficients carry each gradient row, so the bf16 rounding of
-    the coefficients shows in the largest element (up to 2^-8); against the same-coefficient oracle it does not."""
+    """Strong positives and a low temperature: a few coefficients carry each gradient row.  The largest of them, the
+    positive's own, is kept in fp32 (it is not part of the bf16 contractions), so these cases meet the stated
+    tolerance like any other."""
     q, p, r = synth.dpr_batch(B, P, d, torch.bfloat16, seed=2500 + B, positive_mix=0.5)
     q64, p64 = synth.widen(q), synth.widen(p)
     want = O.loss_and_rep_grad(q64, p64, r.numpy(), 1.0, temp)
-    same_g = O.loss_and_rep_grad(q64, p64, r.numpy(), 1.0, temp, g_dtype="bf16")
     for path in PATHS:
         out = run_ex(q, p, r, 1.0, temp, flags=path)
         tag = "peaked %dx%dx%d path %d" % (B, P, d, path)
         check_loss(tag + " loss", out["loss"].item(), want["loss"], 1e-5)
         check(tag + " lse", relerr(to_np(out["lse"]), want["lse"]), 1e-5)
         for k in ("dq", "dp"):
-            check(tag + " " + k, relerr(to_np(out[k]), want[k]), TOL_BF16_PEAKED)
-            if k == "dp" or d < 256 or path == gc.GC_PATH_STATS_PASS:   # see test_bf16_shapes_and_edges
-                check(tag + " " + k + " vs same-g", normerr(to_np(out[k]), same_g[k]), TOL_SAME_G)
+            check(tag + " " + k, relerr(to_np(out[k]), want[k]), TOL_BF16)
 
 
 @pytest.mark.parametrize("B,P,d,dtype", [(200, 700, 256, torch.bfloat16), (90, 300, 768, torch.bfloat16),

@@ -477,7 +477,7 @@ def test_planted_mistakes_fail_the_pins(mutation):
     assert_close_norm(good["dp"], fd_grad(f, p), 1e-7)
 
 
-# ------------------------------------------ the optional roundings (g_dtype, rep_dtype) of the oracle
+# ------------------------------------------ the optional storage rounding (rep_dtype) of the oracle
 def torch_bf16(a):
     """The bf16 grid through torch's cast (the library routine), back in float64."""
     return torch.tensor(np.asarray(a, dtype=np.float64), dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
@@ -502,62 +502,11 @@ def softmax_rows_by_enumeration(s, skip_diagonal=False):
     return out
 
 
-@pytest.mark.parametrize("mask_self,shared", [(False, False), (False, True), (True, False)])
-def test_g_dtype_bf16_is_the_definition_with_torch_cast_coefficients(mask_self, shared):
-    """Eq. 5-6 with the coefficients g_ij = p_ij - [j = r_i] rounded to bf16 once, before the two contractions:
-    rebuilt with torch's cast and explicit loops, and held to the error bound of one rounding per coefficient."""
-    B, P, d = (7, 7, 5) if mask_self else (6, 9, 5)
-    q, p, r = rand_problem(B, P, d, seed=80 + B + shared, std=1.0)
-    if mask_self:
-        r = np.arange(B) ^ 1
-        r[-1] = 0
-    if shared:
-        r[:3] = 4           # three anchors share target 4 (Eq. 7 summed over them)
-    scale, temp = 1.4, 0.6
-    alpha = scale / temp
-    got = O.loss_and_rep_grad(q, p, r, scale, temp, mask_self=mask_self, g_dtype="bf16")
-    ref = O.loss_and_rep_grad(q, p, r, scale, temp, mask_self=mask_self)
-    s = alpha * q @ p.T
-    g = softmax_rows_by_enumeration(s, skip_diagonal=mask_self)
-    g[np.arange(B), r] -= 1.0
-    gb = torch_bf16(g)
-    np.testing.assert_allclose(got["dq"], loop_contract(gb, p, alpha / B), rtol=1e-12, atol=1e-16)
-    np.testing.assert_allclose(got["dp"], loop_contract(gb.T, q, alpha / B), rtol=1e-12, atol=1e-16)
-    # the rounding touches the two contractions only
-    assert got["loss"] == ref["loss"] and np.array_equal(got["lse"], ref["lse"]) and np.array_equal(got["argmax"], ref["argmax"])
-    # |dq_i - definition| <= 2^-8 (alpha/B) sum_j |g_ij| |p_j|, likewise dp; and the rounding is not a no-op
-    bq = 2.0 ** -8 * (alpha / B) * np.abs(g) @ np.abs(p)
-    bp = 2.0 ** -8 * (alpha / B) * np.abs(g).T @ np.abs(q)
-    assert np.all(np.abs(got["dq"] - ref["dq"]) <= bq + 1e-18) and np.all(np.abs(got["dp"] - ref["dp"]) <= bp + 1e-18)
-    assert np.abs(got["dq"] - ref["dq"]).max() > 0 and np.abs(got["dp"] - ref["dp"]).max() > 0
-    if mask_self:           # the masked entry has coefficient 0 on both sides
-        assert np.all(gb[np.arange(B), np.arange(B)] == 0.0)
-
-
-def test_g_dtype_bf16_of_the_symmetric_loss():
-    n, d = 8, 4
-    q, p, _ = rand_problem(n, n, d, seed=90, std=1.0)
-    r = rng(91).permutation(n)
-    alpha = 1.2
-    got = O.bidirectional(q, p, r, scale=alpha, g_dtype="bf16")
-    ref = O.bidirectional(q, p, r, scale=alpha)
-    s = alpha * q @ p.T
-    g = 0.5 * (softmax_rows_by_enumeration(s) + softmax_rows_by_enumeration(s.T).T)
-    g[np.arange(n), r] -= 1.0
-    gb = torch_bf16(g)
-    np.testing.assert_allclose(got["dq"], loop_contract(gb, p, alpha / n), rtol=1e-12, atol=1e-16)
-    np.testing.assert_allclose(got["dp"], loop_contract(gb.T, q, alpha / n), rtol=1e-12, atol=1e-16)
-    assert got["loss"] == ref["loss"]
-    assert np.all(np.abs(got["dq"] - ref["dq"]) <= 2.0 ** -8 * (alpha / n) * np.abs(g) @ np.abs(p) + 1e-18)
-    assert np.all(np.abs(got["dp"] - ref["dp"]) <= 2.0 ** -8 * (alpha / n) * np.abs(g).T @ np.abs(q) + 1e-18)
-    assert np.abs(got["dq"] - ref["dq"]).max() > 0
-
-
-def test_rep_dtype_and_g_dtype_of_the_bilinear_distance():
-    """Where the two optional roundings of bilinear_distance act.  rep_dtype: h_i = Omega^T f_i is a stored
+def test_rep_dtype_of_the_bilinear_distance_is_a_straight_through_cast():
+    """Where the optional rounding of bilinear_distance acts.  rep_dtype: h_i = Omega^T f_i is a stored
     representation; the scores and v see the stored values, u and dOmega flow through the unrounded form: exactly
-    what autograd gives with a straight-through cast h + (cast(h) - h).detach().  g_dtype: one rounding of
-    w_ij / (alpha/B) before the three sums of the section."""
+    what autograd gives with a straight-through cast h + (cast(h) - h).detach().  The same rebuilt with explicit
+    loops over torch-cast values."""
     B, P, d = 6, 9, 4
     q, p, r = rand_problem(B, P, d, seed=95, std=1.0)
     om = rng(96).standard_normal((d, d))
@@ -580,17 +529,12 @@ def test_rep_dtype_and_g_dtype_of_the_bilinear_distance():
     # it is not the unrounded result, and not the result of rounding h everywhere (v then also changes u's input)
     plain = O.bilinear_distance(q, p, r, om, scale=alpha)
     assert np.abs(got["v"] - plain["v"]).max() > 1e-6 and np.abs(got["u"] - plain["u"]).max() > 1e-9
-    # g_dtype on top: explicit loops over torch-cast coefficients
-    both = O.bilinear_distance(q, p, r, om, scale=alpha, rep_dtype="bf16", g_dtype="bf16")
+    # explicit loops over the torch-cast H: the section's three sums with w materialised
     hb = torch_bf16(q @ om)
-    s = alpha * hb @ p.T
-    g = softmax_rows_by_enumeration(s)
+    s_ = alpha * hb @ p.T
+    g = softmax_rows_by_enumeration(s_)
     g[np.arange(B), r] -= 1.0
-    gb = torch_bf16(g)
-    a = loop_contract(gb, p, alpha / B)                       # sum_j w_ij g(t_j)
-    np.testing.assert_allclose(both["u"], a @ om.T, rtol=1e-12, atol=1e-16)
-    np.testing.assert_allclose(both["v"], loop_contract(gb.T, hb, alpha / B), rtol=1e-12, atol=1e-16)
-    np.testing.assert_allclose(both["domega"], q.T @ a, rtol=1e-12, atol=1e-16)
-    np.testing.assert_allclose(both["w"], (alpha / B) * gb, rtol=1e-13, atol=0)
-    assert both["loss"] == got["loss"]
-    assert np.all(np.abs(both["v"] - got["v"]) <= 2.0 ** -8 * (alpha / B) * np.abs(g).T @ np.abs(hb) + 1e-18)
+    a = loop_contract(g, p, alpha / B)                        # sum_j w_ij g(t_j)
+    np.testing.assert_allclose(got["u"], a @ om.T, rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(got["v"], loop_contract(g.T, hb, alpha / B), rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(got["domega"], q.T @ a, rtol=1e-12, atol=1e-16)
