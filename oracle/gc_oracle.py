@@ -25,7 +25,7 @@ import numpy as np
 from scipy.special import erf
 
 __all__ = [
-    "loss_and_rep_grad", "ntxent", "bidirectional", "bilinear_distance", "mlp_forward", "mlp_backward",
+    "loss_and_rep_grad", "ntxent", "bidirectional", "bilinear_distance", "deep_distance", "mlp_forward", "mlp_backward",
     "mlp_fullbatch_grad", "mlp_chunked_grad", "mlp_accumulation_grad", "round_to_bf16",
 ]
 
@@ -171,6 +171,70 @@ def bilinear_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, rep_dtype=None)
     w = (alpha / B) * g
     a = w @ p                                    # sum_j w_ij g(t_j)
     return dict(loss=float(loss), w=w, u=a @ om.T, v=w.T @ h, domega=q.T @ a)
+
+
+def deep_distance(q, p, pos_idx, omega, scale=1.0, temp=1.0, block=8):
+    """Loss with a deep (non-bilinear) distance function (Sec. "Extend to Deep Distance
+    Function", all four equations), for the additive interaction
+      Phi_Omega(f, g) = sum_k w_k tanh((A f)_k + (C g)_k),   Omega = (A [h, d], C [h, d], w [h]),
+    a one-hidden-layer network on the pair (f, g); it does not factor into a product of
+    a function of f and a function of g, so every one of the B * P distances is an
+    evaluation of Phi of its own (the early-interaction case the section ends with).
+      d_ij = Phi(f(s_i), g(t_j))                                    first equation
+      logits alpha * d_ij, loss as Eq. 1
+      w_ij = dL/dd_ij = (alpha / B) (p_ij - [j == r_i])             the Distance Gradient Cache, B x P, materialised
+      dOmega = sum_ij w_ij dPhi(f_i, g_j)/dOmega                    second equation (the sub-batch double sum, all pairs)
+      u_i = sum_j w_ij dd_ij/df(s_i)                                third equation
+      v_j = sum_i w_ij dd_ij/dg(t_j)                                fourth equation
+    With z_ijk = (A f_i)_k + (C g_j)_k, t = tanh z, t' = 1 - t^2:
+      dd_ij/df_i = A^T (w * t'_ij),  dd_ij/dg_j = C^T (w * t'_ij),
+      dPhi/dw_k = t_ijk,  dPhi/dA = (w * t'_ij) f_i^T,  dPhi/dC = (w * t'_ij) g_j^T.
+    The pairs are visited `block` anchors at a time (a [block, P, h] array), nothing else is blocked.
+    omega: dict(A, C, w).  Returns dict(loss, lse, w (the cache, called `cache` to keep it apart
+    from the parameter w), u, v, dA, dC, dw)."""
+    q = _f64(q)
+    p = _f64(p)
+    A, C, wv = _f64(omega["A"]), _f64(omega["C"]), _f64(omega["w"])
+    r = np.asarray(pos_idx, dtype=np.int64)
+    B, d = q.shape
+    P = p.shape[0]
+    h = A.shape[0]
+    assert A.shape == (h, d) and C.shape == (h, d) and wv.shape == (h,) and p.shape[1] == d and r.shape == (B,)
+    assert np.all((r >= 0) & (r < P))
+    alpha = float(scale) / float(temp)
+    a = q @ A.T                                   # (A f_i)_k
+    c = p @ C.T                                   # (C g_j)_k
+    # first forward: all distances
+    dist = np.empty((B, P))
+    for i0 in range(0, B, block):
+        z = a[i0:i0 + block, None, :] + c[None, :, :]
+        dist[i0:i0 + block] = np.tanh(z) @ wv
+    s = alpha * dist
+    m = s.max(axis=1)
+    lse = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    loss = np.sum(lse - s[np.arange(B), r]) / B
+    cache = np.exp(s - lse[:, None])
+    cache[np.arange(B), r] -= 1.0
+    cache *= alpha / B                            # w_ij
+    # the three sums over the cached w_ij
+    u = np.zeros((B, d))
+    v = np.zeros((P, d))
+    dA = np.zeros((h, d))
+    dC = np.zeros((h, d))
+    dw = np.zeros(h)
+    for i0 in range(0, B, block):
+        sl = slice(i0, min(i0 + block, B))
+        t = np.tanh(a[sl, None, :] + c[None, :, :])              # [b, P, h]
+        wij = cache[sl][:, :, None]                              # [b, P, 1]
+        e = wij * (wv * (1.0 - t * t))                           # w_ij (w * t'_ij): [b, P, h]
+        dw += (wij * t).sum(axis=(0, 1))
+        ei = e.sum(axis=1)                                       # sum_j ...: [b, h]
+        ej = e.sum(axis=0)                                       # sum_i (this block) ...: [P, h]
+        u[sl] = ei @ A
+        v += ej @ C
+        dA += ei.T @ q[sl]
+        dC += ej.T @ p
+    return dict(loss=float(loss), lse=lse, cache=cache, u=u, v=v, dA=dA, dC=dC, dw=dw)
 
 
 # ---------------------------------------------------------------------------

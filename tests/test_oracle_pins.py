@@ -538,3 +538,127 @@ def test_rep_dtype_of_the_bilinear_distance_is_a_straight_through_cast():
     np.testing.assert_allclose(got["u"], a @ om.T, rtol=1e-12, atol=1e-16)
     np.testing.assert_allclose(got["v"], loop_contract(g.T, hb, alpha / B), rtol=1e-12, atol=1e-16)
     np.testing.assert_allclose(got["domega"], q.T @ a, rtol=1e-12, atol=1e-16)
+
+
+# ----------------------------------------------- deep (non-bilinear) distance function
+def deep_problem(B=5, P=7, d=4, h=3, seed=100):
+    g = rng(seed)
+    q, p, r = rand_problem(B, P, d, seed=seed, std=1.0)
+    om = dict(A=g.standard_normal((h, d)) * 0.7, C=g.standard_normal((h, d)) * 0.7, w=g.standard_normal(h))
+    return q, p, r, om
+
+
+def test_deep_distance_against_autograd_of_the_plain_definition():
+    """Phi(f, g) = sum_k w_k tanh((A f)_k + (C g)_k) written with torch, cross-entropy of alpha * d_ij (library
+    routine), gradients of f, g, A, C, w and of the distances themselves by autograd."""
+    q, p, r, om = deep_problem()
+    alpha = 1.7
+    out = O.deep_distance(q, p, r, om, scale=alpha, temp=1.0, block=2)
+    tq, tp = torch.tensor(q, requires_grad=True), torch.tensor(p, requires_grad=True)
+    tA, tC, tw = (torch.tensor(om[k], requires_grad=True) for k in ("A", "C", "w"))
+    dist = (torch.tanh((tq @ tA.T)[:, None, :] + (tp @ tC.T)[None, :, :]) * tw).sum(-1)
+    dist.retain_grad()
+    loss = torch.nn.functional.cross_entropy(alpha * dist, torch.tensor(r, dtype=torch.long))
+    loss.backward()
+    assert out["loss"] == pytest.approx(loss.item(), rel=1e-12)
+    np.testing.assert_allclose(out["cache"], dist.grad.numpy(), rtol=1e-9, atol=1e-15)     # the distance gradient cache
+    for k, t in (("u", tq), ("v", tp), ("dA", tA), ("dC", tC), ("dw", tw)):
+        np.testing.assert_allclose(out[k], t.grad.numpy(), rtol=1e-9, atol=1e-14, err_msg=k)
+    # the anchor blocking is only a blocking
+    one = O.deep_distance(q, p, r, om, scale=alpha, temp=1.0, block=100)
+    for k in ("u", "v", "dA", "dC", "dw"):
+        np.testing.assert_allclose(out[k], one[k], rtol=1e-12, atol=1e-15)
+
+
+def test_deep_distance_pair_by_pair_and_finite_differences():
+    """The section's sums written out pair by pair in Python (distance and its partial derivatives of ONE pair from
+    the scalar formulas), and central differences of the loss by enumeration on every parameter and representation."""
+    q, p, r, om = deep_problem(B=3, P=4, d=3, h=2, seed=101)
+    alpha = 0.9
+    out = O.deep_distance(q, p, r, om, scale=alpha)
+    A, C, w = om["A"], om["C"], om["w"]
+    B, P, d, h = 3, 4, 3, 2
+
+    def phi(f, g):
+        return sum(w[k] * math.tanh(sum(A[k][x] * f[x] for x in range(d)) + sum(C[k][x] * g[x] for x in range(d))) for k in range(h))
+
+    def loss_by_enumeration():
+        tot = 0.0
+        for i in range(B):
+            den = sum(math.exp(alpha * phi(q[i], p[j])) for j in range(P))
+            tot += -math.log(math.exp(alpha * phi(q[i], p[r[i]])) / den)
+        return tot / B
+
+    assert out["loss"] == pytest.approx(loss_by_enumeration(), rel=1e-13)
+    # cache: w_ij = (alpha / B) (softmax - y), then u_i = sum_j w_ij dd_ij/df_i with dd/df = A^T (w * (1 - tanh^2))
+    u = np.zeros((B, d)); v = np.zeros((P, d)); dw = np.zeros(h)
+    for i in range(B):
+        den = sum(math.exp(alpha * phi(q[i], p[j])) for j in range(P))
+        for j in range(P):
+            wij = (alpha / B) * (math.exp(alpha * phi(q[i], p[j])) / den - (1.0 if j == r[i] else 0.0))
+            assert out["cache"][i, j] == pytest.approx(wij, rel=1e-11, abs=1e-16)
+            for k in range(h):
+                t = math.tanh(float(A[k] @ q[i] + C[k] @ p[j]))
+                dw[k] += wij * t
+                u[i] += wij * w[k] * (1 - t * t) * A[k]
+                v[j] += wij * w[k] * (1 - t * t) * C[k]
+    np.testing.assert_allclose(out["u"], u, rtol=1e-10, atol=1e-15)
+    np.testing.assert_allclose(out["v"], v, rtol=1e-10, atol=1e-15)
+    np.testing.assert_allclose(out["dw"], dw, rtol=1e-10, atol=1e-15)
+    f = loss_by_enumeration
+    assert_close_norm(out["u"], fd_grad(f, q), 1e-7)
+    assert_close_norm(out["v"], fd_grad(f, p), 1e-7)
+    assert_close_norm(out["dA"], fd_grad(f, A), 1e-7)
+    assert_close_norm(out["dC"], fd_grad(f, C), 1e-7)
+    assert_close_norm(out["dw"], fd_grad(f, w), 1e-7)
+
+
+def test_deep_distance_closed_forms_and_invariants():
+    q, p, r, om = deep_problem(B=6, P=9, d=5, h=4, seed=102)
+    # C = 0: every distance of an anchor is the same number, so the softmax is uniform: L = log P, and dd/df does not
+    # depend on j, so u_i = (sum_j w_ij) x = 0; v = C^T (...) = 0; dC = sum_j (sum_i w_ij e_i) g_j^T need not vanish
+    z = dict(om, C=np.zeros_like(om["C"]))
+    out = O.deep_distance(q, p, r, z, scale=2.0, temp=0.5)
+    assert out["loss"] == pytest.approx(math.log(9), rel=1e-13)
+    np.testing.assert_allclose(out["u"], 0.0, atol=1e-15)
+    assert np.all(out["v"] == 0.0)
+    np.testing.assert_allclose(out["dw"], 0.0, atol=1e-15)          # sum_j w_ij tanh(a_i) = tanh(a_i) * 0
+    # rows of the cache sum to zero (rows of softmax - Y do), whatever Phi is
+    full = O.deep_distance(q, p, r, om, scale=2.0, temp=0.5)
+    np.testing.assert_allclose(full["cache"].sum(axis=1), 0.0, atol=1e-15)
+    # h = 1, w = 1, d = 1, A = C = 1: d_ij = tanh(f_i + g_j); 1 x 2 worked example
+    f0, g0, g1 = 0.3, -0.2, 0.5
+    one = O.deep_distance([[f0]], [[g0], [g1]], [1], dict(A=[[1.0]], C=[[1.0]], w=[1.0]))
+    d0, d1 = math.tanh(f0 + g0), math.tanh(f0 + g1)
+    p1 = math.exp(d1) / (math.exp(d0) + math.exp(d1))
+    assert one["loss"] == pytest.approx(-math.log(p1), rel=1e-13)
+    # dL/df = (1 - p1) (1 - d0^2) + (p1 - 1) (1 - d1^2)
+    assert one["u"][0, 0] == pytest.approx((1 - p1) * (1 - d0 * d0) + (p1 - 1) * (1 - d1 * d1), rel=1e-12)
+    assert one["v"][1, 0] == pytest.approx((p1 - 1) * (1 - d1 * d1), rel=1e-12)
+    # small arguments: tanh z ~ z, Phi ~ w^T A f + w^T C g is additive, so the anchor part cancels in the softmax and
+    # the loss is that of the scores alpha * (w^T C g_j) alone (limit check, first order)
+    eps = 1e-4
+    lin = dict(A=om["A"] * eps, C=om["C"] * eps, w=om["w"])
+    got = O.deep_distance(q, p, r, lin, scale=1.0 / eps)
+    sc = (p @ om["C"].T) @ om["w"]
+    want = np.mean(np.log(np.exp(sc).sum()) - sc[r])
+    assert got["loss"] == pytest.approx(want, rel=1e-6)
+
+
+@pytest.mark.parametrize("mutation", ["drop_w_in_u", "tanh_prime_sign", "transpose_cache"])
+def test_deep_distance_planted_mistakes_fail_the_pins(mutation):
+    """Sanity of the pins: a mutated copy of the three sums disagrees with finite differences."""
+    q, p, r, om = deep_problem(B=4, P=4, d=3, h=2, seed=103)
+    good = O.deep_distance(q, p, r, om)
+    A, C, w = om["A"], om["C"], om["w"]
+    t = np.tanh((q @ A.T)[:, None, :] + (p @ C.T)[None, :, :])
+    cache = good["cache"].T if mutation == "transpose_cache" else good["cache"]
+    tp = (1 + t * t) if mutation == "tanh_prime_sign" else (1 - t * t)
+    e = cache[:, :, None] * ((1.0 if mutation == "drop_w_in_u" else w) * tp)
+    u_bad = e.sum(axis=1) @ A
+
+    def loss():
+        return O.deep_distance(q, p, r, om)["loss"]
+    ref = fd_grad(loss, q)
+    assert np.abs(u_bad - ref).max() / np.abs(ref).max() > 1e-3
+    assert_close_norm(good["u"], ref, 1e-6)
