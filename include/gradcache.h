@@ -207,6 +207,26 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
                                     float* domega, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Loss with a deep, non-bilinear distance function (Sec. "Extend to Deep Distance Function", all four equations):
+ *   d_ij = Phi_Omega(f(s_i), g(t_j)) = sum_k w_k tanh((A f(s_i))_k + (C g(t_j))_k),   Omega = (A [h,d], C [h,d], w [h]),
+ * logits scale * d_ij / temp, loss as Eq. 1.  Phi does not factor over its arguments: each of the B * P distances is
+ * evaluated on its own (twice: once for the softmax normaliser, once for the gradients).  With
+ * w_ij = dL/dd_ij, the section's Distance Gradient Cache, the outputs are
+ *   u[B,d] = sum_j w_ij dd_ij/df(s_i),   v[P,d] = sum_i w_ij dd_ij/dg(t_j)      (the Representation Gradient Cache)
+ *   dA[h,d], dC[h,d], dw[h] = sum_ij w_ij dPhi(f(s_i), g(t_j))/dOmega           (the gradient of Omega)
+ * w_ij is never stored: it exists for one pair at a time inside the kernel that walks the pairs, and is consumed
+ * there for all three sums.  q[B,d], p[P,d], A, C, w bf16; pos_idx[B] int32; loss[1], u, v, dA, dC, dw float,
+ * overwritten; all device memory.  d must be a multiple of 128 and h = 128 (else GC_ERR_UNSUPPORTED).  Errors as
+ * gc_loss_and_rep_grad_ex; the asynchronous pos_idx error is read with gc_check_async_error(workspace).
+ * workspace: gc_deepdist_workspace_bytes(B, P, d, h) (0 for an unsupported shape).
+ */
+size_t gc_deepdist_workspace_bytes(int B, int P, int d, int h);
+int gc_deepdist_loss_and_grads_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                                    const void* A, const void* C, const void* w, int h, float scale, float temp,
+                                    float* loss, float* u, float* v, float* dA, float* dC, float* dw, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
+/*
  * Stand-in encoder  y = GELU(x W1 + b1) W2 + b2  (exact erf GELU), bf16 storage,
  * fp32 accumulation.  W1[din,dh], b1[dh], W2[dh,dout], b2[dout], all device bf16.
  * din must be a multiple of 64, dh and dout multiples of 128 (else

@@ -27,7 +27,7 @@ EXPORTS = [
     "gc_loss_and_rep_grad_ex", "gc_check_async_error", "gc_ntxent_workspace_bytes",
     "gc_ntxent_loss_and_grad_bf16", "gc_bidirectional_workspace_bytes",
     "gc_bidirectional_loss_and_rep_grad_bf16", "gc_bilinear_workspace_bytes", "gc_bilinear_workspace_layout",
-    "gc_bilinear_loss_and_grads_bf16",
+    "gc_bilinear_loss_and_grads_bf16", "gc_deepdist_workspace_bytes", "gc_deepdist_loss_and_grads_bf16",
     "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
     "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
     "gc_step_mlp_release", "gc_profile_begin", "gc_profile_end",
@@ -88,6 +88,10 @@ def load():
     lib.gc_bilinear_workspace_layout.argtypes = [ci, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.gc_bilinear_loss_and_grads_bf16.restype = ci
     lib.gc_bilinear_loss_and_grads_bf16.argtypes = [vp, vp, vp, ci, ci, ci, vp, cf, cf, vp, vp, vp, vp, vp, sz, vp]
+    lib.gc_deepdist_workspace_bytes.restype = sz
+    lib.gc_deepdist_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.gc_deepdist_loss_and_grads_bf16.restype = ci
+    lib.gc_deepdist_loss_and_grads_bf16.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp, vp, ci, cf, cf, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     pp, pg = ctypes.POINTER(gc_mlp_params), ctypes.POINTER(gc_mlp_grads)
     lib.gc_mlp_workspace_bytes.restype = sz
     lib.gc_mlp_workspace_bytes.argtypes = [ci, pp]
@@ -298,6 +302,37 @@ def gc_bilinear_loss_and_grads_bf16(q, p, pos_idx, omega, scale=1.0, temp=1.0, w
                                              _ptr(out["loss"]), _ptr(out["u"]), _ptr(out["v"]), _ptr(out["domega"]),
                                              wp, wn, _stream(stream))
     _check(rc, "gc_bilinear_loss_and_grads_bf16")
+    out["workspace"] = workspace
+    return out
+
+
+def gc_deepdist_loss_and_grads_bf16(q, p, pos_idx, omega, scale=1.0, temp=1.0, workspace=None, out=None, stream=None):
+    """Deep distance Phi = sum_k w_k tanh((A f)_k + (C g)_k); omega = dict(A [h,d], C [h,d], w [h]) of bf16 device
+    tensors.  Returns dict(loss, u, v, dA, dC, dw, workspace)."""
+    lib = load()
+    A, C, w = omega["A"], omega["C"], omega["w"]
+    for t, name in ((q, "q"), (p, "p"), (A, "A"), (C, "C"), (w, "w")):
+        _dev_contig(t, torch.bfloat16, name)
+    _dev_contig(pos_idx, torch.int32, "pos_idx")
+    B, d = q.shape
+    P = p.shape[0]
+    h = A.shape[0]
+    if p.shape[1] != d or tuple(A.shape) != (h, d) or tuple(C.shape) != (h, d) or tuple(w.shape) != (h,) or tuple(pos_idx.shape) != (B,):
+        raise GradCacheError(GC_ERR_SHAPE, "gc_deepdist_loss_and_grads_bf16")
+    if out is None:
+        f32 = dict(dtype=torch.float32, device=q.device)
+        out = dict(loss=torch.empty(1, **f32), u=torch.empty(B, d, **f32), v=torch.empty(P, d, **f32),
+                   dA=torch.empty(h, d, **f32), dC=torch.empty(h, d, **f32), dw=torch.empty(h, **f32))
+    if workspace is None:
+        need = lib.gc_deepdist_workspace_bytes(B, P, d, h)
+        if need == 0:
+            raise GradCacheError(GC_ERR_UNSUPPORTED, "gc_deepdist_workspace_bytes")
+        workspace = alloc_workspace(need, q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib.gc_deepdist_loss_and_grads_bf16(_ptr(q), _ptr(p), _ptr(pos_idx), B, P, d, _ptr(A), _ptr(C), _ptr(w), h, scale,
+                                             temp, _ptr(out["loss"]), _ptr(out["u"]), _ptr(out["v"]), _ptr(out["dA"]),
+                                             _ptr(out["dC"]), _ptr(out["dw"]), wp, wn, _stream(stream))
+    _check(rc, "gc_deepdist_loss_and_grads_bf16")
     out["workspace"] = workspace
     return out
 

@@ -60,7 +60,7 @@ __device__ __forceinline__ void load8(const void* base, size_t idx, bool live, u
 // C[M x N] += A^T B over the rows of a sub-batch: A [K][M] (bf16 or fp32), B [K][N] fp32, C fp32 in HBM.
 struct WgradArgs {
   const void* A; int lda;   // elements
-  const float* B; int ldb;
+  const void* B; int ldb;   // fp32, or bf16 where the kernel is instantiated with B_F32 = false
   int M, N, K;              // M a multiple of 64 (WG_M), N a multiple of 128, K = rows of the sub-batch (any)
   float* C; int ldc;        // += in place (one workgroup per tile: single writer)
   float* colsum;            // optional: [N] += column sums of B (db2; written by the m-tile 0 workgroups)
@@ -70,7 +70,7 @@ struct WgradArgs {
 constexpr int WG_M = 64;
 constexpr int WG_KCH = 32, WG_A_LD = WG_M + 8, WG_B_LD = 128 + 8;  // LDS tiles (bf16): [k rows][width + 8], hi then lo part
 
-template <bool A_F32>
+template <bool A_F32, bool B_F32 = true>
 __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, unsigned short* As, unsigned short* Bs) {
   constexpr int KCH = WG_KCH, A_LD = WG_A_LD, B_LD = WG_B_LD;
   constexpr int A_LO = KCH * A_LD, B_LO = KCH * B_LD;
@@ -100,9 +100,9 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
     for (int c = tid; c < KCH * 16; c += 256) {  // B[k][n0 .. n0 + 127]
       const int r = c / 16, cc = c % 16;
       u32x4 vh, vl;
-      load8<true>(g.B, (size_t)(k0 + r) * g.ldb + n0 + cc * 8, k0 + r < g.K, vh, vl);
+      load8<B_F32>(g.B, (size_t)(k0 + r) * g.ldb + n0 + cc * 8, k0 + r < g.K, vh, vl);
       *(u32x4*)(Bs + r * B_LD + cc * 8) = vh;
-      *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
+      if (B_F32) *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
     }
     __syncthreads();
 #pragma unroll
@@ -115,13 +115,15 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
         s16x8 t = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, t);
       };
-      const bf16x8 bfv = frag(Bs, B_LD, wave * 32), bfl = frag(Bs + B_LO, B_LD, wave * 32);
+      const bf16x8 bfv = frag(Bs, B_LD, wave * 32);
+      bf16x8 bfl = bfv;
+      if (B_F32) bfl = frag(Bs + B_LO, B_LD, wave * 32);
 #pragma unroll
       for (int mt = 0; mt < 2; mt++) {
         const bf16x8 af = frag(As, A_LD, 32 * mt);
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfv, acc[mt], 0, 0, 0);
         if (A_F32) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(As + A_LO, A_LD, 32 * mt), bfv, acc[mt], 0, 0, 0);
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfl, acc[mt], 0, 0, 0);
+        if (B_F32) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfl, acc[mt], 0, 0, 0);
       }
     }
     __syncthreads();
@@ -135,7 +137,7 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
     }
   if (g.colsum && by == 0 && tid < 128) {
     float s = 0.f;
-    for (int k = 0; k < g.K; k++) s += g.B[(size_t)k * g.ldb + n0 + tid];
+    for (int k = 0; k < g.K; k++) s += ((const float*)g.B)[(size_t)k * g.ldb + n0 + tid];   // (fp32 B only)
     g.colsum[n0 + tid] += s;
   }
 }
@@ -157,6 +159,7 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g2, WgradArgs 
 
 // C = A^T B with the rows (K) cut into slices: workgroup (tile, slice) adds its slice's product to partial s of C
 // (g.C + s * M * ldc, zeroed by the caller), which a fixed-order sum combines afterwards.  A bf16.
+template <bool A_F32, bool B_F32>
 __global__ void __launch_bounds__(256) wgrad_splitk_kernel(WgradArgs g, int rows_per_slice) {
   __shared__ __attribute__((aligned(16))) unsigned short As[2 * WG_KCH * WG_A_LD];
   __shared__ __attribute__((aligned(16))) unsigned short Bs[2 * WG_KCH * WG_B_LD];
@@ -164,12 +167,12 @@ __global__ void __launch_bounds__(256) wgrad_splitk_kernel(WgradArgs g, int rows
   const int tile = blockIdx.x % tiles, slice = blockIdx.x / tiles;
   const int k0 = slice * rows_per_slice;
   WgradArgs s = g;
-  s.A = (const unsigned short*)g.A + (size_t)k0 * g.lda;
-  s.B = g.B + (size_t)k0 * g.ldb;
+  s.A = (const char*)g.A + (size_t)k0 * g.lda * (A_F32 ? 4 : 2);
+  s.B = (const char*)g.B + (size_t)k0 * g.ldb * (B_F32 ? 4 : 2);
   s.K = min(rows_per_slice, g.K - k0);
   s.C = g.C + (size_t)slice * g.M * g.ldc;
   s.colsum = nullptr;
-  wgrad_tile<false>(s, tile % nb, tile / nb, As, Bs);
+  wgrad_tile<A_F32, B_F32>(s, tile % nb, tile / nb, As, Bs);
 }
 
 __global__ void __launch_bounds__(256) fill_f32_kernel(float* x, size_t n, float v) {
@@ -188,6 +191,7 @@ struct SkinnyArgs {
   unsigned short* Cb; int ldc;       // EP_BIAS: bf16 output; EP_PLAIN: bf16 output if set
   float* Cf;                         // EP_DH: dH out (fp32, ldc); EP_PLAIN: fp32 output if Cb is not set
   float* colsum;                     // EP_DH: db1 [N] += column sums (one m-tile per launch: single writer)
+  float plain_mul;                   // EP_PLAIN: factor on the product (0 means 1)
 };
 
 typedef float SkinnyRed[32][33];   // one partial tile; a workgroup holds four
@@ -264,7 +268,7 @@ __device__ __forceinline__ void skinny_tile(const SkinnyArgs& g, int bx, int by,
     } else if (EP == EP_PLAIN) {  // the product itself
       if (mm < g.M) {
         if (g.Cb) g.Cb[(size_t)mm * g.ldc + n] = f2bf(sum);
-        else g.Cf[(size_t)mm * g.ldc + n] = sum;
+        else g.Cf[(size_t)mm * g.ldc + n] = g.plain_mul != 0.f ? sum * g.plain_mul : sum;
       }
     } else {  // EP_DH
       float v = 0.f;
@@ -620,6 +624,241 @@ static int run_step(const StepCall& c, hipStream_t s) {
   return enqueue_step(c, s);
 }
 
+
+// ---- deep (non-bilinear) distance function (Sec. "Extend to Deep Distance Function") ---------------------------
+//   Phi_Omega(f, g) = sum_k w_k tanh((A f)_k + (C g)_k),  Omega = (A [h,d], C [h,d], w [h]).
+// Phi does not factor over its two arguments, so each of the B * P distances is an evaluation of its own: h tanh per
+// pair, plain vector arithmetic (no contraction for the MFMAs to take).  The pair part works on a_i = A f_i and
+// c_j = C g_j (two skinny products), both scaled by 2 log2(e), so that with r = 1 / (1 + 2^(a + c)):
+//   tanh z = 1 - 2 r,   1 - tanh^2 z = 4 r (1 - r).
+// One kernel walks the pairs in three roles, each with an owner side whose rows a workgroup keeps in registers and a
+// streamed side that passes through LDS 32 rows at a time:
+//   DD_STATS  owner = anchors: d_ij for every pair, online max / sum of 2^t per anchor, the positive's logit
+//   DD_DA     owner = anchors: d_ij again, the weight w_ij = dL/dd_ij (the section's Distance Gradient Cache, which
+//             exists for one pair at a time in a register), and with it sum_j w_ij t'_ijk (-> dL/da_i, hence u_i and
+//             dL/dA) and sum_j w_ij t_ijk (-> dL/dw)
+//   DD_DC     owner = targets: the same pairs walked the other way for sum_i w_ij t'_ijk (-> dL/dc_j, hence v_j, dL/dC);
+//             a second walk instead of a cross-workgroup sum: no atomics, fixed order.
+// Thread (o, kq) of a workgroup owns owner row o (64 rows) and the quarter kq of the k range: the four threads of a
+// row add their partial distances with two cross-lane moves, everything else stays in the thread's registers.
+constexpr int DD_OWN = 64, DD_TS = 32;
+enum DdRole { DD_STATS = 0, DD_DA = 1, DD_DC = 2 };
+struct DdArgs {
+  const float* own; const float* str;   // [n_own][H], [n_str][H]: 2 log2(e) (A f) resp. (C g), owner and streamed side
+  const unsigned short* wv;             // [H] bf16: w
+  int n_own, n_str, n_oblk, stream_len; // owner blocks; streamed rows per split
+  float alpha2, out_scale;              // alpha log2(e); alpha / B
+  const int32_t* pos_idx;               // [B] r_i (DD_STATS, DD_DA: of the owner rows)
+  float* part_m; float* part_l; int* part_idx; float* pos_t;   // DD_STATS out: per split and anchor
+  const float* lse2; const int32_t* pos_pad;                   // gradient roles: per anchor, padded (+inf, -1)
+  float* out_a;   // [split][n_own][H]: dL/da (DD_DA) or dL/dc (DD_DC) partial, final scale applied
+  float* out_e;   // DD_DA: [split][n_own][H]: (alpha/B) sum_j w_ij tanh_ijk partial (its column sums are dL/dw)
+};
+
+__device__ __forceinline__ float quad_sum(float x) {   // over the four lanes 4 i .. 4 i + 3
+  x += __shfl_xor(x, 1);
+  x += __shfl_xor(x, 2);
+  return x;
+}
+
+template <int H, int ROLE>
+__global__ void __launch_bounds__(256, 2) deepdist_walk_kernel(DdArgs g) {
+  constexpr int HQ = H / 4;            // k values per thread
+  constexpr int LD4 = DD_TS * H / 4 / 256;   // float4 loads per thread and tile
+  __shared__ __attribute__((aligned(16))) float tile[2][DD_TS][H];
+  __shared__ float st_lse[2][DD_TS];
+  __shared__ int st_pos[2][DD_TS];
+  const int tid = threadIdx.x, o = tid >> 2, kq = tid & 3;
+  const int oblk = blockIdx.x % g.n_oblk, split = blockIdx.x / g.n_oblk;
+  const int row = oblk * DD_OWN + o, rowc = min(row, g.n_own - 1);
+  const int sbeg = split * g.stream_len, send = min(g.n_str, sbeg + g.stream_len);
+  const int nt = (send - sbeg + DD_TS - 1) / DD_TS;
+
+  float ao[HQ], wq[HQ];
+#pragma unroll
+  for (int k = 0; k < HQ; k += 4) {
+    const f32x4 v = *(const f32x4*)(g.own + (size_t)rowc * H + kq * HQ + k);
+    ao[k] = v[0]; ao[k + 1] = v[1]; ao[k + 2] = v[2]; ao[k + 3] = v[3];
+  }
+  float w1 = 0.f;
+#pragma unroll
+  for (int k = 0; k < HQ; k++) { wq[k] = bf2f(g.wv[kq * HQ + k]); w1 += wq[k]; }
+  w1 = quad_sum(w1);   // sum_k w_k
+
+  int r_o = -1; float lse_o = INFINITY;
+  if (ROLE != DD_DC && row < g.n_own) r_o = g.pos_idx[row];
+  if (ROLE == DD_DA && row < g.n_own) lse_o = g.lse2[row];
+  float acc_a[HQ], acc_e[HQ];
+#pragma unroll
+  for (int k = 0; k < HQ; k++) { acc_a[k] = 0.f; acc_e[k] = 0.f; }
+  float sw = 0.f, m = -INFINITY, l = 0.f, pos = 0.f;
+  bool got = false;
+
+  // tile u of the streamed rows: global -> registers -> LDS, one tile ahead
+  f32x4 pre[LD4]; float pre_lse = INFINITY; int pre_pos = -1;
+  auto fetch = [&](int u) __attribute__((always_inline)) {
+    const int t0 = sbeg + u * DD_TS;
+#pragma unroll
+    for (int v = 0; v < LD4; v++) {
+      const int e4 = tid + 256 * v, rr = e4 / (H / 4), c4 = e4 % (H / 4);
+      pre[v] = *(const f32x4*)(g.str + (size_t)min(t0 + rr, g.n_str - 1) * H + 4 * c4);
+    }
+    if (ROLE == DD_DC && tid < DD_TS) {   // statistics of the streamed anchors (padded: +inf / -1 past the end)
+      pre_lse = g.lse2[t0 + tid]; pre_pos = g.pos_pad[t0 + tid];
+    }
+  };
+  auto stash = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int v = 0; v < LD4; v++) {
+      const int e4 = tid + 256 * v, rr = e4 / (H / 4), c4 = e4 % (H / 4);
+      *(f32x4*)&tile[buf][rr][4 * c4] = pre[v];
+    }
+    if (ROLE == DD_DC && tid < DD_TS) { st_lse[buf][tid] = pre_lse; st_pos[buf][tid] = pre_pos; }
+  };
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int u = 0; u < nt; u++) {
+    const int buf = u & 1;
+    if (u + 1 < nt) fetch(u + 1);
+    const int t0 = sbeg + u * DD_TS, rows = min(DD_TS, send - t0);
+    for (int s_ = 0; s_ < rows; s_++) {
+      const float* cs = &tile[buf][s_][kq * HQ];
+      float rr[HQ], part = 0.f;
+#pragma unroll
+      for (int k = 0; k < HQ; k += 4) {
+        const f32x4 c4 = *(const f32x4*)(cs + k);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const float r = __builtin_amdgcn_rcpf(1.f + fast_exp2(ao[k + e] + c4[e]));   // 1 / (1 + e^(2 z))
+          rr[k + e] = r;
+          part = __builtin_fmaf(wq[k + e], r, part);
+        }
+      }
+      const float t = g.alpha2 * (w1 - 2.f * quad_sum(part));   // base-2 logit of the pair
+      const int gs = t0 + s_;
+      if (ROLE == DD_STATS) {
+        if (gs == r_o) { pos = t; got = true; }
+        const float mn = fmaxf(m, t);
+        l = l * fast_exp2(m - mn) + fast_exp2(t - mn);
+        m = mn;
+      } else {
+        float wij;   // dL/dd_ij in units of alpha / B
+        if (ROLE == DD_DA) wij = fast_exp2(t - lse_o) - (gs == r_o ? 1.f : 0.f);
+        else wij = fast_exp2(t - st_lse[buf][s_]) - (st_pos[buf][s_] == row ? 1.f : 0.f);
+#pragma unroll
+        for (int k = 0; k < HQ; k++) {
+          acc_a[k] = __builtin_fmaf(wij, __builtin_fmaf(-rr[k], rr[k], rr[k]), acc_a[k]);   // w_ij r (1 - r)
+          if (ROLE == DD_DA) acc_e[k] = __builtin_fmaf(wij, rr[k], acc_e[k]);
+        }
+        if (ROLE == DD_DA) sw += wij;
+      }
+    }
+    if (u + 1 < nt) stash(buf ^ 1);
+    __syncthreads();
+  }
+  if (row >= g.n_own) return;
+  if (ROLE == DD_STATS) {
+    if (kq == 0) {
+      const size_t oo = (size_t)split * g.n_own + row;
+      g.part_m[oo] = m; g.part_l[oo] = l; g.part_idx[oo] = 0;
+      if (got) g.pos_t[row] = pos;
+    }
+  } else {
+    // dL/da_ik = w_k (alpha/B) 4 sum_j w_ij r (1 - r);  (alpha/B) sum_j w_ij tanh = (alpha/B) (sum_j w_ij - 2 sum_j w_ij r)
+    float* oa = g.out_a + ((size_t)split * g.n_own + row) * H + kq * HQ;
+#pragma unroll
+    for (int k = 0; k < HQ; k += 4)
+      *(f32x4*)(oa + k) = f32x4{acc_a[k] * wq[k], acc_a[k + 1] * wq[k + 1], acc_a[k + 2] * wq[k + 2], acc_a[k + 3] * wq[k + 3]} * (4.f * g.out_scale);
+    if (ROLE == DD_DA) {
+      float* oe = g.out_e + ((size_t)split * g.n_own + row) * H + kq * HQ;
+#pragma unroll
+      for (int k = 0; k < HQ; k += 4)
+        *(f32x4*)(oe + k) = (f32x4{sw, sw, sw, sw} - 2.f * f32x4{acc_e[k], acc_e[k + 1], acc_e[k + 2], acc_e[k + 3]}) * g.out_scale;
+    }
+  }
+}
+
+// column sums of x[rows][cols] over a slice of the rows: partial[slice][cols] (fixed order; cols a multiple of 32)
+__global__ void __launch_bounds__(256) colsum_slices_kernel(const float* __restrict__ x, int rows, int cols, int rows_per_slice,
+                                                           float* __restrict__ partial) {
+  __shared__ float red[8][33];
+  const int cx = threadIdx.x & 31, ry = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cx, slice = blockIdx.y;
+  const int r0 = slice * rows_per_slice, r1 = min(rows, r0 + rows_per_slice);
+  float s = 0.f;
+  for (int r = r0 + ry; r < r1; r += 8) s += x[(size_t)r * cols + c];
+  red[ry][cx] = s;
+  __syncthreads();
+  if (ry == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; k++) t += red[k][cx];
+    partial[(size_t)slice * cols + c] = t;
+  }
+}
+
+struct DeepWs {
+  LossPlan st;                 // the statistics part of a loss workspace (split statistics, lse2, row losses, error word)
+  size_t off_stat, off_a, off_c, off_AT, off_CT, off_da_part, off_e_part, off_dc_part, off_da, off_dc, off_e, off_wpart,
+      off_gpart, total;
+  int nsa, len_a, nsc, len_c;  // stream splits of the anchor-owner walks / of the target-owner walk
+  int slices_b, rps_b, slices_p, rps_p;   // row slices of the two parameter-gradient products
+};
+static void dd_split(int n_oblk, int n_str, int& ns, int& len) {
+  const int target = 2 * num_cu();               // two workgroups per CU
+  ns = (target + n_oblk - 1) / n_oblk;
+  const int max_ns = (n_str + 4 * DD_TS - 1) / (4 * DD_TS);   // at least four tiles per split
+  if (ns > max_ns) ns = max_ns;
+  if (ns > 64) ns = 64;
+  if (ns < 1) ns = 1;
+  len = ((n_str + ns - 1) / ns + DD_TS - 1) / DD_TS * DD_TS;
+  ns = (n_str + len - 1) / len;
+}
+static DeepWs plan_deep(int B, int P, int d, int h) {
+  DeepWs w{};
+  const int obA = (B + DD_OWN - 1) / DD_OWN, obC = (P + DD_OWN - 1) / DD_OWN;
+  dd_split(obA, P, w.nsa, w.len_a);
+  dd_split(obC, B, w.nsc, w.len_c);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = up256(off + bytes); return o; };
+  // statistics, laid out as the loss kernels' merge expects them
+  LossPlan& st = w.st;
+  st.use_mfma = 0; st.stat_splits = w.nsa; st.b_pad = (B + 63) / 64 * 64;
+  w.off_stat = 0;
+  st.off_err = take(256);
+  st.off_part_m = take((size_t)w.nsa * B * 4); st.off_part_l = take((size_t)w.nsa * B * 4); st.off_part_idx = take((size_t)w.nsa * B * 4);
+  st.off_pos = take((size_t)B * 4); st.off_lse2 = take((size_t)st.b_pad * 4); st.off_pos_pad = take((size_t)st.b_pad * 4);
+  st.off_rowloss = take((size_t)B * 4);
+  w.off_a = take((size_t)B * h * 4); w.off_c = take((size_t)P * h * 4);
+  w.off_AT = take((size_t)d * h * 2); w.off_CT = take((size_t)d * h * 2);
+  w.off_da_part = take((size_t)w.nsa * B * h * 4); w.off_e_part = take((size_t)w.nsa * B * h * 4);
+  w.off_dc_part = take((size_t)w.nsc * P * h * 4);
+  w.off_da = take((size_t)B * h * 4); w.off_dc = take((size_t)P * h * 4); w.off_e = take((size_t)B * h * 4);
+  w.off_wpart = take((size_t)64 * h * 4);
+  auto slices_of = [&](int rows, int& sl, int& rps) {
+    const int tiles = (d / 128) * (h / WG_M);
+    sl = (2 * num_cu() + tiles - 1) / tiles;
+    const int mx = (rows + 127) / 128;
+    if (sl > mx) sl = mx;
+    if (sl > 64) sl = 64;
+    if (sl < 1) sl = 1;
+    rps = ((rows + sl - 1) / sl + 31) / 32 * 32;
+    sl = (rows + rps - 1) / rps;
+  };
+  slices_of(B, w.slices_b, w.rps_b);
+  slices_of(P, w.slices_p, w.rps_p);
+  const int smax = w.slices_b > w.slices_p ? w.slices_b : w.slices_p;
+  w.off_gpart = take((size_t)smax * h * d * 4);
+  w.total = off;
+  return w;
+}
+static int deep_shape_status(int B, int P, int d, int h) {
+  if (B < 1 || P < 1 || d < 1 || h < 1 || (long long)B * d > (1ll << 40) || (long long)P * d > (1ll << 40)) return GC_ERR_SHAPE;
+  if (d % 128 || h != 128) return GC_ERR_UNSUPPORTED;
+  return GC_OK;
+}
+
 // Drops what run_step has recorded for the current device: waits for the device, then destroys the graph
 // executables and the capture stream.
 static int release_step_graphs() {
@@ -787,11 +1026,113 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
     fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, n, 0.f);
     WgradArgs g{};
     g.A = q; g.lda = d; g.B = A; g.ldb = d; g.M = d; g.N = d; g.K = B; g.C = part; g.ldc = d;
-    wgrad_splitk_kernel<<<(d / 128) * (d / WG_M) * w.slices, 256, 0, s>>>(g, w.rows_per_slice);
+    wgrad_splitk_kernel<false, true><<<(d / 128) * (d / WG_M) * w.slices, 256, 0, s>>>(g, w.rows_per_slice);
     if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
     const float* srcs[1] = {part}; int counts[1] = {w.slices}; size_t strides[1] = {(size_t)d * d};
     if (launch_partial_reduce(domega, srcs, counts, strides, 1, (size_t)d * d, s) != hipSuccess) return GC_ERR_HIP;
   }
+  return GC_OK;
+}
+
+// ---- deep distance function, Phi = sum_k w_k tanh((A f)_k + (C g)_k) --------------------------------------------
+size_t gc_deepdist_workspace_bytes(int B, int P, int d, int h) {
+  if (deep_shape_status(B, P, d, h) != GC_OK) return 0;
+  return plan_deep(B, P, d, h).total;
+}
+
+int gc_deepdist_loss_and_grads_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+                                    const void* A, const void* C, const void* w, int h, float scale, float temp,
+                                    float* loss, float* u, float* v, float* dA, float* dC, float* dw, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  if (!q || !p || !pos_idx || !A || !C || !w || !loss || !u || !v || !dA || !dC || !dw) return GC_ERR_NULL;
+  int rc = deep_shape_status(B, P, d, h);
+  if (rc != GC_OK) return rc;
+  if (!(scale > 0.f) || !(temp > 0.f) || !std::isfinite(scale) || !std::isfinite(temp) || !std::isfinite(scale / temp) ||
+      !(scale / temp > 0.f))
+    return GC_ERR_SHAPE;
+  const DeepWs pw = plan_deep(B, P, d, h);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pw.total) return GC_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t s = (hipStream_t)stream;
+  const float alpha = scale / temp;
+  float* a2 = (float*)(ws + pw.off_a);
+  float* c2 = (float*)(ws + pw.off_c);
+  unsigned short* AT = (unsigned short*)(ws + pw.off_AT);
+  unsigned short* CT = (unsigned short*)(ws + pw.off_CT);
+  // a = 2 log2(e) F A^T, c = 2 log2(e) G C^T (fp32): Bt[n][k] = A[n][k] as stored
+  auto project = [&](const void* x, int rows, const void* M, float* out) {
+    SkinnyArgs g{};
+    g.A = x; g.lda = d; g.Bt = (const unsigned short*)M; g.ldb = d; g.M = rows; g.N = h; g.K = d; g.Cf = out; g.ldc = h;
+    g.plain_mul = 2.f * kLog2e;
+    mlp_skinny_kernel<false, EP_PLAIN><<<dim3(h / 32, (rows + 31) / 32), 256, 0, s>>>(g);
+  };
+  project(q, B, A, a2);
+  project(p, P, C, c2);
+  transpose_bf16_kernel<<<dim3(d / 32, h / 32), 256, 0, s>>>((const unsigned short*)A, h, d, AT);   // A^T [d][h]
+  transpose_bf16_kernel<<<dim3(d / 32, h / 32), 256, 0, s>>>((const unsigned short*)C, h, d, CT);
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  const int obA = (B + DD_OWN - 1) / DD_OWN, obC = (P + DD_OWN - 1) / DD_OWN;
+  DdArgs g{};
+  g.wv = (const unsigned short*)w; g.alpha2 = alpha * kLog2e; g.out_scale = alpha / (float)B; g.pos_idx = pos_idx;
+  g.part_m = (float*)(ws + pw.st.off_part_m); g.part_l = (float*)(ws + pw.st.off_part_l);
+  g.part_idx = (int*)(ws + pw.st.off_part_idx); g.pos_t = (float*)(ws + pw.st.off_pos);
+  g.lse2 = (const float*)(ws + pw.st.off_lse2); g.pos_pad = (const int32_t*)(ws + pw.st.off_pos_pad);
+  // statistics of every anchor, then their merge (lse2, row losses) and the loss
+  g.own = a2; g.str = c2; g.n_own = B; g.n_str = P; g.n_oblk = obA; g.stream_len = pw.len_a;
+  deepdist_walk_kernel<128, DD_STATS><<<obA * pw.nsa, 256, 0, s>>>(g);
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  LossArgs la{};
+  la.dt = GC_BF16; la.pos_idx = pos_idx; la.B = B; la.P = P; la.d = d; la.alpha = alpha; la.loss = loss; la.ws = ws; la.stream = s;
+  if (launch_stats_merge(la, pw.st) != hipSuccess) return GC_ERR_HIP;
+  // the two gradient walks
+  g.out_a = (float*)(ws + pw.off_da_part); g.out_e = (float*)(ws + pw.off_e_part);
+  deepdist_walk_kernel<128, DD_DA><<<obA * pw.nsa, 256, 0, s>>>(g);
+  g.own = c2; g.str = a2; g.n_own = P; g.n_str = B; g.n_oblk = obC; g.stream_len = pw.len_c;
+  g.out_a = (float*)(ws + pw.off_dc_part); g.out_e = nullptr;
+  deepdist_walk_kernel<128, DD_DC><<<obC * pw.nsc, 256, 0, s>>>(g);
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  float* da = (float*)(ws + pw.off_da);
+  float* dc = (float*)(ws + pw.off_dc);
+  float* e = (float*)(ws + pw.off_e);
+  auto sum_parts = [&](float* out, size_t off_part, int parts, size_t n) {
+    const float* srcs[1] = {(const float*)(ws + off_part)}; int counts[1] = {parts}; size_t strides[1] = {n};
+    return launch_partial_reduce(out, srcs, counts, strides, 1, n, s);
+  };
+  if (sum_parts(da, pw.off_da_part, pw.nsa, (size_t)B * h) != hipSuccess) return GC_ERR_HIP;
+  if (sum_parts(e, pw.off_e_part, pw.nsa, (size_t)B * h) != hipSuccess) return GC_ERR_HIP;
+  if (sum_parts(dc, pw.off_dc_part, pw.nsc, (size_t)P * h) != hipSuccess) return GC_ERR_HIP;
+  {  // dL/dw_k = sum_i e_ik: row slices, then their fixed-order sum
+    int sl = (B + 255) / 256;
+    if (sl > 64) sl = 64;
+    const int rps = (B + sl - 1) / sl;
+    sl = (B + rps - 1) / rps;
+    float* wp = (float*)(ws + pw.off_wpart);
+    colsum_slices_kernel<<<dim3(h / 32, sl), 256, 0, s>>>(e, B, h, rps, wp);
+    if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+    if (sum_parts(dw, pw.off_wpart, sl, (size_t)h) != hipSuccess) return GC_ERR_HIP;
+  }
+  // u = dL/da A, v = dL/dc C (third and fourth equation): Bt[n][k] = A^T[n][k]
+  auto pull = [&](const float* grad, int rows, const unsigned short* MT, float* out) {
+    SkinnyArgs k{};
+    k.A = grad; k.lda = h; k.Bt = MT; k.ldb = h; k.M = rows; k.N = d; k.K = h; k.Cf = out; k.ldc = d;
+    mlp_skinny_kernel<true, EP_PLAIN><<<dim3(d / 32, (rows + 31) / 32), 256, 0, s>>>(k);
+  };
+  pull(da, B, AT, u);
+  pull(dc, P, CT, v);
+  if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  // dL/dA = (dL/da)^T F, dL/dC = (dL/dc)^T G (second equation): rows cut into slices, partial sums in a fixed order
+  auto param_grad = [&](const float* grad, const void* x, int rows, int slices, int rps, float* out) {
+    float* part = (float*)(ws + pw.off_gpart);
+    const size_t n = (size_t)slices * h * d;
+    fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, n, 0.f);
+    WgradArgs k{};
+    k.A = grad; k.lda = h; k.B = x; k.ldb = d; k.M = h; k.N = d; k.K = rows; k.C = part; k.ldc = d;
+    wgrad_splitk_kernel<true, false><<<(d / 128) * (h / WG_M) * slices, 256, 0, s>>>(k, rps);
+    if (hipGetLastError() != hipSuccess) return hipErrorUnknown;
+    return sum_parts(out, pw.off_gpart, slices, (size_t)h * d);
+  };
+  if (param_grad(da, q, B, pw.slices_b, pw.rps_b, dA) != hipSuccess) return GC_ERR_HIP;
+  if (param_grad(dc, p, P, pw.slices_p, pw.rps_p, dC) != hipSuccess) return GC_ERR_HIP;
   return GC_OK;
 }
 

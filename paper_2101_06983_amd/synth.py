@@ -96,3 +96,12 @@ def bilinear_omega(d, dtype=torch.bfloat16, seed=SEED0 + 6, noise=0.5):
     `noise` times an iid N(0, 1/d) matrix, rounded to the storage type."""
     rng = np.random.default_rng(seed)
     return (torch.eye(d) + noise * _normal(rng, (d, d), d ** -0.5)).to(dtype)
+
+
+def deep_omega(d, h=128, dtype=torch.bfloat16, seed=SEED0 + 7):
+    """Parameters of the deep distance Phi = sum_k w_k tanh((A f)_k + (C g)_k): A, C [h, d] iid N(0, 1) (with
+    representation entries of variance 1/d the pre-activations then have variance about 2), w [h] iid N(0, 1/h),
+    rounded to the storage type."""
+    rng = np.random.default_rng(seed)
+    return dict(A=_normal(rng, (h, d), 1.0).to(dtype), C=_normal(rng, (h, d), 1.0).to(dtype),
+                w=_normal(rng, (h,), h ** -0.5).to(dtype))

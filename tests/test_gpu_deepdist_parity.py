@@ -1,0 +1,80 @@
+"""GPU parity of the deep-distance entry point (loss, u, v, dA, dC, dw) against the fp64 oracle; calls go through
+the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gc_oracle as O
+from paper_2101_06983_amd import binding as gc
+from paper_2101_06983_amd import synth
+from parity import TOL_BF16, check, check_loss, relerr, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+KEYS = ("u", "v", "dA", "dC", "dw")
+# The pair part of this path is fp32 throughout (no coefficient is rounded to bf16: the stated 2e-3 for bf16 inputs is
+# met with three orders of magnitude to spare); its fp32 operands enter the MFMA products around it as two bf16 pieces
+# (about 16 significant bits), and exp2 / reciprocal are the hardware's 1-ulp approximations: held to 1e-4.
+TOL_DEEP = 1e-4
+assert TOL_DEEP <= TOL_BF16
+
+
+def run(q, p, r, om, scale=1.0, temp=1.0):
+    out = gc.gc_deepdist_loss_and_grads_bf16(q.to(DEV), p.to(DEV), r.to(DEV), {k: t.to(DEV) for k, t in om.items()}, scale, temp)
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error(out["workspace"]) == gc.GC_OK
+    return out
+
+
+def oracle(q, p, r, om, scale=1.0, temp=1.0):
+    return O.deep_distance(synth.widen(q), synth.widen(p), r.numpy(), {k: synth.widen(t) for k, t in om.items()}, scale, temp)
+
+
+@pytest.mark.parametrize("B,P,d,scale,temp", [(96, 200, 128, 1.0, 1.0), (130, 257, 256, 2.0, 0.5), (300, 600, 768, 1.0, 1.0),
+                                              (1, 40, 384, 1.0, 1.0), (700, 333, 512, 1.0, 0.25), (64, 1, 128, 1.0, 1.0)])
+def test_deep_distance_matches_the_oracle(B, P, d, scale, temp):
+    q, p, _ = synth.dpr_batch(B, P, d, seed=8000 + B, positive_mix=0.3)
+    r = torch.from_numpy(np.random.default_rng(B + P).integers(0, P, size=B).astype(np.int32))   # shared positives
+    om = synth.deep_omega(d, seed=8100 + d)
+    want = oracle(q, p, r, om, scale, temp)
+    out = run(q, p, r, om, scale, temp)
+    tag = "deepdist %dx%dx%d" % (B, P, d)
+    check_loss(tag + " loss", out["loss"].item(), want["loss"], TOL_DEEP, 1e-6)
+    for k in KEYS:
+        if P == 1:   # one target: the softmax is 1, every gradient is zero
+            assert float(out[k].abs().max()) <= 1e-7, k
+        else:
+            check(tag + " " + k, relerr(to_np(out[k]), want[k]), TOL_DEEP)
+
+
+def test_deep_distance_at_the_benchmark_size():
+    """B = 1024, P = 2048, d = 768, h = 128 (the shape `bench.py --workload deepdist` times)."""
+    q, p, r = synth.dpr_batch(1024, 2048, 768, seed=8200)
+    om = synth.deep_omega(768)
+    want = oracle(q, p, r, om, 1.0, 0.5)
+    out = run(q, p, r, om, 1.0, 0.5)
+    check_loss("deepdist bench loss", out["loss"].item(), want["loss"], TOL_DEEP)
+    for k in KEYS:
+        check("deepdist bench " + k, relerr(to_np(out[k]), want[k]), TOL_DEEP)
+    # bit-identical from run to run (no atomics, fixed order of every sum)
+    again = run(q, p, r, om, 1.0, 0.5)
+    for k in KEYS + ("loss",):
+        assert torch.equal(out[k], again[k]), k
+
+
+def test_unsupported_shapes_and_bad_positive():
+    q, p, r = synth.dpr_batch(16, 32, 96, seed=8300)
+    with pytest.raises(gc.GradCacheError):
+        run(q, p, r, synth.deep_omega(96))
+    q, p, r = synth.dpr_batch(16, 32, 128, seed=8301)
+    with pytest.raises(gc.GradCacheError):
+        run(q, p, r, synth.deep_omega(128, h=64))
+    r = r.clone()
+    r[3] = 32
+    om = {k: t.to(DEV) for k, t in synth.deep_omega(128).items()}
+    out = gc.gc_deepdist_loss_and_grads_bf16(q.to(DEV), p.to(DEV), r.to(DEV), om)
+    torch.cuda.synchronize()
+    assert math.isnan(out["loss"].item())
+    assert gc.gc_check_async_error(out["workspace"]) == gc.GC_ERR_POS_IDX

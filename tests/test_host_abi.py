@@ -106,6 +106,25 @@ def test_argument_errors_are_raised_on_the_host():
     assert bl(*bargs(ws=None)) == gc.GC_ERR_WORKSPACE
     assert bl(*bargs(wsb=1024)) == gc.GC_ERR_WORKSPACE
     assert lib.gc_bilinear_workspace_bytes(8, 16, 96) == 0 and lib.gc_bilinear_workspace_bytes(8, 16, 128) > 0
+    dd = lib.gc_deepdist_loss_and_grads_bf16
+    dargs = lambda **k: [k.get("q", fake), fake, fake, k.get("B", 8), 16, k.get("d", 128), fake, fake, k.get("w", fake),
+                         k.get("h", 128), 1.0, k.get("temp", 1.0), fake, fake, fake, fake, fake, k.get("dw", fake),
+                         k.get("ws", fake), k.get("wsb", 1 << 30), None]
+    assert dd(*dargs(q=None)) == gc.GC_ERR_NULL
+    assert dd(*dargs(w=None)) == gc.GC_ERR_NULL
+    assert dd(*dargs(dw=None)) == gc.GC_ERR_NULL
+    assert dd(*dargs(B=0)) == gc.GC_ERR_SHAPE
+    assert dd(*dargs(temp=-1.0)) == gc.GC_ERR_SHAPE
+    assert dd(*dargs(d=96)) == gc.GC_ERR_UNSUPPORTED
+    assert dd(*dargs(h=64)) == gc.GC_ERR_UNSUPPORTED
+    assert dd(*dargs(ws=None)) == gc.GC_ERR_WORKSPACE
+    assert dd(*dargs(wsb=1024)) == gc.GC_ERR_WORKSPACE
+    assert lib.gc_deepdist_workspace_bytes(8, 16, 96, 128) == 0 and lib.gc_deepdist_workspace_bytes(8, 16, 128, 64) == 0
+    # linear in the rows (split partials of the h-wide pair gradients), never the B x P distance gradient cache
+    w1 = lib.gc_deepdist_workspace_bytes(4096, 8192, 768, 128)
+    assert 0 < w1 < 4096 * 8192 * 4
+    w2 = lib.gc_deepdist_workspace_bytes(8192, 16384, 768, 128)
+    assert w2 < 2 * w1 and w2 < 8192 * 16384 * 4 / 4
     # loss workspaces (split partials included; four gradient buffers for widths the MFMA kernels do not take):
     # never the n x n scores
     for n in (4096, 8192, 65536):
