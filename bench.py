@@ -125,11 +125,12 @@ def side_workload(args, gc, synth, dev):
         xq, xp, r = xq.to(dev), xp.to(dev), r.to(dev)
         params = {k: v.to(dev) for k, v in params.items()}
         grads = gc.zero_mlp_grads(params)
-        res = gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, grads=grads)
-        step = lambda: gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, out=res)   # same buffers every step
+        G = args.accumulate_group
+        res = gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, grads=grads, accumulate_group=G)
+        step = lambda: gc.gc_step_mlp_bf16(xq, xp, r, 32, 32, params, out=res, accumulate_group=G)   # same buffers every step
         rows = 512 + 1024
         flops = rows * 2.0 * (1024 * 3072 + 3072 * 768) * 4 + 6.0 * 512 * 1024 * 768   # fwd + (re-fwd layer 1, 3 bwd GEMMs) + loss
-        what = "Gradient Cache step, MLP 1024-3072-768, B=512 P=1024, chunk 32"
+        what = "Gradient Cache step, MLP 1024-3072-768, B=512 P=1024, chunk 32, accumulate_group %d" % G
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -158,6 +159,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5", "bidir", "bilinear", "deepdist"],
                     help="config3 (default) is the headline workload; the others print a shorter timing line")
+    ap.add_argument("--accumulate-group", type=int, default=1,
+                    help="config5 only: sub-batches per launch of Step 3 (1 = the sub-batch is the unit, as in the method)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise kernel 4 times that reads 1 GiB and writes 1 GiB (known HBM "
                          "traffic, larger than the 256 MB Infinity Cache; scales rocprofv3 FETCH_SIZE / WRITE_SIZE)")

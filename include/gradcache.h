@@ -287,6 +287,23 @@ int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32
                      const gc_mlp_grads* grads, void* q_rep, void* p_rep, float* dq, float* dp, void* workspace,
                      size_t workspace_bytes, void* stream);
 
+/*
+ * The same step with Step 3 run on groups of accumulate_group (1..8) consecutive sub-batches of one side: the
+ * re-encoded activations of a group are alive at once (accumulate_group times the activation memory of a sub-batch:
+ * the quantity the sub-batch size exists to bound, hence opt-in), and the fp32 gradient accumulators are read and
+ * written once per group instead of once per sub-batch.  The sub-batches of a group are still added in index order
+ * and in the same 32-row pieces, so every output has the bits gc_step_mlp_bf16 gives (accumulate_group = 1 is that
+ * call).  Grouping needs chunk_q and chunk_p to be multiples of 32; otherwise the call runs ungrouped.
+ * workspace: gc_step_mlp_grouped_workspace_bytes(B, P, chunk_q, chunk_p, w, accumulate_group).
+ * Errors as gc_step_mlp_bf16; GC_ERR_SHAPE for accumulate_group outside [1, 8].
+ */
+size_t gc_step_mlp_grouped_workspace_bytes(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w,
+                                           int accumulate_group);
+int gc_step_mlp_grouped_bf16(const void* x_q, int B, const void* x_p, int P, const int32_t* pos_idx, int chunk_q,
+                             int chunk_p, int accumulate_group, const gc_mlp_params* w, float scale, float temp,
+                             float* loss, const gc_mlp_grads* grads, void* q_rep, void* p_rep, float* dq, float* dp,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Forgets the recordings gc_step_mlp_bf16 keeps for the current device (at most 8 argument sets): call it before
  * freeing buffers that a recorded call named, or to give the graph memory back.  It waits for the device to be
  * idle (the one call besides gc_check_async_error that synchronises), then destroys the recorded graphs and the

@@ -30,6 +30,7 @@ EXPORTS = [
     "gc_bilinear_loss_and_grads_bf16", "gc_deepdist_workspace_bytes", "gc_deepdist_loss_and_grads_bf16",
     "gc_mlp_workspace_bytes", "gc_mlp_forward_nograd_bf16",
     "gc_chunk_surrogate_backward_bf16", "gc_step_mlp_workspace_bytes", "gc_step_mlp_bf16",
+    "gc_step_mlp_grouped_workspace_bytes", "gc_step_mlp_grouped_bf16",
     "gc_step_mlp_release", "gc_profile_begin", "gc_profile_end",
 ]
 
@@ -103,6 +104,10 @@ def load():
     lib.gc_step_mlp_workspace_bytes.argtypes = [ci, ci, ci, ci, pp]
     lib.gc_step_mlp_bf16.restype = ci
     lib.gc_step_mlp_bf16.argtypes = [vp, ci, vp, ci, vp, ci, ci, pp, cf, cf, vp, pg, vp, vp, vp, vp, vp, sz, vp]
+    lib.gc_step_mlp_grouped_workspace_bytes.restype = sz
+    lib.gc_step_mlp_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci, pp, ci]
+    lib.gc_step_mlp_grouped_bf16.restype = ci
+    lib.gc_step_mlp_grouped_bf16.argtypes = [vp, ci, vp, ci, vp, ci, ci, ci, pp, cf, cf, vp, pg, vp, vp, vp, vp, vp, sz, vp]
     lib.gc_step_mlp_release.restype = ci
     lib.gc_step_mlp_release.argtypes = []
     lib.gc_profile_begin.restype = ci
@@ -413,10 +418,11 @@ def gc_chunk_surrogate_backward_bf16(x_chunk, params, cached_grad_rows, grads, w
 
 
 def gc_step_mlp_bf16(x_q, x_p, pos_idx, chunk_q, chunk_p, params, scale=1.0, temp=1.0, grads=None, keep=False,
-                     workspace=None, stream=None, out=None):
+                     workspace=None, stream=None, out=None, accumulate_group=1):
     """One Gradient Cache step.  Returns dict(loss, grads[, q, p, dq, dp]).  Passing the dict a
     previous call returned as `out` reuses its buffers (loss, grads, kept outputs, workspace):
-    the library replays a recorded graph when a call repeats with the same buffers."""
+    the library replays a recorded graph when a call repeats with the same buffers.
+    accumulate_group > 1 calls gc_step_mlp_grouped_bf16."""
     if out is not None:
         grads = out["grads"] if grads is None else grads
         workspace = out["workspace"] if workspace is None else workspace
@@ -440,11 +446,18 @@ def gc_step_mlp_bf16(x_q, x_p, pos_idx, chunk_q, chunk_p, params, scale=1.0, tem
             t = prev.get(name)
             out[name] = t if t is not None else torch.empty(n, w.dout, dtype=dt, device=dev)
     if workspace is None:
-        workspace = alloc_workspace(lib.gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, ctypes.byref(w)), dev)
+        workspace = alloc_workspace(lib.gc_step_mlp_grouped_workspace_bytes(B, P, chunk_q, chunk_p, ctypes.byref(w),
+                                                                            accumulate_group), dev)
     wp, wn = _ws_ptr(workspace)
-    rc = lib.gc_step_mlp_bf16(_ptr(x_q), B, _ptr(x_p), P, _ptr(pos_idx), chunk_q, chunk_p, ctypes.byref(w), scale, temp,
-                              _ptr(loss), ctypes.byref(g), _ptr(out.get("q")), _ptr(out.get("p")), _ptr(out.get("dq")),
-                              _ptr(out.get("dp")), wp, wn, _stream(stream))
+    if accumulate_group == 1:
+        rc = lib.gc_step_mlp_bf16(_ptr(x_q), B, _ptr(x_p), P, _ptr(pos_idx), chunk_q, chunk_p, ctypes.byref(w), scale, temp,
+                                  _ptr(loss), ctypes.byref(g), _ptr(out.get("q")), _ptr(out.get("p")), _ptr(out.get("dq")),
+                                  _ptr(out.get("dp")), wp, wn, _stream(stream))
+    else:
+        rc = lib.gc_step_mlp_grouped_bf16(_ptr(x_q), B, _ptr(x_p), P, _ptr(pos_idx), chunk_q, chunk_p, accumulate_group,
+                                          ctypes.byref(w), scale, temp, _ptr(loss), ctypes.byref(g), _ptr(out.get("q")),
+                                          _ptr(out.get("p")), _ptr(out.get("dq")), _ptr(out.get("dp")), wp, wn,
+                                          _stream(stream))
     _check(rc, "gc_step_mlp_bf16")
     out["workspace"] = workspace
     return out

@@ -64,6 +64,8 @@ struct WgradArgs {
   int M, N, K;              // M a multiple of 64 (WG_M), N a multiple of 128, K = rows of the sub-batch (any)
   float* C; int ldc;        // += in place (one workgroup per tile: single writer)
   float* colsum;            // optional: [N] += column sums of B (db2; written by the m-tile 0 workgroups)
+  int colsum_rows;          // the column sums are added colsum_rows rows at a time (0: all K rows in one sum): a launch
+                            // that covers several sub-batches adds them one sub-batch after the other, as single launches do
 };
 
 // a workgroup's tile of C is WG_M x 128 (two 32-row MFMA tiles that share the B operand in LDS)
@@ -136,9 +138,14 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
       if (m < g.M) g.C[(size_t)m * g.ldc + n] = acc[mt][r];
     }
   if (g.colsum && by == 0 && tid < 128) {
-    float s = 0.f;
-    for (int k = 0; k < g.K; k++) s += ((const float*)g.B)[(size_t)k * g.ldb + n0 + tid];   // (fp32 B only)
-    g.colsum[n0 + tid] += s;
+    const int step = g.colsum_rows > 0 ? g.colsum_rows : g.K;
+    float total = g.colsum[n0 + tid];
+    for (int k0 = 0; k0 < g.K; k0 += step) {
+      float s = 0.f;
+      for (int k = k0; k < min(g.K, k0 + step); k++) s += ((const float*)g.B)[(size_t)k * g.ldb + n0 + tid];   // (fp32 B only)
+      total += s;
+    }
+    g.colsum[n0 + tid] = total;
   }
 }
 
@@ -481,7 +488,15 @@ struct StepWs {
   size_t loss_bytes, mlp_bytes, act_bytes;
 };
 
-static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w) {
+// sub-batches that one launch of Step 3 covers: the caller's accumulate_group where the sub-batch sizes allow the
+// result to stay bit-identical (whole 32-row MFMA k-chunks per sub-batch), else 1
+static int effective_group(int group, int chunk_q, int chunk_p) {
+  if (group < 1) group = 1;
+  if (group > kGroup) group = kGroup;
+  return (chunk_q % 32 == 0 && chunk_p % 32 == 0) ? group : 1;
+}
+
+static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w, int group) {
   StepWs s{};
   size_t off = 0;
   auto take = [&](size_t b) { size_t o = off; off = up256(off + b); return o; };
@@ -494,7 +509,8 @@ static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_par
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
   s.mlp_bytes = carve_mlp_ws(nullptr, group_rows(cmax, B > P ? B : P), w).total;
   s.off_mlp = take(s.mlp_bytes);
-  s.act_bytes = 3 * up256((size_t)cmax * w->dh * 4);       // H, Act, dH of one more lane
+  const int g3 = effective_group(group, chunk_q, chunk_p);
+  s.act_bytes = 3 * up256((size_t)cmax * g3 * w->dh * 4);  // H, Act, dH of one more lane
   s.off_act = take((kLanes - 1) * s.act_bytes);
   s.total = off;
   return s;
@@ -510,6 +526,7 @@ struct StepCall {
   gc_mlp_grads grads;
   void* q_rep; void* p_rep; float* dq; float* dp;
   void* workspace;
+  int group;   // accumulate_group
 };
 
 // enqueues Steps 1-3 on s
@@ -520,7 +537,8 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
   const float scale = c.scale, temp = c.temp;
   float* loss = c.loss; void* q_rep = c.q_rep; void* p_rep = c.p_rep; float* dq = c.dq; float* dp = c.dp;
   void* workspace = c.workspace;
-  const StepWs sw = plan_step(B, P, chunk_q, chunk_p, w);
+  const StepWs sw = plan_step(B, P, chunk_q, chunk_p, w, c.group);
+  const int g3 = effective_group(c.group, chunk_q, chunk_p);
   char* base = (char*)workspace;
   unsigned short* Q = q_rep ? (unsigned short*)q_rep : (unsigned short*)(base + sw.off_q);
   unsigned short* Pm = p_rep ? (unsigned short*)p_rep : (unsigned short*)(base + sw.off_p);
@@ -532,18 +550,22 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
   for (int l = 1; l < kLanes; l++) {
     lane[l] = lane[0];
     char* ab = base + sw.off_act + (size_t)(l - 1) * sw.act_bytes;
-    const size_t one = up256((size_t)cmax * w->dh * 4);
+    const size_t one = up256((size_t)cmax * g3 * w->dh * 4);
     lane[l].H = (float*)ab; lane[l].ActF = (float*)(ab + one); lane[l].dH = (float*)(ab + 2 * one);
   }
   auto ok = [](hipError_t e) { return e == hipSuccess; };
   if (!ok(mlp_prepare(w, lane[0], s))) return GC_ERR_HIP;
-  // the sub-batches in index order: anchors first, then targets
-  struct Sub { const unsigned short* x; int rows; unsigned short* y; const float* u; };
+  // the sub-batches in index order: anchors first, then targets.  With accumulate_group = G > 1 an entry covers G
+  // consecutive sub-batches of one side (their rows are contiguous): the kernels of Step 3 visit the rows in the same
+  // order and 32-row k-chunks as G single launches would, and add the bias gradients one sub-batch after the other
+  // (`chunk`), so the parameter gradients keep their bits while the fp32 accumulators make one trip through HBM
+  // instead of G.
+  struct Sub { const unsigned short* x; int rows; unsigned short* y; const float* u; int chunk; };
   std::vector<Sub> subs;
-  for (int a = 0; a < B; a += chunk_q)
-    subs.push_back({(const unsigned short*)x_q + (size_t)a * w->din, B - a < chunk_q ? B - a : chunk_q, Q + (size_t)a * w->dout, dQ + (size_t)a * w->dout});
-  for (int a = 0; a < P; a += chunk_p)
-    subs.push_back({(const unsigned short*)x_p + (size_t)a * w->din, P - a < chunk_p ? P - a : chunk_p, Pm + (size_t)a * w->dout, dP + (size_t)a * w->dout});
+  for (int a = 0; a < B; a += chunk_q * g3)
+    subs.push_back({(const unsigned short*)x_q + (size_t)a * w->din, B - a < chunk_q * g3 ? B - a : chunk_q * g3, Q + (size_t)a * w->dout, dQ + (size_t)a * w->dout, chunk_q});
+  for (int a = 0; a < P; a += chunk_p * g3)
+    subs.push_back({(const unsigned short*)x_p + (size_t)a * w->din, P - a < chunk_p * g3 ? P - a : chunk_p * g3, Pm + (size_t)a * w->dout, dP + (size_t)a * w->dout, chunk_p});
   const int nsub = (int)subs.size();
   // Step 1: graph-less forward, kGroup sub-batches per launch, representations kept
   const int gq = group_rows(chunk_q, B), gp = group_rows(chunk_p, P);
@@ -566,6 +588,7 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
     if (i >= 2) {                      // weight gradients of sub-batch i-2
       const Sub& sb = subs[i - 2];
       wgrad_args(sb.x, sb.rows, w, sb.u, grads, lane[(i - 2) % kLanes], a3.g2, a3.g1);
+      a3.g2.colsum_rows = sb.chunk;
       a3.n_wg2 = n2; a3.n_wg = n2 + n1;
     }
     if (i >= 1 && i - 1 < nsub) {      // dH, db1 of sub-batch i-1
@@ -917,27 +940,39 @@ int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp
   return mlp_backward(x_chunk, rows, w, cached_grad_rows, acc, ws, (hipStream_t)stream) == hipSuccess ? GC_OK : GC_ERR_HIP;
 }
 
+size_t gc_step_mlp_grouped_workspace_bytes(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w, int accumulate_group) {
+  if (B < 1 || P < 1 || chunk_q < 1 || chunk_p < 1 || accumulate_group < 1 || check_mlp_params(w) != GC_OK) return 0;
+  return plan_step(B, P, chunk_q, chunk_p, w, accumulate_group).total;
+}
 size_t gc_step_mlp_workspace_bytes(int B, int P, int chunk_q, int chunk_p, const gc_mlp_params* w) {
-  if (B < 1 || P < 1 || chunk_q < 1 || chunk_p < 1 || check_mlp_params(w) != GC_OK) return 0;
-  return plan_step(B, P, chunk_q, chunk_p, w).total;
+  return gc_step_mlp_grouped_workspace_bytes(B, P, chunk_q, chunk_p, w, 1);
 }
 
 int gc_step_mlp_bf16(const void* x_q, int B, const void* x_p, int P, const int32_t* pos_idx, int chunk_q, int chunk_p,
                      const gc_mlp_params* w, float scale, float temp, float* loss, const gc_mlp_grads* grads, void* q_rep,
                      void* p_rep, float* dq, float* dp, void* workspace, size_t workspace_bytes, void* stream) {
+  return gc_step_mlp_grouped_bf16(x_q, B, x_p, P, pos_idx, chunk_q, chunk_p, 1, w, scale, temp, loss, grads, q_rep, p_rep,
+                                  dq, dp, workspace, workspace_bytes, stream);
+}
+
+int gc_step_mlp_grouped_bf16(const void* x_q, int B, const void* x_p, int P, const int32_t* pos_idx, int chunk_q,
+                             int chunk_p, int accumulate_group, const gc_mlp_params* w, float scale, float temp, float* loss,
+                             const gc_mlp_grads* grads, void* q_rep, void* p_rep, float* dq, float* dp, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (accumulate_group < 1 || accumulate_group > 8) return GC_ERR_SHAPE;
   if (!x_q || !x_p || !pos_idx || !loss || !grads) return GC_ERR_NULL;
   if (!grads->dW1 || !grads->db1 || !grads->dW2 || !grads->db2) return GC_ERR_NULL;
   int rc = check_mlp_params(w);
   if (rc != GC_OK) return rc;
   if (B < 1 || P < 1 || chunk_q < 1 || chunk_p < 1 || B > (1 << 24) || P > (1 << 24)) return GC_ERR_SHAPE;
   if (!(scale > 0.f) || !(temp > 0.f) || !(scale / temp > 0.f) || !(scale / temp < 3.0e38f)) return GC_ERR_SHAPE;
-  const StepWs sw = plan_step(B, P, chunk_q, chunk_p, w);
+  const StepWs sw = plan_step(B, P, chunk_q, chunk_p, w, accumulate_group);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sw.total) return GC_ERR_WORKSPACE;
   StepCall c;
   memset(&c, 0, sizeof(c));  // the struct is compared bytewise: no stray padding
   c.x_q = x_q; c.x_p = x_p; c.pos_idx = pos_idx; c.B = B; c.P = P; c.chunk_q = chunk_q; c.chunk_p = chunk_p;
   c.w = *w; c.scale = scale; c.temp = temp; c.loss = loss; c.grads = *grads; c.q_rep = q_rep; c.p_rep = p_rep;
-  c.dq = dq; c.dp = dp; c.workspace = workspace;
+  c.dq = dq; c.dp = dp; c.workspace = workspace; c.group = accumulate_group;
   return run_step(c, (hipStream_t)stream);
 }
 

@@ -171,6 +171,27 @@ def test_config5_full_size():
     assert torch.equal(out["q"], again["q"]) and torch.equal(out["dp"], again["dp"])
 
 
+@pytest.mark.parametrize("B,P,cq,cp,group", [(512, 1024, 32, 32, 8), (200, 330, 32, 64, 3), (96, 96, 16, 32, 4)])
+def test_accumulate_group_keeps_the_bits(B, P, cq, cp, group):
+    """Step 3 on groups of sub-batches (gc_step_mlp_grouped_bf16) reads and writes the gradient accumulators once per
+    group; the sub-batches are still added in index order and in the same 32-row pieces: bit-identical to the
+    ungrouped call (the last case has a sub-batch size that is no multiple of 32 and runs ungrouped)."""
+    if (B, P) == (512, 1024):
+        xq, xp, r, params = synth.mlp_problem()
+    else:
+        xq, xp, r, params = synth.mlp_problem(B, P, 128, 256, 128, seed=synth.SEED0 + 70 + B)
+    dp = dev_params(params)
+    one = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), cq, cp, dp, keep=True)
+    grp = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), cq, cp, dp, keep=True, accumulate_group=group)
+    torch.cuda.synchronize()
+    assert torch.equal(one["loss"], grp["loss"])
+    for k in ("q", "p", "dq", "dp"):
+        assert torch.equal(one[k], grp[k]), k
+    for k in ("W1", "b1", "W2", "b2"):
+        assert torch.equal(one["grads"][k], grp["grads"][k]), k
+    assert float(one["grads"]["W1"].abs().max()) > 0
+
+
 def test_step_replayed_with_the_same_buffers_matches_the_first_call():
     # a call that repeats with the same buffers is recorded into a graph and replayed: every replay must
     # give the bits of the directly enqueued first call, with other GPU work in between
