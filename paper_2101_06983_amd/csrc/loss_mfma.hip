@@ -643,6 +643,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   // that runs at 1 / (4 NI) * (4 k + WAVE) of that time.  Sections: 0 = phase 1 before the barrier,
   // 1 = phase 1 after it, 2 = phase 2.
   constexpr int KS_PRE = (C::KS + 1) / 2;            // k-steps of phase 1 issued before the barrier
+  static_assert(C::KS == C::CT, "the steady loop pairs the k-steps of phase 1 with the column tiles of phase 2");
   constexpr int MA = 4 * KS_PRE, MB = 4 * (C::KS - KS_PRE), MC = 2 * C::CT;  // MFMAs per section
   constexpr int T16 = 19, T32 = 33;                  // measured issue-to-issue cycles of the two MFMA shapes
   auto slot_of = [](int wave, int k, int sec) constexpr -> int {  // MFMA index in section sec, or -1
@@ -654,6 +655,15 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     t -= T16 * MB;
     return sec == 2 ? (t / T32 < MC ? t / T32 : MC - 1) : -1;
   };
+  // loads of tile u+4 that a steady iteration of wave `wave` has issued once the round of phase-2 MFMA `idx` is over
+  auto issued_by = [slot_of](int wave, int idx) constexpr -> int {
+    int n = 0;
+    for (int k = 0; k < NI; k++) {
+      const int s2 = slot_of(wave, k, 2);
+      if (slot_of(wave, k, 0) >= 0 || slot_of(wave, k, 1) >= 0 || (s2 >= 0 && s2 <= idx)) n++;
+    }
+    return n;
+  };
   // called after MFMA number IDX of section SEC; pin_a: a register that MFMA read, pin_b: one that the
   // next MFMA reads (TWO: they differ)
   auto spread = [&](auto wave_tag, auto sec_tag, auto idx_tag, auto two_tag, int t_pf, unsigned so_pf, u32x4& pin_a, u32x4& pin_b) __attribute__((always_inline)) {
@@ -664,8 +674,25 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       });
     }
   };
-  auto p1_mfma_spread = [&](auto wave_tag, auto sec_tag, int t_pf, unsigned so_pf) __attribute__((always_inline)) {
-    constexpr int SEC = decltype(sec_tag)::value;
+  // phase 2 of the tile in the stage at `so` (WAVE >= 0: a steady iteration, which also issues its share
+  // of the loads of the tile that starts at row t_pf into the stage at so_pf)
+  u32x4 bfr[C::CT];  // phase-2 B fragments (bf16x8 each)
+  auto p2_load = [&](unsigned so, int c0, int c1) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ct = c0; ct < c1; ct++) {
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2lo[ct & 1] + so + 64 * ct));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2hi[ct & 1] + so + 64 * ct));
+      s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      bfr[ct] = __builtin_bit_cast(u32x4, bb);
+    }
+  };
+  // The LDS pipe is shared by the four waves, which run in step: fragment reads bunched at the start of a phase
+  // leave the MFMAs waiting for LDS and LDS idle during the MFMAs.  A steady iteration therefore reads every fragment
+  // half an iteration ahead, into the registers of a fragment that has just been used up: the transposed fragment ct
+  // of phase 2 (tile u, stage so_p2) right behind the four MFMAs of k-step ct of phase 1, and the fragment of k-step ks
+  // of the NEXT iteration's phase 1 (tile u+3, stage so_p1n) right behind the two MFMAs of column tile ks of phase 2.
+  auto p1_mfma_spread = [&](auto wave_tag, auto sec_tag, int t_pf, unsigned so_pf, unsigned so_p2) __attribute__((always_inline)) {
+    constexpr int SEC = decltype(sec_tag)::value, WAVE = decltype(wave_tag)::value;
     constexpr int KS0 = SEC == 0 ? 0 : KS_PRE, KS1 = SEC == 0 ? KS_PRE : C::KS;
     static_for<4 * (KS1 - KS0)>([&](auto i_tag) __attribute__((always_inline)) {
       constexpr int i = decltype(i_tag)::value, ks = KS0 + i / 4, nq = i % 4;
@@ -673,28 +700,23 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       constexpr int ksn = KS0 + (i + 1) / 4;  // k-step of the next MFMA of the section
       if constexpr (ksn != ks && ksn < KS1) spread(wave_tag, sec_tag, i_tag, std::true_type{}, t_pf, so_pf, afr[ks], afr[ksn]);
       else spread(wave_tag, sec_tag, i_tag, std::false_type{}, t_pf, so_pf, afr[ks], afr[ks]);
+      if constexpr (WAVE >= 0 && nq == 3) p2_load(so_p2, ks, ks + 1);
     });
   };
-  // phase 2 of the tile in the stage at `so` (WAVE >= 0: a steady iteration, which also issues its share
-  // of the loads of the tile that starts at row t_pf into the stage at so_pf)
-  u32x4 bfr[C::CT];  // phase-2 B fragments (bf16x8 each)
-  auto p2_load = [&](unsigned so) __attribute__((always_inline)) {
-#pragma unroll
-    for (int ct = 0; ct < C::CT; ct++) {
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2lo[ct & 1] + so + 64 * ct));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p2hi[ct & 1] + so + 64 * ct));
-      s16x8 bb = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      bfr[ct] = __builtin_bit_cast(u32x4, bb);
-    }
-  };
   // after_round(i): arithmetic of the caller that is to run in the shadow of MFMA i
-  auto phase2 = [&](const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf, auto&& after_round) __attribute__((always_inline)) {
+  auto phase2 = [&](const bf16x8 (&gf)[2], auto wave_tag, int t_pf, unsigned so_pf, unsigned so_p1n, auto&& after_round) __attribute__((always_inline)) {
+    constexpr int WAVE = decltype(wave_tag)::value;
     static_for<MC>([&](auto i_tag) __attribute__((always_inline)) {
       constexpr int i = decltype(i_tag)::value, ct = i / 2, mt = i % 2;
       acc[mt][ct] = mfma32(gf[mt], __builtin_bit_cast(bf16x8, bfr[ct]), acc[mt][ct]);
       constexpr std::integral_constant<int, 2> sec{};
       if constexpr (mt == 1 && ct + 1 < C::CT) spread(wave_tag, sec, i_tag, std::true_type{}, t_pf, so_pf, bfr[ct], bfr[ct + 1]);
       else spread(wave_tag, sec, i_tag, std::false_type{}, t_pf, so_pf, bfr[ct], bfr[ct]);
+      if constexpr (WAVE >= 0 && mt == 1) {
+        // tile u+3 has landed once at most the loads this iteration has issued so far (for tile u+4) are in flight
+        if constexpr (ct == 0) wait_vmem<issued_by(WAVE, i)>();
+        p1_load(so_p1n, ct, ct + 1);
+      }
       after_round(i_tag);
     });
   };
@@ -720,10 +742,10 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     const bool p1 = STEADY || (u + 2 < nt);            // tile u+2: phase 1
     const bool pf = STEADY || (u >= 0 && u + 4 < nt);  // tile u+4: start its loads
     __builtin_amdgcn_iglp_opt(0);  // scheduler hint: interleave the LDS reads with the MFMA stream
-    if (p1) {
-      // tile u+2 has landed (in a steady iteration the loads of tile u+3 may still be in flight).  Its
-      // fragment reads are issued ahead of the writes below, so they come back first.
-      if (STEADY) wait_vmem<NI>(); else wait_vmem<0>();
+    if (p1 && !STEADY) {
+      // tile u+2 has landed; its fragment reads are issued ahead of the writes below, so they come back first.  (A
+      // steady iteration finds them in registers: the iteration before it has read them during its phase 2.)
+      wait_vmem<0>();
       p1_load(so2, 0, C::KS);
     }
     // the partial tile of the owner rows this wave finishes itself stays in registers (steady loop: the wave
@@ -740,7 +762,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
       if (g16 == 0) *(float*)(fwp + PAR0 * C::F_PAR + (16 * w + l16) * 4) = f_pub;
       if (lane == 0) *(int*)(fwp + PAR0 * C::F_PAR + 256 + 4 * w) = need_pub;
     }
-    if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 0>{}, t_pf, so4);  // while the writes drain and the barrier gathers the waves
+    if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 0>{}, t_pf, so4, so0);  // while the writes drain and the barrier gathers the waves
     __syncthreads();
     f32x4 xr[4];
     if (xw) {
@@ -762,9 +784,9 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     }
     i32x4 fl = {0, 0, 0, 0};
     if (ONLINE && gw) fl = *(const i32x4*)(fwp + PAR0 * C::F_PAR + 256);
-    if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4);
+    if (p1) p1_mfma_spread(wave_tag, std::integral_constant<int, 1>{}, t_pf, so4, so0);
     if constexpr (ONLINE) __builtin_amdgcn_sched_barrier(0);  // the flag test (and its wait for LDS) stays behind these MFMAs
-    if (gw) p2_load(so0);   // ahead of the flag test: LDS answers in order, the test waits for the flags only
+    if (!STEADY && gw) p2_load(so0, 0, C::CT);   // (a steady iteration has read them behind the MFMAs of phase 1)
     if (ONLINE && gw) {
       // rare after the first tile: some row's reference went up, every wave rescales its columns of those rows
       if (__builtin_amdgcn_ballot_w64((fl[0] | fl[1] | fl[2] | fl[3]) != 0) != 0) {
@@ -861,7 +883,8 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         __builtin_amdgcn_sched_barrier(0);  // the rounds stay in order
       }
     };
-    if (gw) phase2(gf, wave_tag, t_pf, so4, after_round);
+    const unsigned so3 = (so2 + C::STAGE >= RING) ? so2 + C::STAGE - RING : so2 + C::STAGE;   // tile u+3
+    if (gw) phase2(gf, wave_tag, t_pf, so4, so3, after_round);
     if (xw) {
       if constexpr (!INTER) static_for<NP>(piece);
       if constexpr (ONLINE) {
@@ -910,6 +933,12 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
         }
         gq = __builtin_convertvector(gv, bf16x4);
       }
+    }
+    // the iteration after this one may be a steady one, which expects the phase-1 fragments of its tile (u+3) in
+    // registers
+    if (!STEADY && u + 3 < nt) {
+      wait_vmem<0>();
+      p1_load(so3, 0, C::KS);
     }
     if (!STEADY && pf) prefetch(u + 4, so4);  // in a steady iteration phase 2 has issued these loads
   };
