@@ -729,9 +729,13 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
 
   // One pipeline iteration (see the header comment); so0 = ring offset of the stage of tile u.  STEADY:
   // every pipeline slot is live, the tiles involved are full and not the last ones.
-  auto body = [&](int u, unsigned so0, auto wave_tag) __attribute__((always_inline)) {
-    constexpr int WAVE = decltype(wave_tag)::value;
+  // STG >= 0: the ring stage of tile u is known at compile time (the steady loop is unrolled over the five stages), so
+  // every LDS address of the iteration is a per-lane base plus an immediate and no address arithmetic is issued: a
+  // single wave per SIMD issues everything itself, and what it issues besides the MFMAs is what the loop's time is made of.
+  auto body = [&](int u, unsigned so0_dyn, auto stage_tag, auto wave_tag) __attribute__((always_inline)) {
+    constexpr int WAVE = decltype(wave_tag)::value, STG = decltype(stage_tag)::value;
     constexpr bool STEADY = WAVE >= 0;
+    const unsigned so0 = STG >= 0 ? (unsigned)(STG * C::STAGE) : so0_dyn;
     const int t_pf = sbeg + (u + 4) * GR_T;  // first row of tile u+4
     const unsigned so1 = (so0 + C::STAGE >= RING) ? so0 + C::STAGE - RING : so0 + C::STAGE;   // tile u+1
     const unsigned so2 = (so1 + C::STAGE >= RING) ? so1 + C::STAGE - RING : so1 + C::STAGE;   // tile u+2
@@ -951,12 +955,25 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
   auto next_stage = [&](unsigned so) __attribute__((always_inline)) -> unsigned { return (so + C::STAGE >= RING) ? so + C::STAGE - RING : so + C::STAGE; };
   unsigned so = RING - C::STAGE;  // stage of "tile -1"
   constexpr std::integral_constant<int, -1> unsteady{};
-  body(-1, so, unsteady);
+  constexpr std::integral_constant<int, -1> any_stage{};
+  body(-1, so, any_stage, unsteady);
   so = 0;
   int u = 0;
   auto steady_loop = [&](auto wave_tag) __attribute__((always_inline)) {
+    if constexpr (D == 768) {
+      // the widest kernel (the headline shape) is unrolled over the ring: five iterations per trip, tile u is in
+      // stage u % 5 and u is a multiple of 5 here (so stays 0); measured 4 % on the dP walk.  The other widths keep
+      // the rolled loop (five copies of every width would more than double the time this file takes to compile).
 #pragma unroll 1
-    for (; u + 5 < nt; u++) { body(u, so, wave_tag); so = next_stage(so); }
+      for (; u + GR_STAGES + 4 < nt; u += GR_STAGES) {
+        static_for<GR_STAGES>([&](auto stage_tag) __attribute__((always_inline)) {
+          body(u + decltype(stage_tag)::value, 0u, stage_tag, wave_tag);
+        });
+      }
+    } else {
+#pragma unroll 1
+      for (; u + 5 < nt; u++) { body(u, so, any_stage, wave_tag); so = next_stage(so); }
+    }
   };
   // (the steady body of the one-direction kernels has no place for the diagonal mask: with mask_self every
   // iteration takes the general body)
@@ -969,7 +986,7 @@ __device__ __forceinline__ void grad_body(const GradArgs& ga, int oblk, int spli
     }
   }
 #pragma unroll 1
-  for (; u < nt; u++) { body(u, so, unsteady); so = next_stage(so); }
+  for (; u < nt; u++) { body(u, so, any_stage, unsteady); so = next_stage(so); }
 
   // ---- epilogue: scale by alpha / B and store the owned rows ---------------------------------------------------------
   float* out = OWNER_IS_Q ? (ga.dq_out + (size_t)split * ga.dq_split_stride) : (ga.dp_out + (size_t)split * ga.dp_split_stride);
