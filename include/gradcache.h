@@ -58,6 +58,8 @@ typedef enum {
   GC_ERR_TOO_LARGE = -7    /* gc_loss_and_rep_grad_bf16_static: the shape needs more scratch than GC_STATIC_SCRATCH_BYTES */
 } gc_status;
 
+/* element types; the entry points take them as int, so that a value outside the list is an error (GC_ERR_UNSUPPORTED),
+ * not an invalid enum load */
 typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
 
 /* flags of gc_loss_and_rep_grad_ex */
@@ -79,7 +81,7 @@ const char* gc_strerror(int status);
  * Holds per-row softmax statistics and the split partial sums of dq and dp:
  * O((B + P) * d), never O(B * P) (Sec. "Gradient Cache Technique": the cache is
  * (|S| d + |T| d) numbers).  Returns 0 for an invalid shape. */
-size_t gc_workspace_bytes(int B, int P, int d, gc_dtype dt);
+size_t gc_workspace_bytes(int B, int P, int d, int dt);
 
 /*
  * Loss and representation gradients (Step 2; Eq. 1, 4, 5, 6, 7).
@@ -118,14 +120,14 @@ int gc_loss_and_rep_grad_bf16_static(const void* q, const void* p, const int32_t
 
 /*
  * Extended form of the same computation.
- *   dt         type of q and p
+ *   dt         type of q and p, a gc_dtype value
  *   flags      0 or GC_MASK_SELF, optionally with one of GC_PATH_ONLINE / GC_PATH_STATS_PASS, and GC_CACHE_BF16
  *   loss, dq, dp, lse, argmax   each may be NULL (not produced).  lse[B] float is
  *              logsumexp_j s_ij; argmax[B] int32 is the smallest j that attains
  *              max_j s_ij in the kernel's fp32 scores.
  *   workspace  device, 256-byte aligned, at least gc_workspace_bytes(B,P,d,dt)
  */
-int gc_loss_and_rep_grad_ex(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+int gc_loss_and_rep_grad_ex(int dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
                             float scale, float temp, unsigned flags, float* loss, float* dq, float* dp, float* lse,
                             int32_t* argmax, void* workspace, size_t workspace_bytes, void* stream);
 

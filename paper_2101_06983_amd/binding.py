@@ -10,7 +10,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgradcache.so")
+LIB_PATH = os.environ.get("GRADCACHE_LIB") or os.path.join(_HERE, "libgradcache.so")
 
 GC_OK = 0
 GC_ERR_NULL, GC_ERR_SHAPE, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_POS_IDX, GC_ERR_HIP = -1, -2, -3, -4, -5, -6

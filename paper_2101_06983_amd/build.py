@@ -61,5 +61,31 @@ def build(force=True, extra_flags=(), verbose=False):
     return OUT
 
 
+def build_host_checked(out, bdir):
+    """A second library whose HOST code carries UndefinedBehaviorSanitizer checks that abort at the first finding
+    (device code is unchanged: the sanitizer does not exist for it).  For the argument-check tests, which need no
+    GPU.  api.hip, mlp.hip and loss_generic.hip are compiled again with the checks; the object of loss_mfma.hip,
+    minutes of device compilation and no argument checks of its own, is taken from the ordinary build."""
+    mfma = os.path.join(ROOT, "_build", "loss_mfma.o")
+    if not os.path.exists(mfma):
+        raise FileNotFoundError(mfma)
+    san = ["-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+    srcs = [s for s in SOURCES if s != "loss_mfma.hip"]
+    objs = [os.path.join(bdir, s.replace(".hip", "_ubsan.o")) for s in srcs]
+    with ThreadPoolExecutor(max_workers=len(srcs)) as ex:
+        list(ex.map(lambda j: _compile(j[0], j[1], san), zip(srcs, objs)))
+    rt = subprocess.run([HIPCC, "-print-file-name=libclang_rt.ubsan_standalone-x86_64.so"], capture_output=True,
+                        text=True).stdout.strip()
+    if not os.path.isabs(rt):
+        raise FileNotFoundError("the compiler's shared UBSan runtime")
+    rt = os.path.dirname(os.path.realpath(rt))
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-fsanitize=undefined",
+                        "-shared-libsan", "-Wl,-rpath," + rt, "-Wno-option-ignored", "-o", out] + objs + [mfma],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force="-f" in sys.argv, verbose=True))

@@ -247,7 +247,7 @@ static int run_loss(const LossArgs& a_in, const LossPlan& pl) {
   return GC_OK;
 }
 
-static int check_loss_args(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+static int check_loss_args(int dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
                            float scale, float temp, unsigned flags) {
   if (!q || !p || !pos_idx) return GC_ERR_NULL;
   if (!shape_ok(B, P, d)) return GC_ERR_SHAPE;
@@ -300,16 +300,17 @@ const char* gc_strerror(int status) {
   }
 }
 
-size_t gc_workspace_bytes(int B, int P, int d, gc_dtype dt) {
+size_t gc_workspace_bytes(int B, int P, int d, int dt) {
   if (!shape_ok(B, P, d) || (dt != GC_F32 && dt != GC_BF16)) return 0;
-  return make_loss_plan(B, P, d, dt, false).total;
+  return make_loss_plan(B, P, d, (gc_dtype)dt, false).total;
 }
 
-int gc_loss_and_rep_grad_ex(gc_dtype dt, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
+int gc_loss_and_rep_grad_ex(int dt_int, const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d,
                             float scale, float temp, unsigned flags, float* loss, float* dq, float* dp, float* lse,
                             int32_t* argmax, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = check_loss_args(dt, q, p, pos_idx, B, P, d, scale, temp, flags);
+  int rc = check_loss_args(dt_int, q, p, pos_idx, B, P, d, scale, temp, flags);
   if (rc != GC_OK) return rc;
+  const gc_dtype dt = (gc_dtype)dt_int;
   const LossPlan pl = make_loss_plan(B, P, d, dt, false);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return GC_ERR_WORKSPACE;
   LossArgs a{};

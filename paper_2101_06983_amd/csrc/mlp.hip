@@ -375,11 +375,13 @@ static inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 static MlpWs carve_mlp_ws(char* base, int rows, const gc_mlp_params* w) {
   MlpWs m{};
   size_t off = 0;
-  m.H = (float*)(base + off); off += up256((size_t)rows * w->dh * 4);
-  m.ActF = (float*)(base + off); off += up256((size_t)rows * w->dh * 4);
-  m.dH = (float*)(base + off); off += up256((size_t)rows * w->dh * 4);
-  m.W1T = (unsigned short*)(base + off); off += up256((size_t)w->din * w->dh * 2);
-  m.W2T = (unsigned short*)(base + off); off += up256((size_t)w->dh * w->dout * 2);
+  // integer arithmetic: the sizing calls carve from a null base
+  auto at = [base](size_t o) { return (uintptr_t)base + o; };
+  m.H = (float*)at(off); off += up256((size_t)rows * w->dh * 4);
+  m.ActF = (float*)at(off); off += up256((size_t)rows * w->dh * 4);
+  m.dH = (float*)at(off); off += up256((size_t)rows * w->dh * 4);
+  m.W1T = (unsigned short*)at(off); off += up256((size_t)w->din * w->dh * 2);
+  m.W2T = (unsigned short*)at(off); off += up256((size_t)w->dh * w->dout * 2);
   m.total = off;
   return m;
 }

@@ -169,3 +169,27 @@ def test_mlp_argument_errors_are_raised_on_the_host():
     assert step(*sargs(loss=None)) == gc.GC_ERR_NULL
     assert step(*sargs(ws=None)) == gc.GC_ERR_WORKSPACE
     assert step(*sargs(wsb=1024)) == gc.GC_ERR_WORKSPACE
+
+
+def test_host_checks_run_clean_under_ubsan(tmp_path):
+    """The same argument-check tests against a build whose host code carries UndefinedBehaviorSanitizer checks that
+    abort at the first finding (an enum loaded from an invalid integer, arithmetic on a null workspace base, an
+    overflowing size): every rejected call must be rejected by defined behaviour."""
+    import subprocess
+    import sys
+
+    from paper_2101_06983_amd import build
+
+    if os.environ.get("GRADCACHE_LIB"):
+        pytest.skip("already running against a substituted library")
+    try:
+        lib = build.build_host_checked(str(tmp_path / "libgradcache_ubsan.so"), str(tmp_path))
+    except FileNotFoundError as e:
+        pytest.skip("no ordinary build to take the loss_mfma object from, or no shared UBSan runtime: %s" % e)
+    env = dict(os.environ, GRADCACHE_LIB=lib, UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-q", "-x", "-s", "-p", "no:cacheprovider"],
+                       env=env, capture_output=True, text=True, timeout=600, cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    out = r.stdout + r.stderr
+    assert "runtime error" not in out, out[-4000:]
+    assert r.returncode == 0, out[-4000:]
+    assert " passed" in out and "1 skipped" in out
