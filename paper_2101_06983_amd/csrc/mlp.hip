@@ -72,7 +72,36 @@ struct WgradArgs {
 constexpr int WG_M = 64;
 constexpr int WG_KCH = 32, WG_A_LD = WG_M + 8, WG_B_LD = 128 + 8;  // LDS tiles (bf16): [k rows][width + 8], hi then lo part
 
-template <bool A_F32, bool B_F32 = true>
+// raw 8 consecutive elements (one 16-byte load, two for fp32), and their conversion to packed bf16 hi (+ lo) later:
+// between the two a kernel can do other work while the load is in flight
+template <bool F32>
+struct Raw8 { u32x4 v[F32 ? 2 : 1]; };
+template <bool F32>
+__device__ __forceinline__ void fetch8(const void* base, size_t idx, bool live, Raw8<F32>& r) {
+#pragma unroll
+  for (int i = 0; i < (F32 ? 2 : 1); i++) r.v[i] = u32x4{0u, 0u, 0u, 0u};
+  if (!live) return;
+#pragma unroll
+  for (int i = 0; i < (F32 ? 2 : 1); i++) r.v[i] = *(const u32x4*)((const char*)base + idx * (F32 ? 4 : 2) + 16 * i);
+}
+template <bool F32>
+__device__ __forceinline__ void split8(const Raw8<F32>& r, u32x4& hi, u32x4& lo) {
+  if (F32) {
+    typedef __attribute__((ext_vector_type(8))) float f32x8;
+    const f32x4 a = __builtin_bit_cast(f32x4, r.v[0]), b = __builtin_bit_cast(f32x4, r.v[F32 ? 1 : 0]);
+    const f32x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    const bf16x8 h = __builtin_convertvector(v, bf16x8);
+    const f32x8 rest = v - __builtin_convertvector(h, f32x8);
+    hi = __builtin_bit_cast(u32x4, h);
+    lo = __builtin_bit_cast(u32x4, __builtin_convertvector(rest, bf16x8));
+  } else {
+    hi = r.v[0];
+    lo = u32x4{0u, 0u, 0u, 0u};
+  }
+}
+
+// ACCUM: the tile starts from the value of C in HBM (+=); otherwise from zero (C is written, not read)
+template <bool A_F32, bool B_F32 = true, bool ACCUM = true>
 __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, unsigned short* As, unsigned short* Bs) {
   constexpr int KCH = WG_KCH, A_LD = WG_A_LD, B_LD = WG_B_LD;
   constexpr int A_LO = KCH * A_LD, B_LO = KCH * B_LD;
@@ -88,24 +117,38 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       const int m = m0 + 32 * mt + 8 * (r >> 2) + 4 * h + (r & 3);
-      acc[mt][r] = (m < g.M) ? g.C[(size_t)m * g.ldc + n] : 0.f;
+      acc[mt][r] = (ACCUM && m < g.M) ? g.C[(size_t)m * g.ldc + n] : 0.f;
     }
 
+  // the 32 rows of a k-chunk: one 8-element piece of A and two of B per thread, loaded a chunk ahead of their use
+  static_assert(KCH * (WG_M / 8) == 256 && KCH * 16 == 512, "staging pieces per thread");
+  const int ar = tid / (WG_M / 8), ac = tid % (WG_M / 8);
+  Raw8<A_F32> ra;
+  Raw8<B_F32> rb[2];
+  auto fetch = [&](int k0) __attribute__((always_inline)) {
+    fetch8<A_F32>(g.A, (size_t)(k0 + ar) * g.lda + m0 + ac * 8, k0 + ar < g.K, ra);   // A[k][m0 .. m0 + WG_M - 1]
+#pragma unroll
+    for (int i = 0; i < 2; i++) {                                                     // B[k][n0 .. n0 + 127]
+      const int c = tid + 256 * i, r = c / 16, cc = c % 16;
+      fetch8<B_F32>(g.B, (size_t)(k0 + r) * g.ldb + n0 + cc * 8, k0 + r < g.K, rb[i]);
+    }
+  };
+  fetch(0);
   for (int k0 = 0; k0 < g.K; k0 += KCH) {
-    for (int c = tid; c < KCH * (WG_M / 8); c += 256) {   // A[k][m0 .. m0 + WG_M - 1]
-      const int r = c / (WG_M / 8), cc = c % (WG_M / 8);
+    {
       u32x4 vh, vl;
-      load8<A_F32>(g.A, (size_t)(k0 + r) * g.lda + m0 + cc * 8, k0 + r < g.K, vh, vl);
-      *(u32x4*)(As + r * A_LD + cc * 8) = vh;
-      if (A_F32) *(u32x4*)(As + A_LO + r * A_LD + cc * 8) = vl;
+      split8<A_F32>(ra, vh, vl);
+      *(u32x4*)(As + ar * A_LD + ac * 8) = vh;
+      if (A_F32) *(u32x4*)(As + A_LO + ar * A_LD + ac * 8) = vl;
+#pragma unroll
+      for (int i = 0; i < 2; i++) {
+        const int c = tid + 256 * i, r = c / 16, cc = c % 16;
+        split8<B_F32>(rb[i], vh, vl);
+        *(u32x4*)(Bs + r * B_LD + cc * 8) = vh;
+        if (B_F32) *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
+      }
     }
-    for (int c = tid; c < KCH * 16; c += 256) {  // B[k][n0 .. n0 + 127]
-      const int r = c / 16, cc = c % 16;
-      u32x4 vh, vl;
-      load8<B_F32>(g.B, (size_t)(k0 + r) * g.ldb + n0 + cc * 8, k0 + r < g.K, vh, vl);
-      *(u32x4*)(Bs + r * B_LD + cc * 8) = vh;
-      if (B_F32) *(u32x4*)(Bs + B_LO + r * B_LD + cc * 8) = vl;
-    }
+    if (k0 + KCH < g.K) fetch(k0 + KCH);
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < KCH / 16; ks++) {
@@ -165,7 +208,7 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g2, WgradArgs 
 }
 
 // C = A^T B with the rows (K) cut into slices: workgroup (tile, slice) adds its slice's product to partial s of C
-// (g.C + s * M * ldc, zeroed by the caller), which a fixed-order sum combines afterwards.  A bf16.
+// (g.C + s * M * ldc, written whole: one workgroup per tile and slice), which a fixed-order sum combines afterwards.  A bf16.
 template <bool A_F32, bool B_F32>
 __global__ void __launch_bounds__(256) wgrad_splitk_kernel(WgradArgs g, int rows_per_slice) {
   __shared__ __attribute__((aligned(16))) unsigned short As[2 * WG_KCH * WG_A_LD];
@@ -179,12 +222,7 @@ __global__ void __launch_bounds__(256) wgrad_splitk_kernel(WgradArgs g, int rows
   s.K = min(rows_per_slice, g.K - k0);
   s.C = g.C + (size_t)slice * g.M * g.ldc;
   s.colsum = nullptr;
-  wgrad_tile<A_F32, B_F32>(s, tile % nb, tile / nb, As, Bs);
-}
-
-__global__ void __launch_bounds__(256) fill_f32_kernel(float* x, size_t n, float v) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) x[i] = v;
+  wgrad_tile<A_F32, B_F32, false>(s, tile % nb, tile / nb, As, Bs);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -306,6 +344,151 @@ __global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
   } else {
     skinny_tile<A_F32, EP, 4>(g, blockIdx.x, blockIdx.y, red);
   }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// C[M x N] = mul * A[M x K] * Bt[N x K]^T for many rows (the whole batch at once: the projections of the distance
+// function), where the skinny kernel above would stream Bt once per 32 rows.  A workgroup owns a 128 x 128 tile of C,
+// its four waves 64 x 64 each (2 x 2 MFMA tiles 32x32x16); both operands go through LDS in 32-wide k-steps, two
+// buffers, one barrier per step, the loads of the next step in flight during the MFMAs of this one.  An fp32 A is
+// split into hi + lo bf16 planes as everywhere in this file.  Rows of LDS are padded to 80 bytes, which spreads the
+// 16-byte fragment reads of 8 consecutive rows over all banks.
+struct GemmArgs {
+  const void* A; int lda;             // [M][K], bf16 or fp32
+  const unsigned short* Bt; int ldb;  // [N][K] bf16
+  int M, N, K;                        // M may be ragged; N a multiple of 128, K a multiple of 32
+  void* C; int ldc;                   // fp32, or bf16 when the kernel is instantiated with OUT_BF16
+  float mul;
+};
+constexpr int GM_T = 128, GM_BK = 32, GM_LD = GM_BK + 8;
+// BM: rows of the tile, 128 or 64 (wave tiles 64 x 64 or 32 x 64)
+template <bool A_F32, bool OUT_BF16, int BM>
+__global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
+  constexpr int MT = BM / 64;         // 32-row MFMA tiles per wave
+  constexpr int NA = BM / 64;         // staging chunks of A per thread
+  constexpr int AP = A_F32 ? 2 : 1;   // planes of A
+  __shared__ __attribute__((aligned(16))) unsigned short As[2][AP][BM * GM_LD];
+  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][GM_T * GM_LD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
+  const int nbn = g.N / GM_T;
+  const int m0 = (blockIdx.x / nbn) * BM, n0 = (blockIdx.x % nbn) * GM_T;
+  const int wm = wave >> 1, wn = wave & 1;
+  // staging: chunk q = tid + 256 i of a 128 x 32 tile is 8 elements: row q / 4, k 8 (q % 4).  A k-step's MFMAs are far
+  // shorter than a trip to L2, so the loads run three steps ahead, in three register sets used in turn.
+  constexpr int AV = A_F32 ? 2 : 1;   // 16-byte loads per chunk of A
+  struct Regs { u32x4 a[NA][AV]; u32x4 b[2]; };
+  Regs rg[3];
+  auto fetch = [&](Regs& r, int k0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int q = tid + 256 * i, row = q >> 2, kc = q & 3;
+      if (i < NA) {
+        const int am = min(m0 + row, g.M - 1);   // rows past the end repeat the last one; their results are not stored
+        const size_t ia = (size_t)am * g.lda + k0 + 8 * kc;
+#pragma unroll
+        for (int v = 0; v < AV; v++) r.a[i][v] = *(const u32x4*)((const char*)g.A + ia * (A_F32 ? 4 : 2) + 16 * v);
+      }
+      r.b[i] = *(const u32x4*)(g.Bt + (size_t)(n0 + row) * g.ldb + k0 + 8 * kc);
+    }
+  };
+  auto stash = [&](const Regs& r, int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int q = tid + 256 * i, row = q >> 2, kc = q & 3;
+      if (i >= NA) {
+      } else if (A_F32) {
+        typedef __attribute__((ext_vector_type(8))) float f32x8;
+        const f32x4 x0 = __builtin_bit_cast(f32x4, r.a[i][0]), x1 = __builtin_bit_cast(f32x4, r.a[i][AV - 1]);
+        const f32x8 v = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+        const bf16x8 hi = __builtin_convertvector(v, bf16x8);
+        const bf16x8 lo = __builtin_convertvector(v - __builtin_convertvector(hi, f32x8), bf16x8);
+        *(bf16x8*)&As[buf][0][row * GM_LD + 8 * kc] = hi;
+        *(bf16x8*)&As[buf][AP - 1][row * GM_LD + 8 * kc] = lo;
+      } else {
+        *(u32x4*)&As[buf][0][row * GM_LD + 8 * kc] = r.a[i][0];
+      }
+      *(u32x4*)&Bs[buf][row * GM_LD + 8 * kc] = r.b[i];
+    }
+  };
+  f32x16 acc[MT][2];
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
+  const int nk = g.K / GM_BK;
+  // one k-step: the set that held step kt (already in LDS) takes the loads of step kt + 3, the MFMAs of step kt run,
+  // the set of step kt + 1 goes to the other LDS buffer
+  // (STEADY: steps kt + 1 and kt + 3 exist; without branches around the loads the compiler counts them, and its waits
+  // for a set let the loads of the two newer sets stay in flight)
+  auto step = [&](int kt, Regs& mine, const Regs& next, auto steady_tag) __attribute__((always_inline)) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const int buf = kt & 1;
+    if (STEADY || kt + 3 < nk) fetch(mine, (kt + 3) * GM_BK);
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++) {   // 16 of the 32 k each; lane (ln, h): row ln of a fragment, k 16 sub + 8 h ..
+      bf16x8 fa[AP][MT], fb[2];
+#pragma unroll
+      for (int t = 0; t < 2; t++) {
+        const int ra = (wm * 32 * MT + t * 32 + ln) * GM_LD + 16 * sub + 8 * h;
+        const int rb = (wn * 64 + t * 32 + ln) * GM_LD + 16 * sub + 8 * h;
+#pragma unroll
+        for (int pl = 0; pl < AP; pl++)
+          if (t < MT) fa[pl][t] = *(const bf16x8*)&As[buf][pl][ra];
+        fb[t] = *(const bf16x8*)&Bs[buf][rb];
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+          for (int pl = 0; pl < AP; pl++)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[pl][mt], fb[nt], acc[mt][nt], 0, 0, 0);
+    }
+    if (STEADY || kt + 1 < nk) stash(next, buf ^ 1);
+    __syncthreads();
+  };
+  fetch(rg[0], 0);
+  if (nk > 1) fetch(rg[1], GM_BK);
+  if (nk > 2) fetch(rg[2], 2 * GM_BK);
+  stash(rg[0], 0);
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 5 < nk; kt += 3) {
+    step(kt, rg[0], rg[1], std::true_type{});
+    step(kt + 1, rg[1], rg[2], std::true_type{});
+    step(kt + 2, rg[2], rg[0], std::true_type{});
+  }
+  for (; kt < nk; kt += 3) {
+    step(kt, rg[0], rg[1], std::false_type{});
+    if (kt + 1 < nk) step(kt + 1, rg[1], rg[2], std::false_type{});
+    if (kt + 2 < nk) step(kt + 2, rg[2], rg[0], std::false_type{});
+  }
+  // lane (ln, h) holds column ln of each MFMA tile, rows 8 (r / 4) + 4 h + r % 4
+  const float mul = g.mul != 0.f ? g.mul : 1.f;
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int m = m0 + wm * 32 * MT + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+        const int n = n0 + wn * 64 + nt * 32 + ln;
+        if (m < g.M) {
+          const float v = acc[mt][nt][r] * mul;
+          if (OUT_BF16) ((unsigned short*)g.C)[(size_t)m * g.ldc + n] = f2bf(v);
+          else ((float*)g.C)[(size_t)m * g.ldc + n] = v;
+        }
+      }
+}
+template <bool A_F32, bool OUT_BF16>
+static void launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
+  // 64-row tiles while 128-row tiles would leave compute units without one: several small workgroups per unit
+  // then cover each other's barriers and waits
+  const int t128 = ((g.M + 127) / 128) * (g.N / GM_T);
+  if (t128 >= 2 * num_cu()) gemm_nt_kernel<A_F32, OUT_BF16, 128><<<t128, 256, 0, s>>>(g);
+  else gemm_nt_kernel<A_F32, OUT_BF16, 64><<<((g.M + 63) / 64) * (g.N / GM_T), 256, 0, s>>>(g);
 }
 
 // One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
@@ -1044,9 +1227,9 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   // H = F Omega (bf16): Bt[n][k] = Omega[k][n]
   transpose_bf16_kernel<<<dim3(d / 32, d / 32), 256, 0, s>>>((const unsigned short*)omega, d, d, omT);
   {
-    SkinnyArgs g{};
-    g.A = q; g.lda = d; g.Bt = omT; g.ldb = d; g.M = B; g.N = d; g.K = d; g.Cb = H; g.ldc = d;
-    mlp_skinny_kernel<false, EP_PLAIN><<<dim3(d / 32, (B + 31) / 32), 256, 0, s>>>(g);
+    GemmArgs g{};
+    g.A = q; g.lda = d; g.Bt = omT; g.ldb = d; g.M = B; g.N = d; g.K = d; g.C = H; g.ldc = d;
+    launch_gemm_nt<false, true>(g, s);
   }
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
   // loss, A = dL/dH, v = dL/dG
@@ -1054,13 +1237,11 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
                                    ws + w.off_loss, w.loss_bytes, stream);
   if (rc != GC_OK) return rc;
   {  // u = A Omega^T: Bt[n][k] = Omega[n][k]
-    SkinnyArgs g{};
-    g.A = A; g.lda = d; g.Bt = (const unsigned short*)omega; g.ldb = d; g.M = B; g.N = d; g.K = d; g.Cf = u; g.ldc = d;
-    mlp_skinny_kernel<true, EP_PLAIN><<<dim3(d / 32, (B + 31) / 32), 256, 0, s>>>(g);
+    GemmArgs g{};
+    g.A = A; g.lda = d; g.Bt = (const unsigned short*)omega; g.ldb = d; g.M = B; g.N = d; g.K = d; g.C = u; g.ldc = d;
+    launch_gemm_nt<true, false>(g, s);
   }
   {  // dOmega = F^T A, the rows cut into slices, partial sums in a fixed order
-    const size_t n = (size_t)w.slices * d * d;
-    fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, n, 0.f);
     WgradArgs g{};
     g.A = q; g.lda = d; g.B = A; g.ldb = d; g.M = d; g.N = d; g.K = B; g.C = part; g.ldc = d;
     wgrad_splitk_kernel<false, true><<<(d / 128) * (d / WG_M) * w.slices, 256, 0, s>>>(g, w.rows_per_slice);
@@ -1160,8 +1341,6 @@ int gc_deepdist_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   // dL/dA = (dL/da)^T F, dL/dC = (dL/dc)^T G (second equation): rows cut into slices, partial sums in a fixed order
   auto param_grad = [&](const float* grad, const void* x, int rows, int slices, int rps, float* out) {
     float* part = (float*)(ws + pw.off_gpart);
-    const size_t n = (size_t)slices * h * d;
-    fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, n, 0.f);
     WgradArgs k{};
     k.A = grad; k.lda = h; k.B = x; k.ldb = d; k.M = h; k.N = d; k.K = rows; k.C = part; k.ldc = d;
     wgrad_splitk_kernel<true, false><<<(d / 128) * (h / WG_M) * slices, 256, 0, s>>>(k, rps);
