@@ -357,12 +357,15 @@ struct GemmArgs {
   const void* A; int lda;             // [M][K], bf16 or fp32
   const unsigned short* Bt; int ldb;  // [N][K] bf16
   int M, N, K;                        // M may be ragged; N a multiple of 128, K a multiple of 32
-  void* C; int ldc;                   // fp32, or bf16 when the kernel is instantiated with OUT_BF16
-  float mul;
+  void* C; int ldc;                   // fp32 or bf16, see GemmOut
+  float mul;                          // GO_F32 / GO_BF16: factor on the product (0 means 1)
+  const unsigned short* bias;         // GO_GELU_F32 / GO_BIAS_BF16: [N] bf16
 };
+// what a tile writes: the product (times mul) as fp32 or bf16, GELU(product + bias) as fp32, product + bias as bf16
+enum GemmOut { GO_F32 = 0, GO_BF16 = 1, GO_GELU_F32 = 2, GO_BIAS_BF16 = 3 };
 constexpr int GM_T = 128, GM_BK = 32, GM_LD = GM_BK + 8;
 // BM: rows of the tile, 128 or 64 (wave tiles 64 x 64 or 32 x 64)
-template <bool A_F32, bool OUT_BF16, int BM>
+template <bool A_F32, GemmOut OUT, int BM>
 __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
   constexpr int MT = BM / 64;         // 32-row MFMA tiles per wave
   constexpr int NA = BM / 64;         // staging chunks of A per thread
@@ -476,19 +479,21 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
         const int m = m0 + wm * 32 * MT + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
         const int n = n0 + wn * 64 + nt * 32 + ln;
         if (m < g.M) {
-          const float v = acc[mt][nt][r] * mul;
-          if (OUT_BF16) ((unsigned short*)g.C)[(size_t)m * g.ldc + n] = f2bf(v);
-          else ((float*)g.C)[(size_t)m * g.ldc + n] = v;
+          const size_t at = (size_t)m * g.ldc + n;
+          if (OUT == GO_F32) ((float*)g.C)[at] = acc[mt][nt][r] * mul;
+          else if (OUT == GO_BF16) ((unsigned short*)g.C)[at] = f2bf(acc[mt][nt][r] * mul);
+          else if (OUT == GO_GELU_F32) ((float*)g.C)[at] = gelu_f(acc[mt][nt][r] + bf2f(g.bias[n]));
+          else ((unsigned short*)g.C)[at] = f2bf(acc[mt][nt][r] + bf2f(g.bias[n]));
         }
       }
 }
-template <bool A_F32, bool OUT_BF16>
+template <bool A_F32, GemmOut OUT>
 static void launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
   // 64-row tiles while 128-row tiles would leave compute units without one: several small workgroups per unit
   // then cover each other's barriers and waits
   const int t128 = ((g.M + 127) / 128) * (g.N / GM_T);
-  if (t128 >= 2 * num_cu()) gemm_nt_kernel<A_F32, OUT_BF16, 128><<<t128, 256, 0, s>>>(g);
-  else gemm_nt_kernel<A_F32, OUT_BF16, 64><<<((g.M + 63) / 64) * (g.N / GM_T), 256, 0, s>>>(g);
+  if (t128 >= 2 * num_cu()) gemm_nt_kernel<A_F32, OUT, 128><<<t128, 256, 0, s>>>(g);
+  else gemm_nt_kernel<A_F32, OUT, 64><<<((g.M + 63) / 64) * (g.N / GM_T), 256, 0, s>>>(g);
 }
 
 // One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
@@ -610,9 +615,25 @@ static void wgrad_args(const void* x, int rows, const gc_mlp_params* w, const fl
   g1.C = acc->dW1; g1.ldc = w->dh; g1.colsum = nullptr;
 }
 
+constexpr int kGemmRows = 128;   // from this many rows on the graph-less forward runs as tiled GEMMs
 // forward of one sub-batch (after mlp_prepare); keepH: also write the fp32 pre-activations (Step 3)
+// tiled: the graph-less forward of many rows; the caller decides it per input (not per launch), so that a row's bits do
+// not depend on how the rows are cut into launches
 static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, const MlpWs& ws, bool keepH, void* y,
-                              hipStream_t s) {
+                              hipStream_t s, bool tiled = false) {
+  if (tiled && !keepH && y) {
+    // many rows and nothing kept for a backward (Step 1): both layers as tiled GEMMs over all the rows at once, which
+    // read the weights once per 64 or 128 rows instead of once per 32
+    GemmArgs g1{};
+    g1.A = x; g1.lda = w->din; g1.Bt = ws.W1T; g1.ldb = w->din; g1.M = rows; g1.N = w->dh; g1.K = w->din;
+    g1.C = ws.ActF; g1.ldc = w->dh; g1.bias = (const unsigned short*)w->b1;
+    launch_gemm_nt<false, GO_GELU_F32>(g1, s);
+    GemmArgs g2{};
+    g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
+    g2.C = y; g2.ldc = w->dout; g2.bias = (const unsigned short*)w->b2;
+    launch_gemm_nt<true, GO_BIAS_BF16>(g2, s);
+    return hipGetLastError();
+  }
   mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(layer1_args(x, rows, w, ws, keepH));
   if (y) {
     SkinnyArgs g2{};
@@ -652,8 +673,8 @@ static hipError_t mlp_backward(const void* x, int rows, const gc_mlp_params* w, 
 
 // ---- the one-GPU driver of Steps 1-3 -----------------------------------------------------------------------
 // Sub-batches are small, so one of them cannot fill the GPU.  Step 1 keeps nothing but the representations and
-// its rows do not depend on each other, so kGroup consecutive sub-batches go through each launch (the rows
-// come out bit for bit as they do one sub-batch at a time; only transient buffers grow).  In Step 3 the
+// its rows do not depend on each other, so many consecutive sub-batches go through each launch (group_rows; a row's
+// result does not depend on how many rows share the launch; only transient buffers grow).  In Step 3 the
 // accumulation order is fixed (sub-batch order), so it runs as a software pipeline of three stages, one launch
 // (mlp_step3_kernel) per iteration: re-encode of sub-batch c, dH and db1 of c-1, weight gradients of c-2, on three
 // sets of activation buffers.  Everything is enqueued on the caller's stream, in an order that does not depend
@@ -662,9 +683,14 @@ constexpr int kLanes = 3;   // buffer sets = pipeline stages of Step 3
 constexpr int kGroup = 8;   // sub-batches per launch in Step 1
 static std::mutex g_step_mutex;
 
-// rows of kGroup sub-batches of `chunk` rows, at most n
+// rows per launch of Step 1: whole sub-batches, kGroup of them or as many as fit into kStep1Rows rows (enough for the
+// tiled GEMMs of the graph-less forward to fill the GPU), at most n.  Only the transient activation buffer of Step 1
+// grows with it (rows x dh fp32), not what the step keeps.
+constexpr int kStep1Rows = 2048;
 static int group_rows(int chunk, int n) {
-  const long long g = (long long)kGroup * chunk;
+  long long g = (long long)kGroup * chunk;
+  const long long fit = (long long)(kStep1Rows / chunk) * chunk;
+  if (fit > g) g = fit;
   return (int)(g < n ? g : n);
 }
 
@@ -752,15 +778,15 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
   for (int a = 0; a < P; a += chunk_p * g3)
     subs.push_back({(const unsigned short*)x_p + (size_t)a * w->din, P - a < chunk_p * g3 ? P - a : chunk_p * g3, Pm + (size_t)a * w->dout, dP + (size_t)a * w->dout, chunk_p});
   const int nsub = (int)subs.size();
-  // Step 1: graph-less forward, kGroup sub-batches per launch, representations kept
+  // Step 1: graph-less forward, group_rows rows per launch, representations kept
   const int gq = group_rows(chunk_q, B), gp = group_rows(chunk_p, P);
   for (int a = 0; a < B; a += gq) {
     const int rows = B - a < gq ? B - a : gq;
-    if (!ok(mlp_forward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, lane[0], false, Q + (size_t)a * w->dout, s))) return GC_ERR_HIP;
+    if (!ok(mlp_forward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, lane[0], false, Q + (size_t)a * w->dout, s, B >= kGemmRows))) return GC_ERR_HIP;
   }
   for (int a = 0; a < P; a += gp) {
     const int rows = P - a < gp ? P - a : gp;
-    if (!ok(mlp_forward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, lane[0], false, Pm + (size_t)a * w->dout, s))) return GC_ERR_HIP;
+    if (!ok(mlp_forward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, lane[0], false, Pm + (size_t)a * w->dout, s, P >= kGemmRows))) return GC_ERR_HIP;
   }
   // Step 2: loss and the representation gradient cache
   int rc = gc_loss_and_rep_grad_ex(GC_BF16, Q, Pm, pos_idx, B, P, w->dout, scale, temp, 0, loss, dQ, dP, nullptr, nullptr,
@@ -1108,7 +1134,7 @@ int gc_mlp_forward_nograd_bf16(const void* x, int rows, const gc_mlp_params* w, 
     return GC_ERR_WORKSPACE;
   const MlpWs ws = carve_mlp_ws((char*)workspace, rows, w);
   if (mlp_prepare(w, ws, (hipStream_t)stream) != hipSuccess) return GC_ERR_HIP;
-  return mlp_forward(x, rows, w, ws, false, y, (hipStream_t)stream) == hipSuccess ? GC_OK : GC_ERR_HIP;
+  return mlp_forward(x, rows, w, ws, false, y, (hipStream_t)stream, rows >= kGemmRows) == hipSuccess ? GC_OK : GC_ERR_HIP;
 }
 
 int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp_params* w, const float* cached_grad_rows,
@@ -1229,7 +1255,7 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   {
     GemmArgs g{};
     g.A = q; g.lda = d; g.Bt = omT; g.ldb = d; g.M = B; g.N = d; g.K = d; g.C = H; g.ldc = d;
-    launch_gemm_nt<false, true>(g, s);
+    launch_gemm_nt<false, GO_BF16>(g, s);
   }
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
   // loss, A = dL/dH, v = dL/dG
@@ -1239,7 +1265,7 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   {  // u = A Omega^T: Bt[n][k] = Omega[n][k]
     GemmArgs g{};
     g.A = A; g.lda = d; g.Bt = (const unsigned short*)omega; g.ldb = d; g.M = B; g.N = d; g.K = d; g.C = u; g.ldc = d;
-    launch_gemm_nt<true, false>(g, s);
+    launch_gemm_nt<true, GO_F32>(g, s);
   }
   {  // dOmega = F^T A, the rows cut into slices, partial sums in a fixed order
     WgradArgs g{};
