@@ -126,4 +126,17 @@ hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int
                                  int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of = nullptr,
                                  const LossPlan* pl = nullptr, bool out_bf16 = false, const PosFix* fix = nullptr);
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be opted in (hipFuncSetAttribute): once per kernel and
+// device, remembered in `done` (a function-local array of the launcher, one per kernel instantiation).
+inline hipError_t ensure_dyn_lds(const void* fn, int bytes, bool (&done)[64]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done[dev] = true;
+  return e;
+}
+
 }  // namespace gc

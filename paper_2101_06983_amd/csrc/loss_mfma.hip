@@ -318,19 +318,6 @@ __global__ void __launch_bounds__(512) stats_mfma_kernel(const unsigned short* _
   }
 }
 
-// A kernel that uses more than 64 KB of dynamic LDS has to be opted in (hipFuncSetAttribute): once per kernel and
-// device, remembered in `done` (a function-local array of the launcher, one per kernel instantiation).
-static hipError_t ensure_dyn_lds(const void* fn, int bytes, bool (&done)[64]) {
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (done[dev]) return hipSuccess;
-  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) done[dev] = true;
-  return e;
-}
-
 static hipError_t launch_stats128(const LossArgs& a, const LossPlan& pl);
 hipError_t launch_stats_mfma(const LossArgs& a, const LossPlan& pl) {
   if (a.d == 128) return launch_stats128(a, pl);   // whole anchor rows in registers: a kernel of its own

@@ -347,44 +347,44 @@ __global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// C[M x N] = mul * A[M x K] * Bt[N x K]^T for many rows (the whole batch at once: the projections of the distance
-// function), where the skinny kernel above would stream Bt once per 32 rows.  A workgroup owns a 128 x 128 tile of C,
-// its four waves 64 x 64 each (2 x 2 MFMA tiles 32x32x16); both operands go through LDS in 32-wide k-steps, two
-// buffers, one barrier per step, the loads of the next step in flight during the MFMAs of this one.  An fp32 A is
-// split into hi + lo bf16 planes as everywhere in this file.  Rows of LDS are padded to 80 bytes, which spreads the
-// 16-byte fragment reads of 8 consecutive rows over all banks.
+// C[M x N] = A[M x K] * Bt[N x K]^T for many rows (the whole batch at once: the projections of the distance function,
+// the graph-less forward), where the skinny kernel above would stream Bt once per 32 rows.  A workgroup owns a BM x 128
+// tile of C (BM = 128 or 64), its four waves BM/2 x 64 each (MFMA tiles 32x32x16); both operands go through LDS in
+// 64-wide k-steps (whole 128-byte lines of every row), two buffers, one barrier per step; the global loads run two steps
+// ahead in two register sets used in turn.  An fp32 A is split into hi + lo bf16 planes as everywhere in this file.
+// Rows of LDS are padded to 144 bytes, which spreads the 16-byte fragment reads of 8 consecutive rows over all banks.
 struct GemmArgs {
   const void* A; int lda;             // [M][K], bf16 or fp32
   const unsigned short* Bt; int ldb;  // [N][K] bf16
-  int M, N, K;                        // M may be ragged; N a multiple of 128, K a multiple of 32
+  int M, N, K;                        // M may be ragged; N a multiple of 128, K a multiple of 64
   void* C; int ldc;                   // fp32 or bf16, see GemmOut
   float mul;                          // GO_F32 / GO_BF16: factor on the product (0 means 1)
   const unsigned short* bias;         // GO_GELU_F32 / GO_BIAS_BF16: [N] bf16
 };
 // what a tile writes: the product (times mul) as fp32 or bf16, GELU(product + bias) as fp32, product + bias as bf16
 enum GemmOut { GO_F32 = 0, GO_BF16 = 1, GO_GELU_F32 = 2, GO_BIAS_BF16 = 3 };
-constexpr int GM_T = 128, GM_BK = 32, GM_LD = GM_BK + 8;
-// BM: rows of the tile, 128 or 64 (wave tiles 64 x 64 or 32 x 64)
+constexpr int GM_T = 128, GM_BK = 64, GM_LD = GM_BK + 8;
+template <bool A_F32, int BM>
+constexpr int gemm_lds_bytes() { return 2 * ((A_F32 ? 2 : 1) * BM + GM_T) * GM_LD * 2; }
 template <bool A_F32, GemmOut OUT, int BM>
 __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
-  constexpr int MT = BM / 64;         // 32-row MFMA tiles per wave
-  constexpr int NA = BM / 64;         // staging chunks of A per thread
   constexpr int AP = A_F32 ? 2 : 1;   // planes of A
-  __shared__ __attribute__((aligned(16))) unsigned short As[2][AP][BM * GM_LD];
-  __shared__ __attribute__((aligned(16))) unsigned short Bs[2][GM_T * GM_LD];
+  constexpr int MT = BM / 64;         // 32-row MFMA tiles per wave
+  constexpr int NA = BM / 32;         // staging pieces of A per thread (8 elements each); 4 of Bt
+  constexpr int A_PLANE = BM * GM_LD, BUF = (AP * BM + GM_T) * GM_LD;   // elements
+  extern __shared__ __attribute__((aligned(16))) unsigned short gemm_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
   const int nbn = g.N / GM_T;
   const int m0 = (blockIdx.x / nbn) * BM, n0 = (blockIdx.x % nbn) * GM_T;
   const int wm = wave >> 1, wn = wave & 1;
-  // staging: chunk q = tid + 256 i of a 128 x 32 tile is 8 elements: row q / 4, k 8 (q % 4).  A k-step's MFMAs are far
-  // shorter than a trip to L2, so the loads run three steps ahead, in three register sets used in turn.
-  constexpr int AV = A_F32 ? 2 : 1;   // 16-byte loads per chunk of A
-  struct Regs { u32x4 a[NA][AV]; u32x4 b[2]; };
-  Regs rg[3];
+  // staging: piece q = tid + 256 i of a tile is 8 elements: row q / 8, k 8 (q % 8)
+  constexpr int AV = A_F32 ? 2 : 1;   // 16-byte loads per piece of A
+  struct Regs { u32x4 a[NA][AV]; u32x4 b[4]; };
+  Regs rg[2];
   auto fetch = [&](Regs& r, int k0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      const int q = tid + 256 * i, row = q >> 2, kc = q & 3;
+    for (int i = 0; i < 4; i++) {
+      const int q = tid + 256 * i, row = q >> 3, kc = q & 7;
       if (i < NA) {
         const int am = min(m0 + row, g.M - 1);   // rows past the end repeat the last one; their results are not stored
         const size_t ia = (size_t)am * g.lda + k0 + 8 * kc;
@@ -395,22 +395,25 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
     }
   };
   auto stash = [&](const Regs& r, int buf) __attribute__((always_inline)) {
+    unsigned short* As = gemm_lds + buf * BUF;
+    unsigned short* Bs = As + AP * A_PLANE;
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      const int q = tid + 256 * i, row = q >> 2, kc = q & 3;
-      if (i >= NA) {
-      } else if (A_F32) {
-        typedef __attribute__((ext_vector_type(8))) float f32x8;
-        const f32x4 x0 = __builtin_bit_cast(f32x4, r.a[i][0]), x1 = __builtin_bit_cast(f32x4, r.a[i][AV - 1]);
-        const f32x8 v = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-        const bf16x8 hi = __builtin_convertvector(v, bf16x8);
-        const bf16x8 lo = __builtin_convertvector(v - __builtin_convertvector(hi, f32x8), bf16x8);
-        *(bf16x8*)&As[buf][0][row * GM_LD + 8 * kc] = hi;
-        *(bf16x8*)&As[buf][AP - 1][row * GM_LD + 8 * kc] = lo;
-      } else {
-        *(u32x4*)&As[buf][0][row * GM_LD + 8 * kc] = r.a[i][0];
+    for (int i = 0; i < 4; i++) {
+      const int q = tid + 256 * i, row = q >> 3, kc = q & 7;
+      if (i < NA) {
+        if (A_F32) {
+          typedef __attribute__((ext_vector_type(8))) float f32x8;
+          const f32x4 x0 = __builtin_bit_cast(f32x4, r.a[i][0]), x1 = __builtin_bit_cast(f32x4, r.a[i][AV - 1]);
+          const f32x8 v = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+          const bf16x8 hi = __builtin_convertvector(v, bf16x8);
+          const bf16x8 lo = __builtin_convertvector(v - __builtin_convertvector(hi, f32x8), bf16x8);
+          *(bf16x8*)&As[row * GM_LD + 8 * kc] = hi;
+          *(bf16x8*)&As[(AP - 1) * A_PLANE + row * GM_LD + 8 * kc] = lo;
+        } else {
+          *(u32x4*)&As[row * GM_LD + 8 * kc] = r.a[i][0];
+        }
       }
-      *(u32x4*)&Bs[buf][row * GM_LD + 8 * kc] = r.b[i];
+      *(u32x4*)&Bs[row * GM_LD + 8 * kc] = r.b[i];
     }
   };
   f32x16 acc[MT][2];
@@ -421,16 +424,17 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
   const int nk = g.K / GM_BK;
-  // one k-step: the set that held step kt (already in LDS) takes the loads of step kt + 3, the MFMAs of step kt run,
-  // the set of step kt + 1 goes to the other LDS buffer
-  // (STEADY: steps kt + 1 and kt + 3 exist; without branches around the loads the compiler counts them, and its waits
-  // for a set let the loads of the two newer sets stay in flight)
+  // one k-step: the set that held step kt (already in LDS) takes the loads of step kt + 2, the MFMAs of step kt run,
+  // the set of step kt + 1 goes to the other LDS buffer.  (STEADY: steps kt + 1 and kt + 2 exist; without branches
+  // around the loads the compiler counts them, and its waits for a set let the loads of the newer set stay in flight.)
   auto step = [&](int kt, Regs& mine, const Regs& next, auto steady_tag) __attribute__((always_inline)) {
     constexpr bool STEADY = decltype(steady_tag)::value;
     const int buf = kt & 1;
-    if (STEADY || kt + 3 < nk) fetch(mine, (kt + 3) * GM_BK);
+    const unsigned short* As = gemm_lds + buf * BUF;
+    const unsigned short* Bs = As + AP * A_PLANE;
+    if (STEADY || kt + 2 < nk) fetch(mine, (kt + 2) * GM_BK);
 #pragma unroll
-    for (int sub = 0; sub < 2; sub++) {   // 16 of the 32 k each; lane (ln, h): row ln of a fragment, k 16 sub + 8 h ..
+    for (int sub = 0; sub < GM_BK / 16; sub++) {   // 16 k each; lane (ln, h): row ln of a fragment, k 16 sub + 8 h ..
       bf16x8 fa[AP][MT], fb[2];
 #pragma unroll
       for (int t = 0; t < 2; t++) {
@@ -438,8 +442,8 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
         const int rb = (wn * 64 + t * 32 + ln) * GM_LD + 16 * sub + 8 * h;
 #pragma unroll
         for (int pl = 0; pl < AP; pl++)
-          if (t < MT) fa[pl][t] = *(const bf16x8*)&As[buf][pl][ra];
-        fb[t] = *(const bf16x8*)&Bs[buf][rb];
+          if (t < MT) fa[pl][t] = *(const bf16x8*)&As[pl * A_PLANE + ra];
+        fb[t] = *(const bf16x8*)&Bs[rb];
       }
 #pragma unroll
       for (int mt = 0; mt < MT; mt++)
@@ -454,19 +458,16 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
   };
   fetch(rg[0], 0);
   if (nk > 1) fetch(rg[1], GM_BK);
-  if (nk > 2) fetch(rg[2], 2 * GM_BK);
   stash(rg[0], 0);
   __syncthreads();
   int kt = 0;
-  for (; kt + 5 < nk; kt += 3) {
+  for (; kt + 3 < nk; kt += 2) {
     step(kt, rg[0], rg[1], std::true_type{});
-    step(kt + 1, rg[1], rg[2], std::true_type{});
-    step(kt + 2, rg[2], rg[0], std::true_type{});
+    step(kt + 1, rg[1], rg[0], std::true_type{});
   }
-  for (; kt < nk; kt += 3) {
+  for (; kt < nk; kt += 2) {
     step(kt, rg[0], rg[1], std::false_type{});
-    if (kt + 1 < nk) step(kt + 1, rg[1], rg[2], std::false_type{});
-    if (kt + 2 < nk) step(kt + 2, rg[2], rg[0], std::false_type{});
+    if (kt + 1 < nk) step(kt + 1, rg[1], rg[0], std::false_type{});
   }
   // lane (ln, h) holds column ln of each MFMA tile, rows 8 (r / 4) + 4 h + r % 4
   const float mul = g.mul != 0.f ? g.mul : 1.f;
@@ -488,12 +489,23 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
       }
 }
 template <bool A_F32, GemmOut OUT>
-static void launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
+static hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
+  if (g.M < 1 || g.N % GM_T || g.K % GM_BK || g.K < GM_BK) return hipErrorInvalidValue;
   // 64-row tiles while 128-row tiles would leave compute units without one: several small workgroups per unit
   // then cover each other's barriers and waits
   const int t128 = ((g.M + 127) / 128) * (g.N / GM_T);
-  if (t128 >= 2 * num_cu()) gemm_nt_kernel<A_F32, OUT, 128><<<t128, 256, 0, s>>>(g);
-  else gemm_nt_kernel<A_F32, OUT, 64><<<((g.M + 63) / 64) * (g.N / GM_T), 256, 0, s>>>(g);
+  if (t128 >= 2 * num_cu()) {
+    static bool done[64];
+    constexpr int lds = gemm_lds_bytes<A_F32, 128>();
+    if (hipError_t e = ensure_dyn_lds((const void*)gemm_nt_kernel<A_F32, OUT, 128>, lds, done); e != hipSuccess) return e;
+    gemm_nt_kernel<A_F32, OUT, 128><<<t128, 256, lds, s>>>(g);
+  } else {
+    static bool done[64];
+    constexpr int lds = gemm_lds_bytes<A_F32, 64>();
+    if (hipError_t e = ensure_dyn_lds((const void*)gemm_nt_kernel<A_F32, OUT, 64>, lds, done); e != hipSuccess) return e;
+    gemm_nt_kernel<A_F32, OUT, 64><<<((g.M + 63) / 64) * (g.N / GM_T), 256, lds, s>>>(g);
+  }
+  return hipGetLastError();
 }
 
 // One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
@@ -627,12 +639,11 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
     GemmArgs g1{};
     g1.A = x; g1.lda = w->din; g1.Bt = ws.W1T; g1.ldb = w->din; g1.M = rows; g1.N = w->dh; g1.K = w->din;
     g1.C = ws.ActF; g1.ldc = w->dh; g1.bias = (const unsigned short*)w->b1;
-    launch_gemm_nt<false, GO_GELU_F32>(g1, s);
+    if (hipError_t e = launch_gemm_nt<false, GO_GELU_F32>(g1, s); e != hipSuccess) return e;
     GemmArgs g2{};
     g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
     g2.C = y; g2.ldc = w->dout; g2.bias = (const unsigned short*)w->b2;
-    launch_gemm_nt<true, GO_BIAS_BF16>(g2, s);
-    return hipGetLastError();
+    return launch_gemm_nt<true, GO_BIAS_BF16>(g2, s);
   }
   mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(layer1_args(x, rows, w, ws, keepH));
   if (y) {
@@ -1255,7 +1266,7 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   {
     GemmArgs g{};
     g.A = q; g.lda = d; g.Bt = omT; g.ldb = d; g.M = B; g.N = d; g.K = d; g.C = H; g.ldc = d;
-    launch_gemm_nt<false, GO_BF16>(g, s);
+    if (launch_gemm_nt<false, GO_BF16>(g, s) != hipSuccess) return GC_ERR_HIP;
   }
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
   // loss, A = dL/dH, v = dL/dG
@@ -1265,7 +1276,7 @@ int gc_bilinear_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   {  // u = A Omega^T: Bt[n][k] = Omega[n][k]
     GemmArgs g{};
     g.A = A; g.lda = d; g.Bt = (const unsigned short*)omega; g.ldb = d; g.M = B; g.N = d; g.K = d; g.C = u; g.ldc = d;
-    launch_gemm_nt<true, GO_F32>(g, s);
+    if (launch_gemm_nt<true, GO_F32>(g, s) != hipSuccess) return GC_ERR_HIP;
   }
   {  // dOmega = F^T A, the rows cut into slices, partial sums in a fixed order
     WgradArgs g{};
