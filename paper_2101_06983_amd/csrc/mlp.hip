@@ -182,10 +182,19 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs& g, int bx, int by, u
     }
   if (g.colsum && by == 0 && tid < 128) {
     const int step = g.colsum_rows > 0 ? g.colsum_rows : g.K;
+    const float* col = (const float*)g.B + n0 + tid;   // (fp32 B only)
     float total = g.colsum[n0 + tid];
     for (int k0 = 0; k0 < g.K; k0 += step) {
+      const int k1 = min(g.K, k0 + step);
       float s = 0.f;
-      for (int k = k0; k < min(g.K, k0 + step); k++) s += ((const float*)g.B)[(size_t)k * g.ldb + n0 + tid];   // (fp32 B only)
+      for (int k = k0; k < k1; k += 8) {   // eight loads in flight, added in row order
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = (k + j < k1) ? col[(size_t)(k + j) * g.ldb] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+          if (k + j < k1) s += v[j];
+      }
       total += s;
     }
     g.colsum[n0 + tid] = total;
@@ -235,7 +244,6 @@ struct SkinnyArgs {
   float* ActF;                       // EP_GELU: fp32 activation out (ldh)
   unsigned short* Cb; int ldc;       // EP_BIAS: bf16 output; EP_PLAIN: bf16 output if set
   float* Cf;                         // EP_DH: dH out (fp32, ldc); EP_PLAIN: fp32 output if Cb is not set
-  float* colsum;                     // EP_DH: db1 [N] += column sums (one m-tile per launch: single writer)
   float plain_mul;                   // EP_PLAIN: factor on the product (0 means 1)
 };
 
@@ -297,7 +305,6 @@ __device__ __forceinline__ void skinny_tile(const SkinnyArgs& g, int bx, int by,
   for (int r = 0; r < 16; r++) red[wave][8 * (r >> 2) + 4 * h + (r & 3)][ln] = acc[r];
   __syncthreads();
   const int en = tid & 31, n = n0 + en;
-  float colv = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int em = (tid >> 5) + 8 * i, mm = m0 + em;
@@ -315,35 +322,18 @@ __device__ __forceinline__ void skinny_tile(const SkinnyArgs& g, int bx, int by,
         if (g.Cb) g.Cb[(size_t)mm * g.ldc + n] = f2bf(sum);
         else g.Cf[(size_t)mm * g.ldc + n] = g.plain_mul != 0.f ? sum * g.plain_mul : sum;
       }
-    } else {  // EP_DH
-      float v = 0.f;
-      if (mm < g.M) {
-        v = sum * gelu_prime_f(g.H[(size_t)mm * g.ldh + n]);
-        g.Cf[(size_t)mm * g.ldc + n] = v;
-      }
-      red[0][em][en] = v;  // own element only: nobody else reads it before the barrier below
-    }
-  }
-  if (EP == EP_DH) {
-    __syncthreads();
-    if (tid < 32) {
-      for (int em = 0; em < 32; em++) colv += red[0][em][tid];
-      g.colsum[n0 + tid] += colv;
+    } else {  // EP_DH (the column sums of dH, db1, are formed by the weight-gradient kernel that reads dH next)
+      if (mm < g.M) g.Cf[(size_t)mm * g.ldc + n] = sum * gelu_prime_f(g.H[(size_t)mm * g.ldh + n]);
     }
   }
   __syncthreads();  // red may be reused by the caller's next tile
 }
 
-// grid (N / 32, m-tiles); EP_DH: grid (N / 32, 1), the workgroup walks the m-tiles itself so that each column
-// sum has one writer
+// grid (N / 32, m-tiles)
 template <bool A_F32, Epilogue EP>
 __global__ void __launch_bounds__(256) mlp_skinny_kernel(SkinnyArgs g) {
   __shared__ float red[4][32][33];
-  if (EP == EP_DH) {
-    for (int by = 0; by * 32 < g.M; by++) skinny_tile<A_F32, EP, 4>(g, blockIdx.x, by, red);
-  } else {
-    skinny_tile<A_F32, EP, 4>(g, blockIdx.x, blockIdx.y, red);
-  }
+  skinny_tile<A_F32, EP, 4>(g, blockIdx.x, blockIdx.y, red);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -527,7 +517,8 @@ __global__ void __launch_bounds__(256, 3) mlp_step3_kernel(Step3Args a) {
   // fill in behind them (1.16 -> 1.08 ms per step at config 5 against the other order)
   SkinnyRed* red = (SkinnyRed*)lds;
   if (id < a.n_dh) {
-    for (int by = 0; by * 32 < a.dh.M; by++) skinny_tile<true, EP_DH, 2>(a.dh, id, by, red);
+    const int nb = a.dh.N / 32;
+    skinny_tile<true, EP_DH, 2>(a.dh, id % nb, id / nb, red);
     return;
   }
   id -= a.n_dh;
@@ -614,7 +605,7 @@ static SkinnyArgs layer1_args(const void* x, int rows, const gc_mlp_params* w, c
 static SkinnyArgs dh_args(int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc, const MlpWs& ws) {
   SkinnyArgs g{};
   g.A = u; g.lda = w->dout; g.Bt = (const unsigned short*)w->W2; g.ldb = w->dout; g.M = rows; g.N = w->dh; g.K = w->dout;
-  g.H = ws.H; g.ldh = w->dh; g.Cf = ws.dH; g.ldc = w->dh; g.colsum = acc->db1;
+  g.H = ws.H; g.ldh = w->dh; g.Cf = ws.dH; g.ldc = w->dh;
   return g;
 }
 // dW2 += Act^T U, db2 += column sums of U (g2);  dW1 += X^T dH (g1)
@@ -624,7 +615,7 @@ static void wgrad_args(const void* x, int rows, const gc_mlp_params* w, const fl
   g2.A = ws.ActF; g2.lda = w->dh; g2.B = u; g2.ldb = w->dout; g2.M = w->dh; g2.N = w->dout; g2.K = rows;
   g2.C = acc->dW2; g2.ldc = w->dout; g2.colsum = acc->db2;
   g1.A = x; g1.lda = w->din; g1.B = ws.dH; g1.ldb = w->dh; g1.M = w->din; g1.N = w->dh; g1.K = rows;
-  g1.C = acc->dW1; g1.ldc = w->dh; g1.colsum = nullptr;
+  g1.C = acc->dW1; g1.ldc = w->dh; g1.colsum = acc->db1; g1.colsum_rows = 32;   // db1: 32-row tiles of dH, in order
 }
 
 constexpr int kGemmRows = 128;   // from this many rows on the graph-less forward runs as tiled GEMMs
@@ -659,7 +650,7 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
 // keepH, (2) dH and db1, (3) the weight gradients
 static hipError_t mlp_backward_dh(int rows, const gc_mlp_params* w, const float* u, const gc_mlp_grads* acc,
                                   const MlpWs& ws, hipStream_t s) {
-  mlp_skinny_kernel<true, EP_DH><<<dim3(w->dh / 32, 1), 256, 0, s>>>(dh_args(rows, w, u, acc, ws));
+  mlp_skinny_kernel<true, EP_DH><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(dh_args(rows, w, u, acc, ws));
   return hipGetLastError();
 }
 
@@ -816,7 +807,7 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
     if (i >= 1 && i - 1 < nsub) {      // dH, db1 of sub-batch i-1
       const Sub& sb = subs[i - 1];
       a3.dh = dh_args(sb.rows, w, sb.u, grads, lane[(i - 1) % kLanes]);
-      a3.n_dh = w->dh / 32;
+      a3.n_dh = (w->dh / 32) * ((sb.rows + 31) / 32);
     }
     if (i < nsub) {                    // re-encode of sub-batch i, keeping H and Act
       const Sub& sb = subs[i];
