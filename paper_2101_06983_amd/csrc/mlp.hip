@@ -350,6 +350,8 @@ struct GemmArgs {
   void* C; int ldc;                   // fp32 or bf16, see GemmOut
   float mul;                          // GO_F32 / GO_BF16: factor on the product (0 means 1)
   const unsigned short* bias;         // GO_GELU_F32 / GO_BIAS_BF16: [N] bf16
+  int k_split;                        // GO_F32 only: > 1 cuts K into that many equal ranges (each a multiple of 64); range s
+  size_t split_stride;                //   writes its partial product to C + s * split_stride (elements)
 };
 // what a tile writes: the product (times mul) as fp32 or bf16, GELU(product + bias) as fp32, product + bias as bf16
 enum GemmOut { GO_F32 = 0, GO_BF16 = 1, GO_GELU_F32 = 2, GO_BIAS_BF16 = 3 };
@@ -365,7 +367,10 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned short gemm_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
   const int nbn = g.N / GM_T;
-  const int m0 = (blockIdx.x / nbn) * BM, n0 = (blockIdx.x % nbn) * GM_T;
+  const int tiles = ((g.M + BM - 1) / BM) * nbn;
+  const int tile = blockIdx.x % tiles, split = blockIdx.x / tiles;   // split > 0 only for GO_F32 with k_split > 1
+  const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * GM_T;
+  const int klen = g.K / (g.k_split > 1 ? g.k_split : 1), kbeg = split * klen;
   const int wm = wave >> 1, wn = wave & 1;
   // staging: piece q = tid + 256 i of a tile is 8 elements: row q / 8, k 8 (q % 8)
   constexpr int AV = A_F32 ? 2 : 1;   // 16-byte loads per piece of A
@@ -377,11 +382,11 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
       const int q = tid + 256 * i, row = q >> 3, kc = q & 7;
       if (i < NA) {
         const int am = min(m0 + row, g.M - 1);   // rows past the end repeat the last one; their results are not stored
-        const size_t ia = (size_t)am * g.lda + k0 + 8 * kc;
+        const size_t ia = (size_t)am * g.lda + kbeg + k0 + 8 * kc;
 #pragma unroll
         for (int v = 0; v < AV; v++) r.a[i][v] = *(const u32x4*)((const char*)g.A + ia * (A_F32 ? 4 : 2) + 16 * v);
       }
-      r.b[i] = *(const u32x4*)(g.Bt + (size_t)(n0 + row) * g.ldb + k0 + 8 * kc);
+      r.b[i] = *(const u32x4*)(g.Bt + (size_t)(n0 + row) * g.ldb + kbeg + k0 + 8 * kc);
     }
   };
   auto stash = [&](const Regs& r, int buf) __attribute__((always_inline)) {
@@ -413,7 +418,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
     for (int nt = 0; nt < 2; nt++)
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[mt][nt][r] = 0.f;
-  const int nk = g.K / GM_BK;
+  const int nk = klen / GM_BK;
   // one k-step: the set that held step kt (already in LDS) takes the loads of step kt + 2, the MFMAs of step kt run,
   // the set of step kt + 1 goes to the other LDS buffer.  (STEADY: steps kt + 1 and kt + 2 exist; without branches
   // around the loads the compiler counts them, and its waits for a set let the loads of the newer set stay in flight.)
@@ -471,7 +476,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
         const int n = n0 + wn * 64 + nt * 32 + ln;
         if (m < g.M) {
           const size_t at = (size_t)m * g.ldc + n;
-          if (OUT == GO_F32) ((float*)g.C)[at] = acc[mt][nt][r] * mul;
+          if (OUT == GO_F32) ((float*)g.C)[(size_t)split * g.split_stride + at] = acc[mt][nt][r] * mul;
           else if (OUT == GO_BF16) ((unsigned short*)g.C)[at] = f2bf(acc[mt][nt][r] * mul);
           else if (OUT == GO_GELU_F32) ((float*)g.C)[at] = gelu_f(acc[mt][nt][r] + bf2f(g.bias[n]));
           else ((unsigned short*)g.C)[at] = f2bf(acc[mt][nt][r] + bf2f(g.bias[n]));
@@ -480,22 +485,39 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
 }
 template <bool A_F32, GemmOut OUT>
 static hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
-  if (g.M < 1 || g.N % GM_T || g.K % GM_BK || g.K < GM_BK) return hipErrorInvalidValue;
+  const int ks = g.k_split > 1 ? g.k_split : 1;
+  if (g.M < 1 || g.N % GM_T || g.K % (GM_BK * ks) || g.K < GM_BK * ks || (ks > 1 && OUT != GO_F32)) return hipErrorInvalidValue;
   // 64-row tiles while 128-row tiles would leave compute units without one: several small workgroups per unit
   // then cover each other's barriers and waits
   const int t128 = ((g.M + 127) / 128) * (g.N / GM_T);
-  if (t128 >= 2 * num_cu()) {
+  if (t128 * ks >= 2 * num_cu()) {
     static bool done[64];
     constexpr int lds = gemm_lds_bytes<A_F32, 128>();
     if (hipError_t e = ensure_dyn_lds((const void*)gemm_nt_kernel<A_F32, OUT, 128>, lds, done); e != hipSuccess) return e;
-    gemm_nt_kernel<A_F32, OUT, 128><<<t128, 256, lds, s>>>(g);
+    gemm_nt_kernel<A_F32, OUT, 128><<<t128 * ks, 256, lds, s>>>(g);
   } else {
     static bool done[64];
     constexpr int lds = gemm_lds_bytes<A_F32, 64>();
     if (hipError_t e = ensure_dyn_lds((const void*)gemm_nt_kernel<A_F32, OUT, 64>, lds, done); e != hipSuccess) return e;
-    gemm_nt_kernel<A_F32, OUT, 64><<<((g.M + 63) / 64) * (g.N / GM_T), 256, lds, s>>>(g);
+    gemm_nt_kernel<A_F32, OUT, 64><<<((g.M + 63) / 64) * (g.N / GM_T) * ks, 256, lds, s>>>(g);
   }
   return hipGetLastError();
+}
+
+// out[m][n] = bf16(sum over the k_split partial products, in index order, + bias[n]); 4 elements per thread
+__global__ void __launch_bounds__(256) splitk_bias_bf16_kernel(const float* __restrict__ part, int k_split, size_t stride,
+                                                              const unsigned short* __restrict__ bias, int N,
+                                                              unsigned short* __restrict__ out, size_t n4) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= n4) return;
+  f32x4 acc = ((const f32x4*)part)[e];
+  for (int s = 1; s < k_split; s++) acc += ((const f32x4*)(part + (size_t)s * stride))[e];
+  const int n = (int)((e * 4) % (size_t)N);
+  const s16x4 b = *(const s16x4*)(bias + n);
+  s16x4 o;
+#pragma unroll
+  for (int k = 0; k < 4; k++) o[k] = (short)f2bf(acc[k] + bf2f((unsigned short)b[k]));
+  ((s16x4*)out)[e] = o;
 }
 
 // One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
@@ -619,6 +641,7 @@ static void wgrad_args(const void* x, int rows, const gc_mlp_params* w, const fl
 }
 
 constexpr int kGemmRows = 128;   // from this many rows on the graph-less forward runs as tiled GEMMs
+constexpr int kStep1Rows = 2048;  // rows per launch of Step 1 (see group_rows)
 // forward of one sub-batch (after mlp_prepare); keepH: also write the fp32 pre-activations (Step 3)
 // tiled: the graph-less forward of many rows; the caller decides it per input (not per launch), so that a row's bits do
 // not depend on how the rows are cut into launches
@@ -634,7 +657,20 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
     GemmArgs g2{};
     g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
     g2.C = y; g2.ldc = w->dout; g2.bias = (const unsigned short*)w->b2;
-    return launch_gemm_nt<true, GO_BIAS_BF16>(g2, s);
+    // The second layer is narrow (dout columns) and long (dh): few tiles, each a long chain of k-steps.  While the tiles
+    // do not fill the GPU, the contraction is cut into up to four ranges whose fp32 partial products go to the dH
+    // buffer (unused by a graph-less forward; rows x dh floats hold dh / dout partial outputs) and are summed, in
+    // index order, by a kernel that adds the bias.  The split depends on the shape only, not on the rows of a launch.
+    int ks = 1;
+    const int tiles64 = ((kStep1Rows + 63) / 64) * (w->dout / GM_T);   // tiles of a full Step-1 launch
+    while (ks < 4 && tiles64 * ks < 2 * num_cu() && (ks * 2) * w->dout <= w->dh && w->dh % (GM_BK * ks * 2) == 0) ks *= 2;
+    if (ks == 1) return launch_gemm_nt<true, GO_BIAS_BF16>(g2, s);
+    g2.C = ws.dH; g2.bias = nullptr; g2.k_split = ks; g2.split_stride = (size_t)rows * w->dout;
+    if (hipError_t e = launch_gemm_nt<true, GO_F32>(g2, s); e != hipSuccess) return e;
+    const size_t n4 = (size_t)rows * w->dout / 4;
+    splitk_bias_bf16_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, s>>>(ws.dH, ks, g2.split_stride, (const unsigned short*)w->b2,
+                                                                      w->dout, (unsigned short*)y, n4);
+    return hipGetLastError();
   }
   mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(layer1_args(x, rows, w, ws, keepH));
   if (y) {
@@ -687,8 +723,7 @@ static std::mutex g_step_mutex;
 
 // rows per launch of Step 1: whole sub-batches, kGroup of them or as many as fit into kStep1Rows rows (enough for the
 // tiled GEMMs of the graph-less forward to fill the GPU), at most n.  Only the transient activation buffer of Step 1
-// grows with it (rows x dh fp32), not what the step keeps.
-constexpr int kStep1Rows = 2048;
+// grows with it (rows x dh fp32), not what the step keeps.  (kStep1Rows is defined with the forward above.)
 static int group_rows(int chunk, int n) {
   long long g = (long long)kGroup * chunk;
   const long long fit = (long long)(kStep1Rows / chunk) * chunk;

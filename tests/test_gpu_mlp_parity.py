@@ -62,13 +62,15 @@ def small_problem(B=48, P=96, din=128, dh=256, dout=128, seed=9):
     return synth.mlp_problem(B, P, din, dh, dout, seed=synth.SEED0 + seed)
 
 
-@pytest.mark.parametrize("rows", [1, 32, 40, 100])
-def test_forward_nograd(rows):
-    xq, _, _, params = small_problem(B=rows)
+# (from 128 rows on the forward runs as tiled GEMMs: whole tiles, ragged last tiles, one- and two-step contractions)
+@pytest.mark.parametrize("rows,din,dh", [(1, 128, 256), (32, 128, 256), (40, 128, 256), (100, 128, 256), (128, 128, 256),
+                                         (200, 128, 256), (1000, 128, 256), (130, 64, 128), (333, 192, 384)])
+def test_forward_nograd(rows, din, dh):
+    xq, _, _, params = small_problem(B=rows, din=din, dh=dh)
     want = O.mlp_forward(synth.widen(xq), widen_params(params))
     y = gc.gc_mlp_forward_nograd_bf16(xq.to(DEV), dev_params(params))
     torch.cuda.synchronize()
-    check("forward rows=%d" % rows, relerr(to_np(y), want), TOL_STORED)
+    check("forward rows=%d din=%d dh=%d" % (rows, din, dh), relerr(to_np(y), want), TOL_STORED)
 
 
 @pytest.mark.parametrize("rows", [1, 16, 32, 45])
