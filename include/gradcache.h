@@ -19,9 +19,13 @@
  *     with hipMalloc on first use and grows on demand (growing frees the old
  *     buffer with hipFree, which waits for the device; while `stream` is being
  *     captured into a graph a call that would have to grow it returns
- *     GC_ERR_UNSUPPORTED instead).  Two such calls that overlap in time on one
- *     device race on it - use the *_ex forms with your own workspace for that,
- *     or gc_loss_and_rep_grad_bf16_static where nothing may be allocated.
+ *     GC_ERR_UNSUPPORTED instead).  Such calls share the buffer, so the library
+ *     puts them in order: a call made on another stream than the previous one
+ *     first waits (on the GPU, through an event) for that one's kernels.  Calls
+ *     made while their stream is being captured are not ordered this way and
+ *     must not overlap with other calls.  To run calls side by side use the
+ *     *_ex forms with a workspace each, or gc_loss_and_rep_grad_bf16_static
+ *     where nothing may be allocated.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  A
  *     call only enqueues work and returns; outputs are valid once the stream
  *     has been synchronised.  No call synchronises the device, except

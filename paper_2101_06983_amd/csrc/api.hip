@@ -158,6 +158,38 @@ static int own_workspace(size_t need, hipStream_t stream, void** out) {
   return GC_OK;
 }
 
+// Calls that share the library's buffer from different streams are put in order: each call leaves an event behind
+// its last kernel, and a call on another stream waits for it first.  (Not while a stream is being captured: an
+// event of ordinary work cannot be waited for inside a capture; a captured call must not overlap with other calls
+// on the buffer.)
+static hipEvent_t g_ws_done[64];
+static hipStream_t g_ws_last[64];
+static bool g_ws_used[64];
+static bool is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cap) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return cap != hipStreamCaptureStatusNone;
+}
+static int own_workspace_enter(hipStream_t stream) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+  if (is_capturing(stream)) return GC_OK;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  if (g_ws_used[dev] && g_ws_last[dev] != stream && hipStreamWaitEvent(stream, g_ws_done[dev], 0) != hipSuccess) return GC_ERR_HIP;
+  return GC_OK;
+}
+static int own_workspace_leave(hipStream_t stream) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return GC_ERR_HIP;
+  if (is_capturing(stream)) return GC_OK;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  if (!g_ws_done[dev] && hipEventCreateWithFlags(&g_ws_done[dev], hipEventDisableTiming) != hipSuccess) return GC_ERR_HIP;
+  if (hipEventRecord(g_ws_done[dev], stream) != hipSuccess) return GC_ERR_HIP;
+  g_ws_last[dev] = stream;
+  g_ws_used[dev] = true;
+  return GC_OK;
+}
+
 // ---- the workspace of the entry point that allocates nothing: a fixed array in the device image ---------------
 // One copy per GPU, at an address of its own.  Host code never uses the array's name as an address (on the host
 // it is only a handle for the lookup): the address is asked for once per device, with that device current, and
@@ -330,8 +362,11 @@ static int simple_loss(gc_dtype dt, const void* q, const void* p, const int32_t*
   void* ws = nullptr;
   rc = own_workspace(need, (hipStream_t)stream, &ws);
   if (rc != GC_OK) return rc;
-  return gc_loss_and_rep_grad_ex(dt, q, p, pos_idx, B, P, d, scale, temp, 0, loss, dq, dp, nullptr, nullptr, ws, need,
-                                 stream);
+  rc = own_workspace_enter((hipStream_t)stream);
+  if (rc != GC_OK) return rc;
+  rc = gc_loss_and_rep_grad_ex(dt, q, p, pos_idx, B, P, d, scale, temp, 0, loss, dq, dp, nullptr, nullptr, ws, need, stream);
+  const int rc2 = own_workspace_leave((hipStream_t)stream);   // also after a failed launch: some kernels may be queued
+  return rc != GC_OK ? rc : rc2;
 }
 
 int gc_loss_and_rep_grad_bf16(const void* q, const void* p, const int32_t* pos_idx, int B, int P, int d, float scale,

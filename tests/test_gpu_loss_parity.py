@@ -249,6 +249,24 @@ def test_optional_outputs_and_reuse_of_workspace():
     assert torch.equal(only_dq["dq"], full["dq"]) and only_dq["loss"].item() == full["loss"].item()
 
 
+def test_calls_on_two_streams_that_share_the_library_buffer_are_ordered():
+    # the entry points without a workspace argument share one buffer per device; calls on different streams are put in
+    # order by the library (an event behind each call), so each still gets its own result
+    cases = []
+    for k in range(6):
+        q, p, r = synth.dpr_batch(512 + 64 * k, 1024, 256, seed=9100 + k)
+        cases.append((q.to(DEV), p.to(DEV), r.to(DEV)))
+    want = [gc.gc_loss_and_rep_grad_ex(q, p, r, want=("loss", "dq", "dp")) for q, p, r in cases]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = [gc.gc_loss_and_rep_grad_bf16(q, p, r, stream=streams[k % 2]) for k, (q, p, r) in enumerate(cases)]
+    torch.cuda.synchronize()
+    assert gc.gc_check_async_error(None) == gc.GC_OK
+    for k, ((loss, dq, dp), w) in enumerate(zip(got, want)):
+        assert loss.item() == w["loss"].item(), k
+        assert torch.equal(dq, w["dq"]) and torch.equal(dp, w["dp"]), k
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_pos_idx_out_of_range_is_reported_not_faulted(path):
     q, p, r = synth.config2()
