@@ -112,14 +112,14 @@ def side_workload(args, gc, synth, dev):
         qd, pd, rd = q.to(dev), p.to(dev), r.to(dev)
         res = gc.gc_deepdist_loss_and_grads_bf16(qd, pd, rd, om, 1.0, 0.5)
         step = lambda: gc.gc_deepdist_loss_and_grads_bf16(qd, pd, rd, om, 1.0, 0.5, workspace=res["workspace"], out=res)
-        # vector arithmetic of the three walks over the B*P*h (pair, k) terms: add, exp2, add, reciprocal, fma in each
-        # (6 flop, an fma counted as 2), plus 3 fma in the anchor-owner gradient walk and 2 in the target-owner one
-        flops = float(B) * P * h * (6 + 12 + 10)
+        # vector arithmetic of the two walks over the B*P*h (pair, k) terms: add, exp2, add, reciprocal, fma in each
+        # (6 flop, an fma counted as 2), plus 3 fma in the anchor-owner walk and 2 in the target-owner one
+        flops = float(B) * P * h * (12 + 10)
         what = "deep distance sum_k w_k tanh((A f)_k + (C g)_k): loss, u, v, dA, dC, dw at B=1024 P=2048 d=768 h=128 bf16"
         extra_roofline = {"bound": "alu", "peak": 157.3, "unit": "TFLOP/s",
                           "peak_note": "published fp32 vector rate (packed fp32); plain fp32 FMAs, which is what this build "
                                        "issues, peak at 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 = 78.6, and exp2 / "
-                                       "reciprocal (2 of the 5-8 instructions per term) run at a quarter of that rate"}
+                                       "reciprocal (2 of the 7-8 instructions per term) run at a quarter of that rate"}
     else:
         xq, xp, r, params = synth.mlp_problem()
         xq, xp, r = xq.to(dev), xp.to(dev), r.to(dev)

@@ -902,28 +902,34 @@ static int run_step(const StepCall& c, hipStream_t s) {
 // pair, plain vector arithmetic (no contraction for the MFMAs to take).  The pair part works on a_i = A f_i and
 // c_j = C g_j (two skinny products), both scaled by 2 log2(e), so that with r = 1 / (1 + 2^(a + c)):
 //   tanh z = 1 - 2 r,   1 - tanh^2 z = 4 r (1 - r).
-// One kernel walks the pairs in three roles, each with an owner side whose rows a workgroup keeps in registers and a
+// One kernel walks the pairs in two roles, each with an owner side whose rows a workgroup keeps in registers and a
 // streamed side that passes through LDS 32 rows at a time:
-//   DD_STATS  owner = anchors: d_ij for every pair, online max / sum of 2^t per anchor, the positive's logit
-//   DD_DA     owner = anchors: d_ij again, the weight w_ij = dL/dd_ij (the section's Distance Gradient Cache, which
-//             exists for one pair at a time in a register), and with it sum_j w_ij t'_ijk (-> dL/da_i, hence u_i and
-//             dL/dA) and sum_j w_ij t_ijk (-> dL/dw)
-//   DD_DC     owner = targets: the same pairs walked the other way for sum_i w_ij t'_ijk (-> dL/dc_j, hence v_j, dL/dC);
-//             a second walk instead of a cross-workgroup sum: no atomics, fixed order.
+//   DD_DA     owner = anchors: d_ij for every pair and, in the same walk, the row's softmax statistics and the sums
+//             sum_j 2^(t_ij - m) t'_ijk and sum_j 2^(t_ij - m) t_ijk relative to a reference m that is raised (the
+//             sums scaled down) only when a logit exceeds it by more than a margin; a finish kernel merges the splits
+//             into lse_i, the loss, dL/da_i (hence u_i and dL/dA) and the rows whose column sums are dL/dw.  The weight
+//             w_ij = dL/dd_ij of a pair (the section's Distance Gradient Cache) is 2^(t_ij - lse_i) - [j = r_i]: it
+//             exists as the factor 2^(t_ij - m) for one pair at a time in a register, times 2^(m - lse_i) at the
+//             finish, where the positive's -1 is subtracted too (its r values are put aside by the walk)
+//   DD_DC     owner = targets: the same pairs walked the other way, with the final lse_i of the streamed anchors, for
+//             sum_i w_ij t'_ijk (-> dL/dc_j, hence v_j, dL/dC); a second walk instead of a cross-workgroup sum: no
+//             atomics, fixed order.
 // Thread (o, kq) of a workgroup owns owner row o (64 rows) and the quarter kq of the k range: the four threads of a
 // row add their partial distances with two cross-lane moves, everything else stays in the thread's registers.
 constexpr int DD_OWN = 64, DD_TS = 32;
-enum DdRole { DD_STATS = 0, DD_DA = 1, DD_DC = 2 };
+enum DdRole { DD_DA = 0, DD_DC = 1 };
+constexpr float kDdMargin = 16.f;   // DD_DA: the reference of a row is raised when a logit exceeds it by more than this
 struct DdArgs {
   const float* own; const float* str;   // [n_own][H], [n_str][H]: 2 log2(e) (A f) resp. (C g), owner and streamed side
   const unsigned short* wv;             // [H] bf16: w
   int n_own, n_str, n_oblk, stream_len; // owner blocks; streamed rows per split
   float alpha2, out_scale;              // alpha log2(e); alpha / B
-  const int32_t* pos_idx;               // [B] r_i (DD_STATS, DD_DA: of the owner rows)
-  float* part_m; float* part_l; int* part_idx; float* pos_t;   // DD_STATS out: per split and anchor
-  const float* lse2; const int32_t* pos_pad;                   // gradient roles: per anchor, padded (+inf, -1)
-  float* out_a;   // [split][n_own][H]: dL/da (DD_DA) or dL/dc (DD_DC) partial, final scale applied
-  float* out_e;   // DD_DA: [split][n_own][H]: (alpha/B) sum_j w_ij tanh_ijk partial (its column sums are dL/dw)
+  const int32_t* pos_idx;               // [B] r_i (DD_DA: of the owner rows)
+  float* part_m; float* part_l; float* pos_t;   // DD_DA out, per split and anchor: reference m, sum_j 2^(t_ij - m); the positive's logit
+  const float* lse2; const int32_t* pos_pad;                   // DD_DC in: per anchor, padded (+inf, -1)
+  float* out_a;   // [split][n_own][H]: DD_DA: sum_j 2^(t_ij - m) r (1 - r), unscaled; DD_DC: dL/dc partial, final scale applied
+  float* out_e;   // DD_DA: [split][n_own][H]: sum_j 2^(t_ij - m) r, unscaled
+  float* pos_r;   // DD_DA: [n_own][H]: r_{i r_i k} of the positive pair (its -1 term is subtracted by the finish kernel)
 };
 
 __device__ __forceinline__ float quad_sum(float x) {   // over the four lanes 4 i .. 4 i + 3
@@ -956,13 +962,12 @@ __global__ void __launch_bounds__(256, 2) deepdist_walk_kernel(DdArgs g) {
   for (int k = 0; k < HQ; k++) { wq[k] = bf2f(g.wv[kq * HQ + k]); w1 += wq[k]; }
   w1 = quad_sum(w1);   // sum_k w_k
 
-  int r_o = -1; float lse_o = INFINITY;
-  if (ROLE != DD_DC && row < g.n_own) r_o = g.pos_idx[row];
-  if (ROLE == DD_DA && row < g.n_own) lse_o = g.lse2[row];
+  int r_o = -1;
+  if (ROLE == DD_DA && row < g.n_own) r_o = g.pos_idx[row];
   float acc_a[HQ], acc_e[HQ];
 #pragma unroll
   for (int k = 0; k < HQ; k++) { acc_a[k] = 0.f; acc_e[k] = 0.f; }
-  float sw = 0.f, m = -INFINITY, l = 0.f, pos = 0.f;
+  float m = -INFINITY, l = 0.f, pos = 0.f;
   bool got = false;
 
   // tile u of the streamed rows: global -> registers -> LDS, one tile ahead
@@ -1008,46 +1013,109 @@ __global__ void __launch_bounds__(256, 2) deepdist_walk_kernel(DdArgs g) {
       }
       const float t = g.alpha2 * (w1 - 2.f * quad_sum(part));   // base-2 logit of the pair
       const int gs = t0 + s_;
-      if (ROLE == DD_STATS) {
-        if (gs == r_o) { pos = t; got = true; }
-        const float mn = fmaxf(m, t);
-        l = l * fast_exp2(m - mn) + fast_exp2(t - mn);
-        m = mn;
-      } else {
-        float wij;   // dL/dd_ij in units of alpha / B
-        if (ROLE == DD_DA) wij = fast_exp2(t - lse_o) - (gs == r_o ? 1.f : 0.f);
-        else wij = fast_exp2(t - st_lse[buf][s_]) - (st_pos[buf][s_] == row ? 1.f : 0.f);
+      if (ROLE == DD_DA) {
+        // statistics and gradient sums in one walk: sums relative to a reference m that is raised (and the sums scaled
+        // down with it) only when a logit exceeds it by more than the margin -- at the first pair, and rarely afterwards
+        if (gs == r_o) {
+          pos = t; got = true;
+          if (row < g.n_own) {
+#pragma unroll
+            for (int k = 0; k < HQ; k += 4)
+              *(f32x4*)(g.pos_r + (size_t)row * H + kq * HQ + k) = f32x4{rr[k], rr[k + 1], rr[k + 2], rr[k + 3]};
+          }
+        }
+        if (t > m + kDdMargin) {
+          const float f = fast_exp2(m - t);   // 2^-inf = 0 the first time
+#pragma unroll
+          for (int k = 0; k < HQ; k++) { acc_a[k] *= f; acc_e[k] *= f; }
+          l *= f;
+          m = t;
+        }
+        const float e = fast_exp2(t - m);
+        l += e;
 #pragma unroll
         for (int k = 0; k < HQ; k++) {
-          acc_a[k] = __builtin_fmaf(wij, __builtin_fmaf(-rr[k], rr[k], rr[k]), acc_a[k]);   // w_ij r (1 - r)
-          if (ROLE == DD_DA) acc_e[k] = __builtin_fmaf(wij, rr[k], acc_e[k]);
+          acc_a[k] = __builtin_fmaf(e, __builtin_fmaf(-rr[k], rr[k], rr[k]), acc_a[k]);
+          acc_e[k] = __builtin_fmaf(e, rr[k], acc_e[k]);
         }
-        if (ROLE == DD_DA) sw += wij;
+      } else {
+        const float wij = fast_exp2(t - st_lse[buf][s_]) - (st_pos[buf][s_] == row ? 1.f : 0.f);   // dL/dd_ij in units of alpha / B
+#pragma unroll
+        for (int k = 0; k < HQ; k++) acc_a[k] = __builtin_fmaf(wij, __builtin_fmaf(-rr[k], rr[k], rr[k]), acc_a[k]);   // w_ij r (1 - r)
       }
     }
     if (u + 1 < nt) stash(buf ^ 1);
     __syncthreads();
   }
   if (row >= g.n_own) return;
-  if (ROLE == DD_STATS) {
+  if (ROLE == DD_DA) {
     if (kq == 0) {
       const size_t oo = (size_t)split * g.n_own + row;
-      g.part_m[oo] = m; g.part_l[oo] = l; g.part_idx[oo] = 0;
+      g.part_m[oo] = m; g.part_l[oo] = l;
       if (got) g.pos_t[row] = pos;
     }
+    float* oa = g.out_a + ((size_t)split * g.n_own + row) * H + kq * HQ;
+    float* oe = g.out_e + ((size_t)split * g.n_own + row) * H + kq * HQ;
+#pragma unroll
+    for (int k = 0; k < HQ; k += 4) {
+      *(f32x4*)(oa + k) = f32x4{acc_a[k], acc_a[k + 1], acc_a[k + 2], acc_a[k + 3]};
+      *(f32x4*)(oe + k) = f32x4{acc_e[k], acc_e[k + 1], acc_e[k + 2], acc_e[k + 3]};
+    }
   } else {
-    // dL/da_ik = w_k (alpha/B) 4 sum_j w_ij r (1 - r);  (alpha/B) sum_j w_ij tanh = (alpha/B) (sum_j w_ij - 2 sum_j w_ij r)
+    // dL/dc_jk = w_k (alpha/B) 4 sum_i w_ij r (1 - r)
     float* oa = g.out_a + ((size_t)split * g.n_own + row) * H + kq * HQ;
 #pragma unroll
     for (int k = 0; k < HQ; k += 4)
       *(f32x4*)(oa + k) = f32x4{acc_a[k] * wq[k], acc_a[k + 1] * wq[k + 1], acc_a[k + 2] * wq[k + 2], acc_a[k + 3] * wq[k + 3]} * (4.f * g.out_scale);
-    if (ROLE == DD_DA) {
-      float* oe = g.out_e + ((size_t)split * g.n_own + row) * H + kq * HQ;
-#pragma unroll
-      for (int k = 0; k < HQ; k += 4)
-        *(f32x4*)(oe + k) = (f32x4{sw, sw, sw, sw} - 2.f * f32x4{acc_e[k], acc_e[k + 1], acc_e[k + 2], acc_e[k + 3]}) * g.out_scale;
-    }
   }
+}
+
+// After the DD_DA walk: merge of what its splits left per anchor (reference m_s, l_s = sum_j 2^(t_ij - m_s)) into
+// lse2_i and the row loss, and with the weights 2^(m_s - lse2_i) of the splits (index order)
+//   dL/da_ik   = (alpha/B) 4 w_k (sum_j p_ij r (1 - r) - r_pos (1 - r_pos))
+//   e_ik       = (alpha/B) sum_j w_ij tanh_ijk = -2 (alpha/B) (sum_j p_ij r - r_pos)       (sum_j w_ij = 0)
+// with r = r_ijk, r_pos = r_{i r_i k}, p_ij the softmax and w_ij = p_ij - [j = r_i].  One thread per (anchor, k).
+struct DdFinish {
+  const float* part_m; const float* part_l; const float* pos_t; const int32_t* pos_idx;
+  const float* part_a; const float* part_e; const float* pos_r; const unsigned short* wv;
+  int ns, B, P, b_pad;
+  float out_scale;
+  float* lse2; int32_t* pos_pad; float* rowloss; float* da; float* e;
+};
+template <int H>
+__global__ void __launch_bounds__(256) deepdist_finish_kernel(DdFinish f) {
+  constexpr int ROWS = 256 / H;
+  const int i = blockIdx.x * ROWS + threadIdx.x / H, k = threadIdx.x % H;
+  const bool live = i < f.B;
+  if (!live && i < f.b_pad && k == 0) { f.lse2[i] = INFINITY; f.pos_pad[i] = -1; }
+  // the row's split statistics, loaded once by its first ns threads (ns <= 64 <= H)
+  __shared__ float sm[ROWS][64], sl[ROWS][64];
+  const int rr = threadIdx.x / H;
+  if (live && k < f.ns) { sm[rr][k] = f.part_m[(size_t)k * f.B + i]; sl[rr][k] = f.part_l[(size_t)k * f.B + i]; }
+  __syncthreads();
+  if (!live) return;
+  float M = -INFINITY;
+  for (int s = 0; s < f.ns; s++) M = fmaxf(M, sm[rr][s]);
+  float L = 0.f;
+  for (int s = 0; s < f.ns; s++) L += sl[rr][s] * exp2f(sm[rr][s] - M);
+  const float l2 = M + log2f(L);
+  const int r = f.pos_idx[i];
+  const bool ok = (r >= 0 && r < f.P);
+  if (k == 0) {
+    f.lse2[i] = l2;
+    f.pos_pad[i] = r;
+    f.rowloss[i] = ok ? (l2 - f.pos_t[i]) * kLn2 : NAN;
+  }
+  float sa = 0.f, se = 0.f;
+#pragma unroll 4
+  for (int s = 0; s < f.ns; s++) {
+    const float w = exp2f(sm[rr][s] - l2);
+    sa += w * f.part_a[((size_t)s * f.B + i) * H + k];
+    se += w * f.part_e[((size_t)s * f.B + i) * H + k];
+  }
+  const float pr = ok ? f.pos_r[(size_t)i * H + k] : 0.f;
+  f.da[(size_t)i * H + k] = 4.f * f.out_scale * bf2f(f.wv[k]) * (sa - (pr - pr * pr));
+  f.e[(size_t)i * H + k] = -2.f * f.out_scale * (se - pr);
 }
 
 // column sums of x[rows][cols] over a slice of the rows: partial[slice][cols] (fixed order; cols a multiple of 32)
@@ -1072,7 +1140,7 @@ __global__ void __launch_bounds__(256) colsum_slices_kernel(const float* __restr
 struct DeepWs {
   LossPlan st;                 // the statistics part of a loss workspace (split statistics, lse2, row losses, error word)
   size_t off_stat, off_a, off_c, off_AT, off_CT, off_da_part, off_e_part, off_dc_part, off_da, off_dc, off_e, off_wpart,
-      off_gpart, total;
+      off_gpart, off_pos_r, total;
   int nsa, len_a, nsc, len_c;  // stream splits of the anchor-owner walks / of the target-owner walk
   int slices_b, rps_b, slices_p, rps_p;   // row slices of the two parameter-gradient products
 };
@@ -1107,6 +1175,7 @@ static DeepWs plan_deep(int B, int P, int d, int h) {
   w.off_dc_part = take((size_t)w.nsc * P * h * 4);
   w.off_da = take((size_t)B * h * 4); w.off_dc = take((size_t)P * h * 4); w.off_e = take((size_t)B * h * 4);
   w.off_wpart = take((size_t)64 * h * 4);
+  w.off_pos_r = take((size_t)B * h * 4);
   auto slices_of = [&](int rows, int& sl, int& rps) {
     const int tiles = (d / 128) * (h / WG_M);
     sl = (2 * num_cu() + tiles - 1) / tiles;
@@ -1356,31 +1425,39 @@ int gc_deepdist_loss_and_grads_bf16(const void* q, const void* p, const int32_t*
   DdArgs g{};
   g.wv = (const unsigned short*)w; g.alpha2 = alpha * kLog2e; g.out_scale = alpha / (float)B; g.pos_idx = pos_idx;
   g.part_m = (float*)(ws + pw.st.off_part_m); g.part_l = (float*)(ws + pw.st.off_part_l);
-  g.part_idx = (int*)(ws + pw.st.off_part_idx); g.pos_t = (float*)(ws + pw.st.off_pos);
+  g.pos_t = (float*)(ws + pw.st.off_pos);
   g.lse2 = (const float*)(ws + pw.st.off_lse2); g.pos_pad = (const int32_t*)(ws + pw.st.off_pos_pad);
-  // statistics of every anchor, then their merge (lse2, row losses) and the loss
+  // anchors own, targets streamed: statistics and the sums of dL/da and e in one walk (no statistics pass), then the
+  // merge of its splits (lse2, row losses, dL/da, e) and the loss
+  float* da = (float*)(ws + pw.off_da);
+  float* dc = (float*)(ws + pw.off_dc);
+  float* e = (float*)(ws + pw.off_e);
   g.own = a2; g.str = c2; g.n_own = B; g.n_str = P; g.n_oblk = obA; g.stream_len = pw.len_a;
-  deepdist_walk_kernel<128, DD_STATS><<<obA * pw.nsa, 256, 0, s>>>(g);
+  g.out_a = (float*)(ws + pw.off_da_part); g.out_e = (float*)(ws + pw.off_e_part); g.pos_r = (float*)(ws + pw.off_pos_r);
+  deepdist_walk_kernel<128, DD_DA><<<obA * pw.nsa, 256, 0, s>>>(g);
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  {
+    DdFinish f{};
+    f.part_m = g.part_m; f.part_l = g.part_l; f.pos_t = g.pos_t; f.pos_idx = pos_idx;
+    f.part_a = g.out_a; f.part_e = g.out_e; f.pos_r = g.pos_r; f.wv = g.wv;
+    f.ns = pw.nsa; f.B = B; f.P = P; f.b_pad = pw.st.b_pad; f.out_scale = g.out_scale;
+    f.lse2 = (float*)(ws + pw.st.off_lse2); f.pos_pad = (int32_t*)(ws + pw.st.off_pos_pad);
+    f.rowloss = (float*)(ws + pw.st.off_rowloss); f.da = da; f.e = e;
+    deepdist_finish_kernel<128><<<(pw.st.b_pad + 1) / 2, 256, 0, s>>>(f);
+    if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
+  }
   LossArgs la{};
   la.dt = GC_BF16; la.pos_idx = pos_idx; la.B = B; la.P = P; la.d = d; la.alpha = alpha; la.loss = loss; la.ws = ws; la.stream = s;
-  if (launch_stats_merge(la, pw.st) != hipSuccess) return GC_ERR_HIP;
-  // the two gradient walks
-  g.out_a = (float*)(ws + pw.off_da_part); g.out_e = (float*)(ws + pw.off_e_part);
-  deepdist_walk_kernel<128, DD_DA><<<obA * pw.nsa, 256, 0, s>>>(g);
+  if (launch_loss_sum(la, pw.st) != hipSuccess) return GC_ERR_HIP;
+  // targets own, anchors streamed (with their final lse2)
   g.own = c2; g.str = a2; g.n_own = P; g.n_str = B; g.n_oblk = obC; g.stream_len = pw.len_c;
   g.out_a = (float*)(ws + pw.off_dc_part); g.out_e = nullptr;
   deepdist_walk_kernel<128, DD_DC><<<obC * pw.nsc, 256, 0, s>>>(g);
   if (hipGetLastError() != hipSuccess) return GC_ERR_HIP;
-  float* da = (float*)(ws + pw.off_da);
-  float* dc = (float*)(ws + pw.off_dc);
-  float* e = (float*)(ws + pw.off_e);
   auto sum_parts = [&](float* out, size_t off_part, int parts, size_t n) {
     const float* srcs[1] = {(const float*)(ws + off_part)}; int counts[1] = {parts}; size_t strides[1] = {n};
     return launch_partial_reduce(out, srcs, counts, strides, 1, n, s);
   };
-  if (sum_parts(da, pw.off_da_part, pw.nsa, (size_t)B * h) != hipSuccess) return GC_ERR_HIP;
-  if (sum_parts(e, pw.off_e_part, pw.nsa, (size_t)B * h) != hipSuccess) return GC_ERR_HIP;
   if (sum_parts(dc, pw.off_dc_part, pw.nsc, (size_t)P * h) != hipSuccess) return GC_ERR_HIP;
   {  // dL/dw_k = sum_i e_ik: row slices, then their fixed-order sum
     int sl = (B + 255) / 256;

@@ -33,7 +33,9 @@ def oracle(q, p, r, om, scale=1.0, temp=1.0):
 
 
 @pytest.mark.parametrize("B,P,d,scale,temp", [(96, 200, 128, 1.0, 1.0), (130, 257, 256, 2.0, 0.5), (300, 600, 768, 1.0, 1.0),
-                                              (1, 40, 384, 1.0, 1.0), (700, 333, 512, 1.0, 0.25), (64, 1, 128, 1.0, 1.0)])
+                                              (1, 40, 384, 1.0, 1.0), (700, 333, 512, 1.0, 0.25), (64, 1, 128, 1.0, 1.0),
+                                              # logits spread over hundreds: the walk raises its reference many times
+                                              (200, 500, 256, 40.0, 0.5), (129, 4100, 128, 16.0, 0.25)])
 def test_deep_distance_matches_the_oracle(B, P, d, scale, temp):
     q, p, _ = synth.dpr_batch(B, P, d, seed=8000 + B, positive_mix=0.3)
     r = torch.from_numpy(np.random.default_rng(B + P).integers(0, P, size=B).astype(np.int32))   # shared positives
