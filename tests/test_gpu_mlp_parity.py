@@ -124,6 +124,22 @@ def test_chunking_does_not_change_the_update():
         assert torch.equal(b["grads"][k], c["grads"][k]), k      # run-to-run reproducible
 
 
+def test_step_with_one_side_on_the_tiled_forward():
+    # B below and P above the row count from which the graph-less forward runs as tiled GEMMs (split contraction in the
+    # second layer): both forward paths in one step, ragged last sub-batches, and the same update for another chunking
+    xq, xp, r, params = small_problem(B=100, P=300, din=192, dh=384, dout=128, seed=11)
+    dp = dev_params(params)
+    out = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 32, 64, dp, 1.0, 0.05, keep=True)
+    torch.cuda.synchronize()
+    stagewise("mixed step 32/64", out, xq, xp, r, params, 32, 64, 1.0, 0.05)
+    other = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 24, 40, dp, 1.0, 0.05, keep=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out["q"], other["q"]) and torch.equal(out["p"], other["p"])   # Step 1 does not depend on the chunking
+    assert out["loss"].item() == other["loss"].item()
+    for k in ("W1", "b1", "W2", "b2"):
+        assert relerr(to_np(other["grads"][k]), to_np(out["grads"][k])) <= 1e-5, k
+
+
 def test_step_with_a_large_batch_takes_the_online_walk():
     """B = P = 4096 with a small encoder (64-128-768): 2^24 scores, so Step 2 runs without a statistics pass; the
     parameter gradients still equal the full-batch ones."""
