@@ -279,7 +279,11 @@ int gc_chunk_surrogate_backward_bf16(const void* x_chunk, int rows, const gc_mlp
  *   loss [1] float (overwritten); grads accumulated (+=): zero them before the call
  *   q_rep [B,dout], p_rep [P,dout] bf16 and dq [B,dout], dp [P,dout] float:
  *     optional outputs (NULL = kept in the workspace only)
- * workspace: gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, w).
+ * workspace: gc_step_mlp_workspace_bytes(B, P, chunk_q, chunk_p, w).  It holds the
+ *   representations and their gradient cache ((B + P) * dout numbers each), the
+ *   loss workspace, three sets of one sub-batch's activations for Step 3, and
+ *   the transient activations of Step 1, whose graph-less forward takes up to
+ *   2048 rows (whole sub-batches) per launch: rows * dh floats, three times.
  * Everything is enqueued on `stream`; the order in which sub-batches are added
  * to the gradients is the index order, so the result is reproducible bit for
  * bit.  A call that repeats with exactly the same arguments (same buffers) is
