@@ -126,6 +126,14 @@ hipError_t launch_partial_reduce(float* out, const float* const* srcs, const int
                                  int nsrc, size_t n, hipStream_t stream, const LossArgs* loss_of = nullptr,
                                  const LossPlan* pl = nullptr, bool out_bf16 = false, const PosFix* fix = nullptr);
 
+// Workgroups are handed to the 8 XCDs round-robin by their id, and each XCD has its own L2.  This
+// turns the hardware id into a task id such that each XCD works on one contiguous range of tasks
+// (tasks that stream the same rows are numbered consecutively by the launchers).
+__device__ __forceinline__ int xcd_task_id() {
+  const int id = blockIdx.x, n = gridDim.x;
+  return (n % 8 == 0) ? (id % 8) * (n / 8) + id / 8 : id;
+}
+
 // A kernel that uses more than 64 KB of dynamic LDS has to be opted in (hipFuncSetAttribute): once per kernel and
 // device, remembered in `done` (a function-local array of the launcher, one per kernel instantiation).
 inline hipError_t ensure_dyn_lds(const void* fn, int bytes, bool (&done)[64]) {

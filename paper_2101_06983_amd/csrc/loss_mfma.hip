@@ -20,14 +20,6 @@ namespace gc {
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-// Workgroups are handed to the 8 XCDs round-robin by their id, and each XCD has its own L2.  This
-// turns the hardware id into a task id such that each XCD works on one contiguous range of tasks
-// (tasks that stream the same rows are numbered consecutively by the launchers).
-__device__ __forceinline__ int xcd_task_id() {
-  const int id = blockIdx.x, n = gridDim.x;
-  return (n % 8 == 0) ? (id % 8) * (n / 8) + id / 8 : id;
-}
-
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

@@ -368,7 +368,8 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, ln = lane & 31;
   const int nbn = g.N / GM_T;
   const int tiles = ((g.M + BM - 1) / BM) * nbn;
-  const int tile = blockIdx.x % tiles, split = blockIdx.x / tiles;   // split > 0 only for GO_F32 with k_split > 1
+  const int bid = xcd_task_id();   // consecutive tiles (they share rows of A) on one XCD, behind one L2
+  const int tile = bid % tiles, split = bid / tiles;   // split > 0 only for GO_F32 with k_split > 1
   const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * GM_T;
   const int klen = g.K / (g.k_split > 1 ? g.k_split : 1), kbeg = split * klen;
   const int wm = wave >> 1, wn = wave & 1;
