@@ -2,23 +2,26 @@
 // Step 1, the per-sub-batch re-encode and surrogate backward of Step 3 (the inner sums of Eq. 8 / 9)
 // and the one-GPU driver that runs Steps 1-3.
 //
-// A sub-batch has few rows (32 at the paper's setting), so every contraction is skinny and is bound by
-// how fast the weights stream in, not by the MFMAs.  Two kernels:
+// A sub-batch has few rows (32 at the paper's setting), so every contraction of Step 3 is skinny and is bound by
+// how fast the weights and the gradient accumulators move, not by the MFMAs.  Three kernels:
 //
 // mlp_skinny_kernel: C[32 x 32 per workgroup] = A[rows x K] * Bt[N x K]^T, both operands with k contiguous, so
 //   every MFMA fragment is a plain 16-byte global load and nothing is staged through LDS.  The four waves of a
-//   workgroup split K (64-wide chunks, round-robin), keep four chunks of loads in flight each, and sum their
+//   workgroup split K (64-wide chunks, round-robin), keep two to four chunks of loads in flight each, and sum their
 //   partial tiles through LDS in a fixed order.  Used for
 //     H  = X  W1  (+b1, GELU)              Bt = W1^T [dh][din]   (transposed copy, made once per call)
 //     Y  = Act W2 (+b2)                    Bt = W2^T [dout][dh]  (transposed copy)      A = Act, fp32
-//     dA = U  W2^T, dH = dA * GELU'(H)     Bt = W2 [dh][dout] as stored                 A = U, fp32; column sums -> db1
+//     dA = U  W2^T, dH = dA * GELU'(H)     Bt = W2 [dh][dout] as stored                 A = U, fp32
 // mlp_wgrad_kernel: the weight-gradient contractions, whose k index is the row of the sub-batch (the slow index
-//   of both operands in memory): 32 x 128 tiles, operands through LDS and transposing ds_read_b64_tr_b16 loads,
-//   fp32 accumulators in HBM updated in place (+=)
+//   of both operands in memory): 64 x 128 tiles, operands through LDS (loaded a 32-row chunk ahead) and transposing
+//   ds_read_b64_tr_b16 loads, fp32 accumulators in HBM updated in place (+=)
 //     dW2 += Act^T U      A = Act (fp32) [rows][dh]    B = U (fp32) [rows][dout]   db2 += column sums of U
-//     dW1 += X^T dH       A = X [rows][din]            B = dH (fp32) [rows][dh]
-// An fp32 operand (the cached gradient rows U, dH, and the activations kept for Step 3) is fed to the bf16 MFMA as hi + lo, two
-// bf16 numbers per value and two MFMAs per step, so that it keeps ~16 mantissa bits: with only
+//     dW1 += X^T dH       A = X [rows][din]            B = dH (fp32) [rows][dh]    db1 += column sums of dH
+// gemm_nt_kernel: the same product as the skinny kernel for MANY rows at once (the graph-less forward of Step 1 over
+//   up to 2048 rows, the batch-wide projections of the distance functions): 64 x 128 or 128 x 128 tiles, both
+//   operands through LDS, optionally with the contraction cut into ranges (split-K).
+// An fp32 operand (the cached gradient rows U, dH, and the activations kept for Step 3) is fed to the bf16 MFMA as
+// hi + lo, two bf16 numbers per value and two MFMAs per step, so that it keeps ~16 mantissa bits: with only
 // rows <= 32 terms per sum a single bf16 rounding (2^-9) would sit right at the error budget.
 #include "gc_common.h"
 #include <mutex>
