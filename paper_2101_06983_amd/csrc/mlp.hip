@@ -355,6 +355,8 @@ struct GemmArgs {
   const unsigned short* bias;         // GO_GELU_F32 / GO_BIAS_BF16: [N] bf16
   int k_split;                        // GO_F32 only: > 1 cuts K into that many equal ranges (each a multiple of 64); range s
   size_t split_stride;                //   writes its partial product to C + s * split_stride (elements)
+  // two row segments (anchors, then targets, in one launch): rows from M1 on are rows 0.. of A2 / C2 when those are set
+  int M1; const void* A2; void* C2;
 };
 // what a tile writes: the product (times mul) as fp32 or bf16, GELU(product + bias) as fp32, product + bias as bf16
 enum GemmOut { GO_F32 = 0, GO_BF16 = 1, GO_GELU_F32 = 2, GO_BIAS_BF16 = 3 };
@@ -386,9 +388,10 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
       const int q = tid + 256 * i, row = q >> 3, kc = q & 7;
       if (i < NA) {
         const int am = min(m0 + row, g.M - 1);   // rows past the end repeat the last one; their results are not stored
-        const size_t ia = (size_t)am * g.lda + kbeg + k0 + 8 * kc;
+        const bool second = g.A2 && am >= g.M1;
+        const size_t ia = (size_t)(second ? am - g.M1 : am) * g.lda + kbeg + k0 + 8 * kc;
 #pragma unroll
-        for (int v = 0; v < AV; v++) r.a[i][v] = *(const u32x4*)((const char*)g.A + ia * (A_F32 ? 4 : 2) + 16 * v);
+        for (int v = 0; v < AV; v++) r.a[i][v] = *(const u32x4*)((const char*)(second ? g.A2 : g.A) + ia * (A_F32 ? 4 : 2) + 16 * v);
       }
       r.b[i] = *(const u32x4*)(g.Bt + (size_t)(n0 + row) * g.ldb + kbeg + k0 + 8 * kc);
     }
@@ -479,11 +482,13 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g) {
         const int m = m0 + wm * 32 * MT + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
         const int n = n0 + wn * 64 + nt * 32 + ln;
         if (m < g.M) {
-          const size_t at = (size_t)m * g.ldc + n;
-          if (OUT == GO_F32) ((float*)g.C)[(size_t)split * g.split_stride + at] = acc[mt][nt][r] * mul;
-          else if (OUT == GO_BF16) ((unsigned short*)g.C)[at] = f2bf(acc[mt][nt][r] * mul);
-          else if (OUT == GO_GELU_F32) ((float*)g.C)[at] = gelu_f(acc[mt][nt][r] + bf2f(g.bias[n]));
-          else ((unsigned short*)g.C)[at] = f2bf(acc[mt][nt][r] + bf2f(g.bias[n]));
+          const bool second = g.C2 && m >= g.M1;
+          void* cb = second ? g.C2 : g.C;
+          const size_t at = (size_t)(second ? m - g.M1 : m) * g.ldc + n;
+          if (OUT == GO_F32) ((float*)cb)[(size_t)split * g.split_stride + at] = acc[mt][nt][r] * mul;
+          else if (OUT == GO_BF16) ((unsigned short*)cb)[at] = f2bf(acc[mt][nt][r] * mul);
+          else if (OUT == GO_GELU_F32) ((float*)cb)[at] = gelu_f(acc[mt][nt][r] + bf2f(g.bias[n]));
+          else ((unsigned short*)cb)[at] = f2bf(acc[mt][nt][r] + bf2f(g.bias[n]));
         }
       }
 }
@@ -509,9 +514,11 @@ static hipError_t launch_gemm_nt(const GemmArgs& g, hipStream_t s) {
 }
 
 // out[m][n] = bf16(sum over the k_split partial products, in index order, + bias[n]); 4 elements per thread
+// (rows from M1 on go to rows 0.. of out2 when that is set)
 __global__ void __launch_bounds__(256) splitk_bias_bf16_kernel(const float* __restrict__ part, int k_split, size_t stride,
                                                               const unsigned short* __restrict__ bias, int N,
-                                                              unsigned short* __restrict__ out, size_t n4) {
+                                                              unsigned short* __restrict__ out, size_t n4, int M1,
+                                                              unsigned short* __restrict__ out2) {
   const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= n4) return;
   f32x4 acc = ((const f32x4*)part)[e];
@@ -521,7 +528,9 @@ __global__ void __launch_bounds__(256) splitk_bias_bf16_kernel(const float* __re
   s16x4 o;
 #pragma unroll
   for (int k = 0; k < 4; k++) o[k] = (short)f2bf(acc[k] + bf2f((unsigned short)b[k]));
-  ((s16x4*)out)[e] = o;
+  const size_t first4 = (size_t)M1 * N / 4;
+  if (out2 && e >= first4) ((s16x4*)out2)[e - first4] = o;
+  else ((s16x4*)out)[e] = o;
 }
 
 // One iteration of Step 3's software pipeline in one launch: the weight gradients of sub-batch c-2, dH and db1 of
@@ -649,18 +658,21 @@ constexpr int kStep1Rows = 2048;  // rows per launch of Step 1 (see group_rows)
 // forward of one sub-batch (after mlp_prepare); keepH: also write the fp32 pre-activations (Step 3)
 // tiled: the graph-less forward of many rows; the caller decides it per input (not per launch), so that a row's bits do
 // not depend on how the rows are cut into launches
+// x2 / rows2 / y2 (tiled only): a second input whose rows follow those of x in the same launches (the targets behind the
+// anchors: together they fill the GPU better than one after the other)
 static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, const MlpWs& ws, bool keepH, void* y,
-                              hipStream_t s, bool tiled = false) {
+                              hipStream_t s, bool tiled = false, const void* x2 = nullptr, int rows2 = 0, void* y2 = nullptr) {
   if (tiled && !keepH && y) {
+    const int all = rows + rows2;
     // many rows and nothing kept for a backward (Step 1): both layers as tiled GEMMs over all the rows at once, which
     // read the weights once per 64 or 128 rows instead of once per 32
     GemmArgs g1{};
-    g1.A = x; g1.lda = w->din; g1.Bt = ws.W1T; g1.ldb = w->din; g1.M = rows; g1.N = w->dh; g1.K = w->din;
-    g1.C = ws.ActF; g1.ldc = w->dh; g1.bias = (const unsigned short*)w->b1;
+    g1.A = x; g1.lda = w->din; g1.Bt = ws.W1T; g1.ldb = w->din; g1.M = all; g1.N = w->dh; g1.K = w->din;
+    g1.C = ws.ActF; g1.ldc = w->dh; g1.bias = (const unsigned short*)w->b1; g1.M1 = rows; g1.A2 = x2;
     if (hipError_t e = launch_gemm_nt<false, GO_GELU_F32>(g1, s); e != hipSuccess) return e;
     GemmArgs g2{};
-    g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = rows; g2.N = w->dout; g2.K = w->dh;
-    g2.C = y; g2.ldc = w->dout; g2.bias = (const unsigned short*)w->b2;
+    g2.A = ws.ActF; g2.lda = w->dh; g2.Bt = ws.W2T; g2.ldb = w->dh; g2.M = all; g2.N = w->dout; g2.K = w->dh;
+    g2.C = y; g2.ldc = w->dout; g2.bias = (const unsigned short*)w->b2; g2.M1 = rows; g2.C2 = y2;
     // The second layer is narrow (dout columns) and long (dh): few tiles, each a long chain of k-steps.  While the tiles
     // do not fill the GPU, the contraction is cut into up to four ranges whose fp32 partial products go to the dH
     // buffer (unused by a graph-less forward; rows x dh floats hold dh / dout partial outputs) and are summed, in
@@ -669,11 +681,11 @@ static hipError_t mlp_forward(const void* x, int rows, const gc_mlp_params* w, c
     const int tiles64 = ((kStep1Rows + 63) / 64) * (w->dout / GM_T);   // tiles of a full Step-1 launch
     while (ks < 4 && tiles64 * ks < 2 * num_cu() && (ks * 2) * w->dout <= w->dh && w->dh % (GM_BK * ks * 2) == 0) ks *= 2;
     if (ks == 1) return launch_gemm_nt<true, GO_BIAS_BF16>(g2, s);
-    g2.C = ws.dH; g2.bias = nullptr; g2.k_split = ks; g2.split_stride = (size_t)rows * w->dout;
+    g2.C = ws.dH; g2.C2 = nullptr; g2.bias = nullptr; g2.k_split = ks; g2.split_stride = (size_t)all * w->dout;
     if (hipError_t e = launch_gemm_nt<true, GO_F32>(g2, s); e != hipSuccess) return e;
-    const size_t n4 = (size_t)rows * w->dout / 4;
+    const size_t n4 = (size_t)all * w->dout / 4;
     splitk_bias_bf16_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, s>>>(ws.dH, ks, g2.split_stride, (const unsigned short*)w->b2,
-                                                                      w->dout, (unsigned short*)y, n4);
+                                                                      w->dout, (unsigned short*)y, n4, rows, (unsigned short*)y2);
     return hipGetLastError();
   }
   mlp_skinny_kernel<false, EP_GELU><<<dim3(w->dh / 32, (rows + 31) / 32), 256, 0, s>>>(layer1_args(x, rows, w, ws, keepH));
@@ -735,6 +747,15 @@ static int group_rows(int chunk, int n) {
   return (int)(g < n ? g : n);
 }
 
+// both inputs in the same launches of Step 1: when each side takes the tiled forward and together they fit a launch
+static bool step1_joint(int B, int P) { return B >= kGemmRows && P >= kGemmRows && (long long)B + P <= kStep1Rows; }
+// rows of the activation buffers that Step 1 (and lane 0 of Step 3) needs
+static int step1_ws_rows(int B, int P, int chunk_q, int chunk_p) {
+  const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
+  const int r = group_rows(cmax, B > P ? B : P);
+  return step1_joint(B, P) && B + P > r ? B + P : r;
+}
+
 struct StepWs {
   size_t off_q, off_p, off_dq, off_dp, off_loss, off_mlp, off_act, total;
   size_t loss_bytes, mlp_bytes, act_bytes;
@@ -759,7 +780,7 @@ static StepWs plan_step(int B, int P, int chunk_q, int chunk_p, const gc_mlp_par
   s.loss_bytes = make_loss_plan(B, P, w->dout, GC_BF16, false).total;
   s.off_loss = take(s.loss_bytes);
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
-  s.mlp_bytes = carve_mlp_ws(nullptr, group_rows(cmax, B > P ? B : P), w).total;
+  s.mlp_bytes = carve_mlp_ws(nullptr, step1_ws_rows(B, P, chunk_q, chunk_p), w).total;
   s.off_mlp = take(s.mlp_bytes);
   const int g3 = effective_group(group, chunk_q, chunk_p);
   s.act_bytes = 3 * up256((size_t)cmax * g3 * w->dh * 4);  // H, Act, dH of one more lane
@@ -798,7 +819,7 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
   float* dP = dp ? dp : (float*)(base + sw.off_dp);
   const int cmax = chunk_q > chunk_p ? chunk_q : chunk_p;
   MlpWs lane[kLanes];  // buffer sets (set 0 also serves Step 1); all share the transposed weights
-  lane[0] = carve_mlp_ws(base + sw.off_mlp, group_rows(cmax, B > P ? B : P), w);
+  lane[0] = carve_mlp_ws(base + sw.off_mlp, step1_ws_rows(B, P, chunk_q, chunk_p), w);
   for (int l = 1; l < kLanes; l++) {
     lane[l] = lane[0];
     char* ab = base + sw.off_act + (size_t)(l - 1) * sw.act_bytes;
@@ -819,15 +840,24 @@ static int enqueue_step(const StepCall& c, hipStream_t s) {
   for (int a = 0; a < P; a += chunk_p * g3)
     subs.push_back({(const unsigned short*)x_p + (size_t)a * w->din, P - a < chunk_p * g3 ? P - a : chunk_p * g3, Pm + (size_t)a * w->dout, dP + (size_t)a * w->dout, chunk_p});
   const int nsub = (int)subs.size();
-  // Step 1: graph-less forward, group_rows rows per launch, representations kept
-  const int gq = group_rows(chunk_q, B), gp = group_rows(chunk_p, P);
-  for (int a = 0; a < B; a += gq) {
-    const int rows = B - a < gq ? B - a : gq;
-    if (!ok(mlp_forward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, lane[0], false, Q + (size_t)a * w->dout, s, B >= kGemmRows))) return GC_ERR_HIP;
-  }
-  for (int a = 0; a < P; a += gp) {
-    const int rows = P - a < gp ? P - a : gp;
-    if (!ok(mlp_forward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, lane[0], false, Pm + (size_t)a * w->dout, s, P >= kGemmRows))) return GC_ERR_HIP;
+  // Step 1: graph-less forward, representations kept: both inputs through the same launches where they fit one
+  // (step1_joint), else group_rows rows of one input per launch
+  if (step1_joint(B, P)) {
+    if (!ok(mlp_forward(x_q, B, w, lane[0], false, Q, s, true, x_p, P, Pm))) return GC_ERR_HIP;
+  } else {
+    const int gq = group_rows(chunk_q, B), gp = group_rows(chunk_p, P);
+    for (int a = 0; a < B; a += gq) {
+      const int rows = B - a < gq ? B - a : gq;
+      if (!ok(mlp_forward((const unsigned short*)x_q + (size_t)a * w->din, rows, w, lane[0], false, Q + (size_t)a * w->dout, s,
+                          B >= kGemmRows)))
+        return GC_ERR_HIP;
+    }
+    for (int a = 0; a < P; a += gp) {
+      const int rows = P - a < gp ? P - a : gp;
+      if (!ok(mlp_forward((const unsigned short*)x_p + (size_t)a * w->din, rows, w, lane[0], false, Pm + (size_t)a * w->dout, s,
+                          P >= kGemmRows)))
+        return GC_ERR_HIP;
+    }
   }
   // Step 2: loss and the representation gradient cache
   int rc = gc_loss_and_rep_grad_ex(GC_BF16, Q, Pm, pos_idx, B, P, w->dout, scale, temp, 0, loss, dQ, dP, nullptr, nullptr,

@@ -124,14 +124,16 @@ def test_chunking_does_not_change_the_update():
         assert torch.equal(b["grads"][k], c["grads"][k]), k      # run-to-run reproducible
 
 
-def test_step_with_one_side_on_the_tiled_forward():
-    # B below and P above the row count from which the graph-less forward runs as tiled GEMMs (split contraction in the
-    # second layer): both forward paths in one step, ragged last sub-batches, and the same update for another chunking
-    xq, xp, r, params = small_problem(B=100, P=300, din=192, dh=384, dout=128, seed=11)
+@pytest.mark.parametrize("B,P", [(100, 300), (130, 200)])
+def test_step_with_the_tiled_forward(B, P):
+    # (100, 300): B below and P above the row count from which the graph-less forward runs as tiled GEMMs (split
+    # contraction in the second layer): both forward paths in one step.  (130, 200): both sides tiled and in the same
+    # launches, a tile straddling the two inputs.  Ragged last sub-batches, and the same update for another chunking.
+    xq, xp, r, params = small_problem(B=B, P=P, din=192, dh=384, dout=128, seed=11)
     dp = dev_params(params)
     out = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 32, 64, dp, 1.0, 0.05, keep=True)
     torch.cuda.synchronize()
-    stagewise("mixed step 32/64", out, xq, xp, r, params, 32, 64, 1.0, 0.05)
+    stagewise("tiled step %d/%d 32/64" % (B, P), out, xq, xp, r, params, 32, 64, 1.0, 0.05)
     other = gc.gc_step_mlp_bf16(xq.to(DEV), xp.to(DEV), r.to(DEV), 24, 40, dp, 1.0, 0.05, keep=True)
     torch.cuda.synchronize()
     assert torch.equal(out["q"], other["q"]) and torch.equal(out["p"], other["p"])   # Step 1 does not depend on the chunking
