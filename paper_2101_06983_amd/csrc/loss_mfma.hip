@@ -383,7 +383,10 @@ struct GradCfg {
   static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
 
-__device__ __forceinline__ int swz3(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+// (Measured with the bank-conflict counter on the two read patterns, all 4096 linear maps of the row bits: this one
+// and 767 others are free of conflicts for both; the first choice, bits 2 and 3 of the row into bits 0 and 1, left
+// the 16-byte fragment reads of phase 1 with a two-way conflict, 21 % of the walks' LDS cycles.)
+__device__ __forceinline__ int swz3(int row) { return (((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1); }
 
 struct GradArgs {
   const unsigned short* Q;
@@ -1013,7 +1016,12 @@ constexpr int G1_STAT = 256;                      // a stage starts with lse2[32
 constexpr int G1_STAGE = G1_STAT + G1_T * 256;    // bytes
 constexpr int G1_SMEM = G1_STAGES * G1_STAGE;
 // chunk c (16 bytes) of tile row r is stored at chunk position c ^ swz128(r): 8 consecutive rows of a
-// fragment read, and the 4 rows x 2 chunks of a transposing read, fall into different 16-byte bank groups
+// fragment read, and the 4 rows x 2 chunks of a transposing read, fall into different 16-byte bank groups.
+// (The bank-conflict counter still shows a conflict on every second LDS cycle of these kernels.  4-bit maps that remove
+// them all -- e.g. ((row & 3) << 2) | ((row >> 2) & 3): the low row bits pick the 64-byte quarter, the next two the
+// chunk inside it -- were measured on the kernels themselves: LDS cycles halved, waits for LDS a tenth, and the gradient
+// kernel 5 % SLOWER, 267 against 250 us, with every such map tried; the loop is paced by its barrier and the waits for
+// the tile loads, not by LDS, so the map that times best stays.)
 __device__ __forceinline__ int swz128(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
 // the first `LANES` lanes of the wave load 16 bytes each to lds_base + lane * 16 (EXEC narrowed inside)

@@ -73,7 +73,10 @@ struct WgradArgs {
 
 // a workgroup's tile of C is WG_M x 128 (two 32-row MFMA tiles that share the B operand in LDS)
 constexpr int WG_M = 64;
-constexpr int WG_KCH = 32, WG_A_LD = WG_M + 8, WG_B_LD = 128 + 8;  // LDS tiles (bf16): [k rows][width + 8], hi then lo part
+// LDS tiles (bf16): [k rows][width + 32], hi then lo part.  Rows are padded by 64 bytes (row stride = 64 mod 128): the
+// transposing reads (four consecutive k rows per 16 lanes, again four rows further on) then show no bank conflicts
+// (SQ_LDS_BANK_CONFLICT 0; with pads of 16, 32, 48 or 80 bytes a quarter to a half of the LDS cycles were conflicts)
+constexpr int WG_KCH = 32, WG_A_LD = WG_M + 32, WG_B_LD = 128 + 32;
 
 // raw 8 consecutive elements (one 16-byte load, two for fp32), and their conversion to packed bf16 hi (+ lo) later:
 // between the two a kernel can do other work while the load is in flight
@@ -1021,7 +1024,8 @@ __global__ void __launch_bounds__(256, 2) deepdist_walk_kernel(DdArgs g) {
 #pragma unroll
     for (int v = 0; v < LD4; v++) {
       const int e4 = tid + 256 * v, rr = e4 / (H / 4), c4 = e4 % (H / 4);
-      *(f32x4*)&tile[buf][rr][4 * c4] = pre[v];
+      // 16-byte piece j of quarter kq sits at piece 4 j + kq: the four threads of a row then read 64 contiguous bytes
+      *(f32x4*)&tile[buf][rr][4 * ((c4 % (HQ / 4)) * 4 + c4 / (HQ / 4))] = pre[v];
     }
     if (ROLE == DD_DC && tid < DD_TS) { st_lse[buf][tid] = pre_lse; st_pos[buf][tid] = pre_pos; }
   };
@@ -1033,11 +1037,11 @@ __global__ void __launch_bounds__(256, 2) deepdist_walk_kernel(DdArgs g) {
     if (u + 1 < nt) fetch(u + 1);
     const int t0 = sbeg + u * DD_TS, rows = min(DD_TS, send - t0);
     for (int s_ = 0; s_ < rows; s_++) {
-      const float* cs = &tile[buf][s_][kq * HQ];
+      const float* cs = &tile[buf][s_][4 * kq];
       float rr[HQ], part = 0.f;
 #pragma unroll
       for (int k = 0; k < HQ; k += 4) {
-        const f32x4 c4 = *(const f32x4*)(cs + k);
+        const f32x4 c4 = *(const f32x4*)(cs + 4 * k);
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           const float r = __builtin_amdgcn_rcpf(1.f + fast_exp2(ao[k + e] + c4[e]));   // 1 / (1 + e^(2 z))
