@@ -1019,9 +1019,10 @@ constexpr int G1_SMEM = G1_STAGES * G1_STAGE;
 // fragment read, and the 4 rows x 2 chunks of a transposing read, fall into different 16-byte bank groups.
 // (The bank-conflict counter still shows a conflict on every second LDS cycle of these kernels.  4-bit maps that remove
 // them all -- e.g. ((row & 3) << 2) | ((row >> 2) & 3): the low row bits pick the 64-byte quarter, the next two the
-// chunk inside it -- were measured on the kernels themselves: LDS cycles halved, waits for LDS a tenth, and the gradient
-// kernel 5 % SLOWER, 267 against 250 us, with every such map tried; the loop is paced by its barrier and the waits for
-// the tile loads, not by LDS, so the map that times best stays.)
+// chunk inside it -- were measured on the kernels themselves: LDS cycles halved, waits for LDS a tenth, the time of the
+// gradient kernel equal within 1 %.  With a 3-bit map fragment k + 4 of a row sits a fixed 128 bytes behind fragment k,
+// an immediate offset; a 4-bit map needs a second set of address registers, which this kernel, at 512 of 512, does not
+// have: it spills again.  The loop is paced by its barrier and the waits for the tile loads, not by LDS.)
 __device__ __forceinline__ int swz128(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
 // the first `LANES` lanes of the wave load 16 bytes each to lds_base + lane * 16 (EXEC narrowed inside)
@@ -1167,11 +1168,13 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
     }
     bf16x8 pfr[8];
     bf16x8 afr[4][2];
-#pragma unroll
-    for (int k = 0; k < 8; k++) {   // round 2 k needs pfr[k] and afr[k / 2][k % 2]
+    // round 2 k needs pfr[k] and afr[k / 2][k % 2]: the first four pairs are read here, pair k + 4 behind round 2 k + 1,
+    // into the registers that pair k has just left (all eight at once cost 32 registers that the loop does not have)
+    auto load_pair = [&](auto k_tag) __attribute__((always_inline)) {
+      constexpr int k = decltype(k_tag)::value;
       if (p1) pfr[k] = *(const bf16x8*)(st_p1 + G1_STAT + ln * 256 + (((2 * k + h) ^ (int)sw_ln) * 16));
       if (p2) {
-        const int mt = k / 2, kk = k % 2;
+        constexpr int mt = k / 2, kk = k % 2;
         s16x4 q[2];
 #pragma unroll
         for (int e = 0; e < 2; e++) {
@@ -1182,7 +1185,8 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
         s16x8 t = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
         afr[mt][kk] = __builtin_bit_cast(bf16x8, t);
       }
-    }
+    };
+    static_for<4>(load_pair);
     // 16 rounds: one phase-1 MFMA pair position, one phase-2 MFMA, the exp2 of two scores
     static_for<16>([&](auto i_tag) __attribute__((always_inline)) {
       constexpr int i = decltype(i_tag)::value;
@@ -1219,6 +1223,7 @@ __device__ __forceinline__ void grad128_body(const GradArgs& ga, int oblk, int s
           sacc[PT ^ 1][n][i] = e;
         }
       }
+      if constexpr (i % 2 == 1 && i / 2 + 4 < 8) load_pair(std::integral_constant<int, i / 2 + 4>{});
       if constexpr (STEADY) __builtin_amdgcn_sched_barrier(0);  // the rounds stay in order
     });
     if (sm) {
